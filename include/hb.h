@@ -1,0 +1,179 @@
+/*
+ * hb.h - C ABI of the tree-verification step of speculative decoding on MI355X (gfx950).
+ *
+ * The step (paper, Section 1): a draft model proposes several tokens, here arranged as a token
+ * tree, and the target model validates all of them in one batched pass.  Because the target
+ * decides, its outputs are unchanged (Section 4.1 "Setup"): under greedy decoding the emitted
+ * stream equals plain autoregressive decoding.  This library is the target-side pass after the
+ * projections: attention of every tree node over the paged prefix KV cache plus its own
+ * ancestors, LM head with a fused argmax, greedy longest-accepted-path selection, and the
+ * append of the accepted nodes' K/V to the cache (the paper keeps committed context in the KV
+ * cache, Section 4.1).
+ *
+ * Conventions for every entry point
+ *   - Returns an hb_status; on failure hb_last_error() gives a thread-local message.
+ *   - "device" pointers are GPU memory owned by the caller (valid on the current HIP device).
+ *     The library never allocates, frees or keeps them.  "host" pointers are ordinary memory.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream)
+ *     and the call returns without waiting for it.
+ *   - Only host-visible arguments are validated.  Malformed device data (a parent index that
+ *     is not smaller than its node, a page id outside the pool, a prefix longer than the page
+ *     table covers) is clamped so that every access stays inside the caller's buffers; the
+ *     result for such input is unspecified.
+ *   - A tree is an int32 parent array local to its sequence: parent[0] = -1 (the root is the
+ *     pending committed token), 0 <= parent[i] < i otherwise.  Trees of a batch are
+ *     concatenated; node_offset[b] .. node_offset[b+1] are the nodes of sequence b.
+ *   - Tensors are dense, row-major, in the layouts stated per function.  bf16 is the upper half
+ *     of an IEEE float32 (round to nearest even on output).
+ */
+#ifndef HB_H
+#define HB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum hb_status {
+  HB_OK = 0,
+  HB_ERR_INVALID_ARG = 1, /* null pointer, negative size, inconsistent sizes           */
+  HB_ERR_UNSUPPORTED = 2, /* a shape or dtype this library has no kernel for           */
+  HB_ERR_WORKSPACE = 3,   /* workspace missing or smaller than the *_workspace_bytes   */
+  HB_ERR_DEVICE = 4       /* a HIP call failed; the message carries hipGetErrorString  */
+} hb_status;
+
+typedef enum hb_dtype { HB_F32 = 0, HB_BF16 = 1 } hb_dtype;
+
+/* Kernel choice for hb_tree_verify_attn. */
+typedef enum hb_attn_algo {
+  HB_ATTN_AUTO = 0,   /* MFMA kernel when the shape allows it, else the scalar kernel        */
+  HB_ATTN_SCALAR = 1, /* one wavefront per (node, query head, split); any dtype, fp32 math  */
+  HB_ATTN_MFMA = 2    /* bf16, head_dim 128, page 16: KV tile shared by all nodes and the   */
+                      /* query heads of a kv group, bf16 MFMA with fp32 accumulation         */
+} hb_attn_algo;
+
+/* Shapes of one attention layer of one verification step. */
+typedef struct hb_attn_desc {
+  int32_t dtype;               /* hb_dtype of q, k/v (tree and pools) and out               */
+  int32_t batch;               /* B, number of sequences                                    */
+  int32_t num_q_heads;         /* Hq                                                        */
+  int32_t num_kv_heads;        /* Hkv, divides Hq; query head h reads kv head h / (Hq/Hkv)  */
+  int32_t head_dim;            /* D, multiple of 8, at most 256                             */
+  int32_t page_size;           /* tokens per KV page                                        */
+  int32_t max_blocks_per_seq;  /* row length of block_table                                 */
+  int32_t num_blocks;          /* pages in each pool (page ids are clamped to this)         */
+  int32_t total_nodes;         /* node_offset[B]                                            */
+  int32_t max_nodes_per_tree;  /* upper bound on nodes per sequence, at most 64             */
+  int32_t num_splits;          /* KV partitions per sequence; 0 = let the library choose    */
+  int32_t max_prefix_len_hint; /* upper bound on prefix_len known to the host, 0 = unknown  */
+                               /* (then max_blocks_per_seq * page_size is assumed)          */
+  int32_t algo;                /* hb_attn_algo                                              */
+  float softmax_scale;         /* scores are softmax_scale * <q, k>                         */
+} hb_attn_desc;
+
+const char *hb_last_error(void);
+int32_t hb_version(void);
+
+/* Host-side check of one tree's parent array (host pointer): HB_OK iff parent[0] == -1 and
+ * 0 <= parent[i] < i for 0 < i < n, and 1 <= n <= 64. */
+int32_t hb_tree_validate_host(const int32_t *parent, int32_t n);
+
+/*
+ * Tree-masked attention (the batched validation pass of Section 1).
+ * For node i of sequence b and query head h (kv head g = h / (Hq/Hkv)):
+ *   keys   = prefix positions 0 .. prefix_len[b]-1  and the tree nodes on the path root .. i
+ *   out    = sum_j softmax_j(softmax_scale * <q[i,h], k_j>) * v_j       over those keys
+ *   lse    = log sum_j exp(softmax_scale * <q[i,h], k_j>)               (natural log)
+ * Prefix position p is read at pool[block_table[b][p / page_size]][g][p % page_size][:].
+ *
+ *   q, out          device [total_nodes, Hq, D]        desc->dtype
+ *   k_tree, v_tree  device [total_nodes, Hkv, D]       desc->dtype (K/V of the tree nodes)
+ *   k_pool, v_pool  device [num_blocks, Hkv, page, D]  desc->dtype
+ *   block_table     device int32 [B, max_blocks_per_seq]
+ *   prefix_len      device int32 [B]
+ *   node_offset     device int32 [B+1]
+ *   parent          device int32 [total_nodes]
+ *   lse             device float32 [total_nodes, Hq], or NULL
+ *   workspace       device, at least hb_tree_verify_attn_workspace_bytes(desc) bytes, 256-byte
+ *                   aligned; may be NULL when that size is 0.  Contents are scratch.
+ * Accumulation is fp32; bf16 results are rounded once at the end.  Slots of a page at or beyond
+ * prefix_len, unmapped pages and tree nodes off the path are never allowed to influence the
+ * result, whatever bit patterns they hold.
+ * Errors: INVALID_ARG (null pointers, sizes <= 0 where a positive size is needed, Hq % Hkv),
+ * UNSUPPORTED (dtype, D, more than 64 nodes per tree, HB_ATTN_MFMA on a shape it cannot take),
+ * WORKSPACE, DEVICE.  batch == 0 or total_nodes == 0 is a successful no-op.
+ */
+int32_t hb_tree_verify_attn(const hb_attn_desc *desc, const void *q, const void *k_tree,
+                            const void *v_tree, const void *k_pool, const void *v_pool,
+                            const int32_t *block_table, const int32_t *prefix_len,
+                            const int32_t *node_offset, const int32_t *parent, void *out,
+                            float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace hb_tree_verify_attn needs for this descriptor (0 on a bad descriptor). */
+size_t hb_tree_verify_attn_workspace_bytes(const hb_attn_desc *desc);
+
+/* The number of KV partitions the library uses for this descriptor (resolves num_splits == 0). */
+int32_t hb_tree_verify_attn_num_splits(const hb_attn_desc *desc);
+
+/*
+ * LM head with fused argmax: the target's token after each node (greedy validation,
+ * Section 1 / Section 4.1).  out_ids[m] = the lowest v maximising sum_k hidden[m,k]*weight[v,k];
+ * logits are never written to memory.  A NaN logit never wins.
+ *
+ *   hidden    device [M, K]   dtype          weight   device [V, K]  dtype (nn.Linear layout)
+ *   out_ids   device int32 [M]               out_max  device float32 [M] or NULL: the winning
+ *                                                     logit as accumulated in fp32
+ *   workspace device, hb_lmhead_argmax_workspace_bytes(M) bytes, 8-byte aligned
+ * bf16 inputs with K % 8 == 0 take the MFMA kernel; everything else a scalar fp32 kernel.
+ * Errors: INVALID_ARG, UNSUPPORTED (dtype), WORKSPACE, DEVICE.  M == 0 is a no-op; V >= 1.
+ */
+int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
+                         const void *weight, int32_t *out_ids, float *out_max, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+size_t hb_lmhead_argmax_workspace_bytes(int32_t M);
+
+/*
+ * Greedy longest accepted path per sequence.  Node 0 is always accepted; node i > 0 matches
+ * when draft_ids[i] == target_ids[parent[i]] and is accepted when it and all its ancestors
+ * match.  The deepest accepted node wins (lowest id among equals).  accept_len is the number
+ * of tokens the step emits (accepted drafts below the root plus the bonus token), the quantity
+ * whose mean the paper reports as average acceptance length (Table 1).
+ *
+ *   node_offset  device int32 [B+1]     parent, draft_ids, target_ids  device int32 [total]
+ *   accept_len   device int32 [B]       bonus_id  device int32 [B] = target_ids[best node]
+ *   accept_path  device int32 [B, max_path]  tree-local node ids root..best, then -1
+ *   out_tokens   device int32 [B, max_path]  draft ids of path[1..], then the bonus id, then -1
+ * Nodes deeper than max_path-1 are treated as not accepted.  Trees with more than
+ * max_nodes_per_tree (<= 64) nodes are cut at that many nodes.
+ * Errors: INVALID_ARG, UNSUPPORTED (max_nodes_per_tree > 64), DEVICE.  B == 0 is a no-op.
+ */
+int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,
+                       const int32_t *parent, const int32_t *draft_ids, const int32_t *target_ids,
+                       int32_t max_path, int32_t *accept_len, int32_t *accept_path,
+                       int32_t *out_tokens, int32_t *bonus_id, void *stream);
+
+/*
+ * Append the accepted path's K/V to the paged cache of one layer (Section 4.1: committed
+ * context lives in the KV cache).  For j < accept_len[b]: position p = prefix_len[b] + j,
+ * slot = block_table[b][p / page] * page + p % page; the K and V rows (all kv heads) of tree
+ * node accept_path[b][j] are copied there bit for bit; out_slots[b][j] = slot, -1 for
+ * j >= accept_len[b]; new_len[b] = prefix_len[b] + accept_len[b].  No other byte of the pools
+ * changes.  The caller guarantees block_table maps the pages up to prefix_len + max_path;
+ * positions beyond max_blocks_per_seq * page are skipped.
+ * Uses desc->{dtype, batch, num_kv_heads, head_dim, page_size, max_blocks_per_seq, num_blocks,
+ * total_nodes}.  out_slots and new_len may be NULL.
+ * Errors: INVALID_ARG, UNSUPPORTED, DEVICE.
+ */
+int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *v_tree,
+                      void *k_pool, void *v_pool, const int32_t *block_table,
+                      const int32_t *prefix_len, const int32_t *node_offset,
+                      const int32_t *accept_len, const int32_t *accept_path, int32_t max_path,
+                      int32_t *out_slots, int32_t *new_len, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HB_H */

@@ -1,0 +1,28 @@
+"""MI355X-native tree verification for speculative decoding: thin binding over libhb.so.
+
+Every step runs in the HIP kernels of the C-ABI library; this package only marshals torch
+tensors (device memory, streams) into its arguments.  Importing it needs the built library:
+``python -m paper_2509_18824_amd.build`` (or ``__graft_entry__.build()``).
+"""
+from .binding import (
+    HbError,
+    AttnDesc,
+    lib,
+    hb_last_error,
+    hb_version,
+    hb_tree_validate_host,
+    hb_tree_verify_attn,
+    hb_tree_verify_attn_workspace_bytes,
+    hb_tree_verify_attn_num_splits,
+    hb_lmhead_argmax,
+    hb_lmhead_argmax_workspace_bytes,
+    hb_tree_accept,
+    hb_kv_compact,
+    HB_F32,
+    HB_BF16,
+    HB_ATTN_AUTO,
+    HB_ATTN_SCALAR,
+    HB_ATTN_MFMA,
+)
+
+__all__ = [n for n in dir() if n.startswith(("hb_", "HB_", "Hb")) or n in ("AttnDesc", "lib")]

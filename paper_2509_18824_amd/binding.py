@@ -1,0 +1,157 @@
+"""ctypes binding of include/hb.h: same names, argument marshalling only.
+
+There is no fallback: if libhb.so is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhb.so")
+
+HB_F32, HB_BF16 = 0, 1
+HB_ATTN_AUTO, HB_ATTN_SCALAR, HB_ATTN_MFMA = 0, 1, 2
+_STATUS = {0: "HB_OK", 1: "HB_ERR_INVALID_ARG", 2: "HB_ERR_UNSUPPORTED", 3: "HB_ERR_WORKSPACE",
+           4: "HB_ERR_DEVICE"}
+
+
+class HbError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"{_STATUS.get(code, code)}: {message}")
+        self.code = code
+
+
+class AttnDesc(C.Structure):
+    """Mirror of hb_attn_desc."""
+
+    _fields_ = [
+        ("dtype", C.c_int32), ("batch", C.c_int32), ("num_q_heads", C.c_int32),
+        ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
+        ("max_blocks_per_seq", C.c_int32), ("num_blocks", C.c_int32), ("total_nodes", C.c_int32),
+        ("max_nodes_per_tree", C.c_int32), ("num_splits", C.c_int32),
+        ("max_prefix_len_hint", C.c_int32), ("algo", C.c_int32), ("softmax_scale", C.c_float),
+    ]
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is not built; run `python -m paper_2509_18824_amd.build` "
+            "(hipcc, gfx950).  There is no fallback path.")
+    lib = C.CDLL(_LIB_PATH)
+    p, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.hb_last_error.restype = C.c_char_p
+    lib.hb_last_error.argtypes = []
+    lib.hb_version.restype = i32
+    lib.hb_version.argtypes = []
+    lib.hb_tree_validate_host.restype = i32
+    lib.hb_tree_validate_host.argtypes = [p, i32]
+    lib.hb_tree_verify_attn.restype = i32
+    lib.hb_tree_verify_attn.argtypes = [C.POINTER(AttnDesc)] + [p] * 11 + [p, sz, p]
+    lib.hb_tree_verify_attn_workspace_bytes.restype = sz
+    lib.hb_tree_verify_attn_workspace_bytes.argtypes = [C.POINTER(AttnDesc)]
+    lib.hb_tree_verify_attn_num_splits.restype = i32
+    lib.hb_tree_verify_attn_num_splits.argtypes = [C.POINTER(AttnDesc)]
+    lib.hb_lmhead_argmax.restype = i32
+    lib.hb_lmhead_argmax.argtypes = [i32, i32, i32, i32, p, p, p, p, p, sz, p]
+    lib.hb_lmhead_argmax_workspace_bytes.restype = sz
+    lib.hb_lmhead_argmax_workspace_bytes.argtypes = [i32]
+    lib.hb_tree_accept.restype = i32
+    lib.hb_tree_accept.argtypes = [i32, i32, p, p, p, p, i32, p, p, p, p, p]
+    lib.hb_kv_compact.restype = i32
+    lib.hb_kv_compact.argtypes = [C.POINTER(AttnDesc)] + [p] * 9 + [i32, p, p, p]
+    return lib
+
+
+lib = _load()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise HbError(rc, lib.hb_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to libhb must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        if not torch.cuda.is_available():
+            return C.c_void_p(0)  # only argument validation can succeed without a device
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return HB_F32
+    if t.dtype == torch.bfloat16:
+        return HB_BF16
+    raise HbError(2, f"dtype {t.dtype} is not supported")
+
+
+def hb_last_error() -> str:
+    return lib.hb_last_error().decode()
+
+
+def hb_version() -> int:
+    return int(lib.hb_version())
+
+
+def hb_tree_validate_host(parent) -> None:
+    arr = (C.c_int32 * len(parent))(*[int(x) for x in parent])
+    _check(lib.hb_tree_validate_host(arr, len(parent)))
+
+
+def hb_tree_verify_attn_workspace_bytes(desc: AttnDesc) -> int:
+    return int(lib.hb_tree_verify_attn_workspace_bytes(C.byref(desc)))
+
+
+def hb_tree_verify_attn_num_splits(desc: AttnDesc) -> int:
+    return int(lib.hb_tree_verify_attn_num_splits(C.byref(desc)))
+
+
+def hb_tree_verify_attn(desc: AttnDesc, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len,
+                        node_offset, parent, out, lse=None, workspace=None, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_tree_verify_attn(C.byref(desc), _ptr(q), _ptr(k_tree), _ptr(v_tree), _ptr(k_pool),
+                                   _ptr(v_pool), _ptr(block_table), _ptr(prefix_len), _ptr(node_offset),
+                                   _ptr(parent), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes,
+                                   _stream(stream)))
+
+
+def hb_lmhead_argmax_workspace_bytes(M: int) -> int:
+    return int(lib.hb_lmhead_argmax_workspace_bytes(M))
+
+
+def hb_lmhead_argmax(hidden, weight, out_ids, out_max=None, workspace=None, stream=None) -> None:
+    M, K = hidden.shape
+    V = weight.shape[0]
+    if weight.shape[1] != K or weight.dtype != hidden.dtype:
+        raise ValueError("weight must be [V, K] in the dtype of hidden")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_lmhead_argmax(_dtype_code(hidden), M, K, V, _ptr(hidden), _ptr(weight), _ptr(out_ids),
+                                _ptr(out_max), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def hb_tree_accept(B: int, max_nodes_per_tree: int, node_offset, parent, draft_ids, target_ids,
+                   max_path: int, accept_len, accept_path, out_tokens, bonus_id, stream=None) -> None:
+    _check(lib.hb_tree_accept(B, max_nodes_per_tree, _ptr(node_offset), _ptr(parent), _ptr(draft_ids),
+                              _ptr(target_ids), max_path, _ptr(accept_len), _ptr(accept_path),
+                              _ptr(out_tokens), _ptr(bonus_id), _stream(stream)))
+
+
+def hb_kv_compact(desc: AttnDesc, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset,
+                  accept_len, accept_path, max_path: int, out_slots=None, new_len=None, stream=None) -> None:
+    _check(lib.hb_kv_compact(C.byref(desc), _ptr(k_tree), _ptr(v_tree), _ptr(k_pool), _ptr(v_pool),
+                             _ptr(block_table), _ptr(prefix_len), _ptr(node_offset), _ptr(accept_len),
+                             _ptr(accept_path), max_path, _ptr(out_slots), _ptr(new_len), _stream(stream)))

@@ -1,0 +1,221 @@
+// Host side of libhb: argument validation, split-K planning, dispatch, error text.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include "hb_internal.h"
+
+namespace hb {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int32_t fail_hip(hipError_t e, const char *what) {
+  return fail(HB_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static int32_t gcd32(int32_t a, int32_t b) { while (b) { int32_t t = a % b; a = b; b = t; } return a; }
+
+static int32_t check_shape(const hb_attn_desc *d) {
+  if (!d) return fail(HB_ERR_INVALID_ARG, "desc is NULL");
+  if (d->dtype != HB_F32 && d->dtype != HB_BF16)
+    return fail(HB_ERR_UNSUPPORTED, "dtype %d: only HB_F32 and HB_BF16 are supported", d->dtype);
+  if (d->batch < 0 || d->total_nodes < 0) return fail(HB_ERR_INVALID_ARG, "negative batch or total_nodes");
+  if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->num_q_heads % d->num_kv_heads)
+    return fail(HB_ERR_INVALID_ARG, "num_q_heads %d must be a positive multiple of num_kv_heads %d",
+                d->num_q_heads, d->num_kv_heads);
+  if (d->head_dim <= 0 || d->head_dim % 8 || d->head_dim > 256)
+    return fail(HB_ERR_UNSUPPORTED, "head_dim %d: must be a multiple of 8, at most 256", d->head_dim);
+  if (d->page_size <= 0 || d->max_blocks_per_seq <= 0 || d->num_blocks <= 0)
+    return fail(HB_ERR_INVALID_ARG, "page_size, max_blocks_per_seq and num_blocks must be positive");
+  if ((int64_t)d->page_size * d->max_blocks_per_seq > (int64_t)1 << 30)
+    return fail(HB_ERR_UNSUPPORTED, "page table covers more than 2^30 positions");
+  if (d->max_nodes_per_tree <= 0) return fail(HB_ERR_INVALID_ARG, "max_nodes_per_tree must be positive");
+  if (d->max_nodes_per_tree > 64)
+    return fail(HB_ERR_UNSUPPORTED, "max_nodes_per_tree %d: trees of more than 64 nodes are not supported",
+                d->max_nodes_per_tree);
+  if (d->num_splits < 0 || d->max_prefix_len_hint < 0)
+    return fail(HB_ERR_INVALID_ARG, "num_splits and max_prefix_len_hint must be >= 0");
+  if (d->algo < HB_ATTN_AUTO || d->algo > HB_ATTN_MFMA) return fail(HB_ERR_INVALID_ARG, "algo %d", d->algo);
+  return HB_OK;
+}
+
+int32_t make_attn_plan(const hb_attn_desc *d, AttnPlan *plan) {
+  int32_t rc = check_shape(d);
+  if (rc) return rc;
+  bool can_mfma = attn_mfma_supports(*d);
+  if (d->algo == HB_ATTN_MFMA && !can_mfma)
+    return fail(HB_ERR_UNSUPPORTED,
+                "HB_ATTN_MFMA needs bf16, head_dim 128, page_size 16 and (Hq/Hkv)*max_nodes_per_tree <= 448");
+  plan->mfma = (d->algo == HB_ATTN_MFMA) || (d->algo == HB_ATTN_AUTO && can_mfma);
+  int64_t span = (int64_t)d->page_size * d->max_blocks_per_seq;
+  if (d->max_prefix_len_hint > 0 && d->max_prefix_len_hint < span) span = d->max_prefix_len_hint;
+  if (span < 1) span = 1;
+  int32_t gran = d->page_size * (64 / gcd32(d->page_size, 64));  // multiple of the page and of 64
+  int64_t splits = d->num_splits;
+  if (splits == 0) {
+    if (plan->mfma) {
+      // one workgroup per (sequence, kv head, chunk): aim at ~2 workgroups per CU, but keep a
+      // chunk at 1024 tokens or more so that partial traffic stays below the KV traffic
+      int64_t items = (int64_t)d->batch * d->num_kv_heads;
+      splits = items > 0 ? (512 + items - 1) / items : 1;
+      int64_t cap = (span + 1023) / 1024;
+      if (splits > cap) splits = cap;
+    } else {
+      int64_t rows = (int64_t)d->total_nodes * d->num_q_heads;
+      splits = rows > 0 ? (2048 + rows - 1) / rows : 1;
+      int64_t cap = (span + 255) / 256;
+      if (splits > cap) splits = cap;
+    }
+    if (splits < 1) splits = 1;
+  }
+  if (splits > 1024) splits = 1024;
+  int64_t chunk = (span + splits - 1) / splits;
+  chunk = (chunk + gran - 1) / gran * gran;
+  splits = (span + chunk - 1) / chunk;
+  if (splits < 1) splits = 1;
+  plan->splits = (int32_t)splits;
+  plan->chunk_tokens = (int32_t)chunk;
+  size_t rows = (size_t)d->total_nodes * d->num_q_heads;
+  if (splits > 1) {
+    plan->ml_offset = align_up(rows * splits * d->head_dim * sizeof(float), 256);
+    plan->bytes = plan->ml_offset + align_up(rows * splits * 2 * sizeof(float), 256);
+  } else {
+    plan->ml_offset = 0;
+    plan->bytes = 0;
+  }
+  return HB_OK;
+}
+
+}  // namespace hb
+
+using namespace hb;
+
+extern "C" {
+
+const char *hb_last_error(void) { return g_err; }
+int32_t hb_version(void) { return 1; }
+
+int32_t hb_tree_validate_host(const int32_t *parent, int32_t n) {
+  if (!parent) return fail(HB_ERR_INVALID_ARG, "parent is NULL");
+  if (n < 1 || n > 64) return fail(HB_ERR_UNSUPPORTED, "a tree has 1..64 nodes, got %d", n);
+  if (parent[0] != -1) return fail(HB_ERR_INVALID_ARG, "parent[0] must be -1, got %d", parent[0]);
+  for (int32_t i = 1; i < n; ++i)
+    if (parent[i] < 0 || parent[i] >= i)
+      return fail(HB_ERR_INVALID_ARG, "parent[%d] = %d must lie in [0, %d)", i, parent[i], i);
+  return HB_OK;
+}
+
+size_t hb_tree_verify_attn_workspace_bytes(const hb_attn_desc *desc) {
+  AttnPlan plan;
+  if (make_attn_plan(desc, &plan)) return 0;
+  return plan.bytes;
+}
+
+int32_t hb_tree_verify_attn_num_splits(const hb_attn_desc *desc) {
+  AttnPlan plan;
+  if (make_attn_plan(desc, &plan)) return 0;
+  return plan.splits;
+}
+
+int32_t hb_tree_verify_attn(const hb_attn_desc *desc, const void *q, const void *k_tree,
+                            const void *v_tree, const void *k_pool, const void *v_pool,
+                            const int32_t *block_table, const int32_t *prefix_len,
+                            const int32_t *node_offset, const int32_t *parent, void *out,
+                            float *lse, void *workspace, size_t workspace_bytes, void *stream) {
+  AttnPlan plan;
+  int32_t rc = make_attn_plan(desc, &plan);
+  if (rc) return rc;
+  if (desc->batch == 0 || desc->total_nodes == 0) return HB_OK;
+  if (!q || !k_tree || !v_tree || !k_pool || !v_pool || !block_table || !prefix_len || !node_offset ||
+      !parent || !out)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  float *part_o = nullptr, *part_ml = nullptr;
+  if (plan.splits > 1) {
+    if (!workspace || workspace_bytes < plan.bytes)
+      return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", plan.bytes,
+                  workspace ? workspace_bytes : (size_t)0);
+    if ((uintptr_t)workspace % 256) return fail(HB_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    part_o = (float *)workspace;
+    part_ml = (float *)((char *)workspace + plan.ml_offset);
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (plan.mfma)
+    HB_HIP_TRY(launch_attn_mfma(*desc, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len,
+                                node_offset, parent, out, lse, part_o, part_ml, s));
+  else
+    HB_HIP_TRY(launch_attn_scalar(*desc, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len,
+                                  node_offset, parent, out, lse, part_o, part_ml, s));
+  if (plan.splits > 1) HB_HIP_TRY(launch_attn_merge(*desc, plan, part_o, part_ml, out, lse, s));
+  return HB_OK;
+}
+
+size_t hb_lmhead_argmax_workspace_bytes(int32_t M) { return M > 0 ? (size_t)M * 8 : 0; }
+
+int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
+                         const void *weight, int32_t *out_ids, float *out_max, void *workspace,
+                         size_t workspace_bytes, void *stream) {
+  if (dtype != HB_F32 && dtype != HB_BF16)
+    return fail(HB_ERR_UNSUPPORTED, "dtype %d: only HB_F32 and HB_BF16 are supported", dtype);
+  if (M < 0 || K <= 0 || V <= 0) return fail(HB_ERR_INVALID_ARG, "need M >= 0, K > 0, V > 0 (got %d, %d, %d)", M, K, V);
+  if (M == 0) return HB_OK;
+  if (!hidden || !weight || !out_ids) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  size_t need = hb_lmhead_argmax_workspace_bytes(M);
+  if (!workspace || workspace_bytes < need)
+    return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  if ((uintptr_t)workspace % 8) return fail(HB_ERR_WORKSPACE, "workspace must be 8-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  unsigned long long *keys = (unsigned long long *)workspace;
+  HB_HIP_TRY(launch_lmhead_init(keys, M, s));
+  if (lmhead_mfma_supports(dtype, M, K, V))
+    HB_HIP_TRY(launch_lmhead_mfma(M, K, V, hidden, weight, keys, s));
+  else
+    HB_HIP_TRY(launch_lmhead_scalar(dtype, M, K, V, hidden, weight, keys, s));
+  HB_HIP_TRY(launch_lmhead_finish(keys, M, V, out_ids, out_max, s));
+  return HB_OK;
+}
+
+int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,
+                       const int32_t *parent, const int32_t *draft_ids, const int32_t *target_ids,
+                       int32_t max_path, int32_t *accept_len, int32_t *accept_path,
+                       int32_t *out_tokens, int32_t *bonus_id, void *stream) {
+  if (B < 0 || max_path <= 0 || max_nodes_per_tree <= 0)
+    return fail(HB_ERR_INVALID_ARG, "need B >= 0, max_path > 0, max_nodes_per_tree > 0");
+  if (max_nodes_per_tree > 64)
+    return fail(HB_ERR_UNSUPPORTED, "max_nodes_per_tree %d: trees of more than 64 nodes are not supported",
+                max_nodes_per_tree);
+  if (B == 0) return HB_OK;
+  if (!node_offset || !parent || !draft_ids || !target_ids || !accept_len || !accept_path || !out_tokens ||
+      !bonus_id)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  HB_HIP_TRY(launch_tree_accept(B, max_nodes_per_tree, node_offset, parent, draft_ids, target_ids, max_path,
+                                accept_len, accept_path, out_tokens, bonus_id, (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *v_tree,
+                      void *k_pool, void *v_pool, const int32_t *block_table,
+                      const int32_t *prefix_len, const int32_t *node_offset,
+                      const int32_t *accept_len, const int32_t *accept_path, int32_t max_path,
+                      int32_t *out_slots, int32_t *new_len, void *stream) {
+  int32_t rc = check_shape(desc);
+  if (rc) return rc;
+  if (max_path <= 0) return fail(HB_ERR_INVALID_ARG, "max_path must be positive");
+  if (desc->batch == 0) return HB_OK;
+  if (!k_tree || !v_tree || !k_pool || !v_pool || !block_table || !prefix_len || !node_offset ||
+      !accept_len || !accept_path)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  HB_HIP_TRY(launch_kv_compact(*desc, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset,
+                               accept_len, accept_path, max_path, out_slots, new_len, (hipStream_t)stream));
+  return HB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+"""Convenience wrappers that allocate outputs/workspaces as torch tensors and call the C ABI.
+
+Nothing here computes: each function sizes buffers, fills an ``AttnDesc`` and forwards to the
+library.  ``VerifyStep`` chains the four calls of one verification step on the current stream.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+from . import binding as hb
+
+
+def make_desc(dtype, B, Hq, Hkv, D, page, max_blocks, num_blocks, total_nodes, max_nodes,
+              softmax_scale, num_splits=0, hint=0, algo=hb.HB_ATTN_AUTO) -> hb.AttnDesc:
+    code = hb.HB_F32 if dtype in ("f32", torch.float32) else hb.HB_BF16
+    return hb.AttnDesc(dtype=code, batch=B, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D,
+                       page_size=page, max_blocks_per_seq=max_blocks, num_blocks=num_blocks,
+                       total_nodes=total_nodes, max_nodes_per_tree=max_nodes, num_splits=num_splits,
+                       max_prefix_len_hint=hint, algo=algo, softmax_scale=float(softmax_scale))
+
+
+@dataclass
+class DeviceInputs:
+    """Device copies of one batch (field names as in the C ABI)."""
+
+    q: torch.Tensor
+    k_tree: torch.Tensor
+    v_tree: torch.Tensor
+    k_pool: torch.Tensor
+    v_pool: torch.Tensor
+    block_table: torch.Tensor
+    prefix_len: torch.Tensor
+    node_offset: torch.Tensor
+    parent: torch.Tensor
+
+
+def to_device(inp, device="cuda") -> DeviceInputs:
+    f = lambda t: t.to(device).contiguous()
+    return DeviceInputs(f(inp.q), f(inp.k_tree), f(inp.v_tree), f(inp.k_pool), f(inp.v_pool),
+                        f(inp.block_table), f(inp.prefix_len), f(inp.node_offset), f(inp.parent))
+
+
+def desc_for(inp, num_splits=0, hint=0, algo=hb.HB_ATTN_AUTO) -> hb.AttnDesc:
+    max_nodes = int((inp.node_offset[1:] - inp.node_offset[:-1]).max()) if inp.B else 1
+    return make_desc(inp.dtype, inp.B, inp.Hq, inp.Hkv, inp.D, inp.page, inp.max_blocks,
+                     inp.num_blocks, inp.total_nodes, max_nodes, inp.softmax_scale, num_splits,
+                     hint, algo)
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def tree_verify_attn(desc: hb.AttnDesc, dev: DeviceInputs, want_lse=True, workspace=None, out=None):
+    """Returns (out, lse).  Allocates what is not passed in."""
+    if out is None:
+        out = torch.empty_like(dev.q)
+    lse = torch.empty(dev.q.shape[:2], dtype=torch.float32, device=dev.q.device) if want_lse else None
+    if workspace is None:
+        workspace = alloc_workspace(hb.hb_tree_verify_attn_workspace_bytes(desc), dev.q.device)
+    hb.hb_tree_verify_attn(desc, dev.q, dev.k_tree, dev.v_tree, dev.k_pool, dev.v_pool, dev.block_table,
+                           dev.prefix_len, dev.node_offset, dev.parent, out, lse, workspace)
+    return out, lse
+
+
+def lmhead_argmax(hidden, weight, want_max=True, workspace=None):
+    M = hidden.shape[0]
+    ids = torch.empty(M, dtype=torch.int32, device=hidden.device)
+    mx = torch.empty(M, dtype=torch.float32, device=hidden.device) if want_max else None
+    if workspace is None:
+        workspace = alloc_workspace(max(8, hb.hb_lmhead_argmax_workspace_bytes(M)), hidden.device)
+    hb.hb_lmhead_argmax(hidden, weight, ids, mx, workspace)
+    return ids, mx
+
+
+def tree_accept(node_offset, parent, draft_ids, target_ids, max_path, max_nodes):
+    B = node_offset.numel() - 1
+    dev = node_offset.device
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    accept_path = torch.empty((B, max_path), dtype=torch.int32, device=dev)
+    out_tokens = torch.empty((B, max_path), dtype=torch.int32, device=dev)
+    bonus = torch.empty(B, dtype=torch.int32, device=dev)
+    hb.hb_tree_accept(B, max_nodes, node_offset, parent, draft_ids, target_ids, max_path, accept_len,
+                      accept_path, out_tokens, bonus)
+    return accept_len, accept_path, out_tokens, bonus
+
+
+def kv_compact(desc, dev: DeviceInputs, accept_len, accept_path):
+    B, max_path = accept_path.shape
+    out_slots = torch.empty((B, max_path), dtype=torch.int32, device=accept_path.device)
+    new_len = torch.empty(B, dtype=torch.int32, device=accept_path.device)
+    hb.hb_kv_compact(desc, dev.k_tree, dev.v_tree, dev.k_pool, dev.v_pool, dev.block_table, dev.prefix_len,
+                     dev.node_offset, accept_len, accept_path, max_path, out_slots, new_len)
+    return out_slots, new_len
+
+
+class VerifyStep:
+    """Pre-allocated buffers for one full verification step (attention of one layer, LM head,
+    acceptance, compaction); ``run`` only enqueues kernels."""
+
+    def __init__(self, desc: hb.AttnDesc, dev: DeviceInputs, weight: torch.Tensor, draft_ids: torch.Tensor,
+                 max_path: int):
+        self.desc, self.dev, self.weight, self.draft_ids, self.max_path = desc, dev, weight, draft_ids, max_path
+        d = dev.q.device
+        T, Hq, D = dev.q.shape
+        B = desc.batch
+        self.out = torch.empty_like(dev.q)
+        self.ws_attn = alloc_workspace(hb.hb_tree_verify_attn_workspace_bytes(desc), d)
+        self.ws_lm = alloc_workspace(max(8, hb.hb_lmhead_argmax_workspace_bytes(T)), d)
+        self.target_ids = torch.empty(T, dtype=torch.int32, device=d)
+        self.accept_len = torch.empty(B, dtype=torch.int32, device=d)
+        self.accept_path = torch.empty((B, max_path), dtype=torch.int32, device=d)
+        self.out_tokens = torch.empty((B, max_path), dtype=torch.int32, device=d)
+        self.bonus = torch.empty(B, dtype=torch.int32, device=d)
+        self.out_slots = torch.empty((B, max_path), dtype=torch.int32, device=d)
+        self.new_len = torch.empty(B, dtype=torch.int32, device=d)
+
+    def run(self, compact=True):
+        dev, desc = self.dev, self.desc
+        hb.hb_tree_verify_attn(desc, dev.q, dev.k_tree, dev.v_tree, dev.k_pool, dev.v_pool, dev.block_table,
+                               dev.prefix_len, dev.node_offset, dev.parent, self.out, None, self.ws_attn)
+        hidden = self.out.view(self.out.shape[0], -1)  # [T, Hq*D]: attention output feeds the LM head
+        hb.hb_lmhead_argmax(hidden, self.weight, self.target_ids, None, self.ws_lm)
+        hb.hb_tree_accept(desc.batch, desc.max_nodes_per_tree, dev.node_offset, dev.parent, self.draft_ids,
+                          self.target_ids, self.max_path, self.accept_len, self.accept_path, self.out_tokens,
+                          self.bonus)
+        if compact:
+            hb.hb_kv_compact(desc, dev.k_tree, dev.v_tree, dev.k_pool, dev.v_pool, dev.block_table,
+                             dev.prefix_len, dev.node_offset, self.accept_len, self.accept_path, self.max_path,
+                             self.out_slots, self.new_len)

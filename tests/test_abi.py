@@ -1,0 +1,105 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad
+arguments on the host without touching a device (runs without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2509_18824_amd as hb
+from paper_2509_18824_amd.step import make_desc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "hb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hb_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert {"hb_tree_verify_attn", "hb_lmhead_argmax", "hb_tree_accept", "hb_kv_compact"} <= set(names)
+    for n in names:
+        assert hasattr(hb.lib, n), n
+        assert hasattr(hb, n), f"python binding lacks {n}"
+
+
+def test_version_and_tree_validation():
+    assert hb.hb_version() >= 1
+    hb.hb_tree_validate_host([-1, 0, 0, 2])
+    for bad in ([0, 0], [-1, 1], [-1, 0, 3], [-1, -1]):
+        with pytest.raises(hb.HbError) as e:
+            hb.hb_tree_validate_host(bad)
+        assert e.value.code == 1
+    with pytest.raises(hb.HbError) as e:
+        hb.hb_tree_validate_host([-1] + list(range(64)))
+    assert e.value.code == 2
+
+
+def _desc(**kw):
+    base = dict(dtype="bf16", B=2, Hq=28, Hkv=4, D=128, page=16, max_blocks=64, num_blocks=200,
+                total_nodes=120, max_nodes=60, softmax_scale=0.1)
+    base.update(kw)
+    return make_desc(**base)
+
+
+def _attn_rc(desc, ws_bytes=0, ptr=0x1000):
+    p = C.c_void_p(ptr)
+    return hb.lib.hb_tree_verify_attn(C.byref(desc), p, p, p, p, p, p, p, p, p, p, None,
+                                      C.c_void_p(0x1000) if ws_bytes else None, ws_bytes, None)
+
+
+def test_attention_argument_errors():
+    assert _attn_rc(_desc(Hq=30)) == 1  # heads do not divide
+    assert "num_q_heads" in hb.hb_last_error()
+    assert _attn_rc(_desc(D=100)) == 2
+    assert _attn_rc(_desc(D=512)) == 2
+    assert _attn_rc(_desc(max_nodes=65)) == 2
+    assert "64" in hb.hb_last_error()
+    assert _attn_rc(_desc(page=0)) == 1
+    d = _desc()
+    d.dtype = 7
+    assert _attn_rc(d) == 2
+    assert _attn_rc(_desc(), ptr=0) == 1  # null pointers
+    d = _desc(num_splits=4)
+    need = hb.hb_tree_verify_attn_workspace_bytes(d)
+    assert need > 0 and hb.hb_tree_verify_attn_num_splits(d) == 4
+    assert _attn_rc(d, ws_bytes=0) == 3
+    assert _attn_rc(d, ws_bytes=need - 1) == 3
+    assert _attn_rc(_desc(dtype="f32", D=64, algo=hb.HB_ATTN_MFMA)) == 2
+    # empty batches are a no-op that needs no pointers
+    assert _attn_rc(_desc(B=0, total_nodes=0), ptr=0) == 0
+
+
+def test_split_plan_is_consistent():
+    for splits in (1, 2, 3, 7, 16):
+        d = _desc(num_splits=splits, max_blocks=513)
+        got = hb.hb_tree_verify_attn_num_splits(d)
+        assert 1 <= got <= splits
+        ws = hb.hb_tree_verify_attn_workspace_bytes(d)
+        assert (ws == 0) == (got == 1)
+        if got > 1:
+            assert ws >= 120 * 28 * got * (128 + 2) * 4
+    auto = hb.hb_tree_verify_attn_num_splits(_desc(max_blocks=2049))
+    assert auto >= 1
+
+
+def test_lmhead_accept_compact_argument_errors():
+    p = C.c_void_p(0x1000)
+    L = hb.lib
+    assert L.hb_lmhead_argmax(1, 4, 8, 0, p, p, p, None, p, 64, None) == 1
+    assert L.hb_lmhead_argmax(5, 4, 8, 16, p, p, p, None, p, 64, None) == 2
+    assert L.hb_lmhead_argmax(1, 4, 8, 16, p, p, p, None, p, 8, None) == 3
+    assert L.hb_lmhead_argmax(1, 4, 8, 16, None, p, p, None, p, 64, None) == 1
+    assert L.hb_lmhead_argmax(1, 0, 8, 16, None, None, None, None, None, 0, None) == 0
+    assert hb.hb_lmhead_argmax_workspace_bytes(960) == 960 * 8
+    assert L.hb_tree_accept(2, 65, p, p, p, p, 6, p, p, p, p, None) == 2
+    assert L.hb_tree_accept(2, 60, p, p, p, p, 0, p, p, p, p, None) == 1
+    assert L.hb_tree_accept(2, 60, None, p, p, p, 6, p, p, p, p, None) == 1
+    assert L.hb_tree_accept(0, 60, None, None, None, None, 6, None, None, None, None, None) == 0
+    d = _desc()
+    assert L.hb_kv_compact(C.byref(d), p, p, p, p, p, p, p, p, p, 0, None, None, None) == 1
+    assert L.hb_kv_compact(C.byref(d), None, p, p, p, p, p, p, p, p, 6, None, None, None) == 1
+    assert L.hb_kv_compact(None, p, p, p, p, p, p, p, p, p, 6, None, None, None) == 1

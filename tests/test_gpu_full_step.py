@@ -1,0 +1,97 @@
+"""GPU end-to-end checks: the full verification step of the batch-16 workload against the
+oracle, and greedy losslessness on the toy decoder with the GPU kernels in the loop."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import ToyDecoderRef, tree_accept_ref, kv_compact_ref, lmhead_logits_ref
+from parity import bits, check_attn, oracle_attn
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def S():
+    import paper_2509_18824_amd.step as s
+    return s
+
+
+@pytest.mark.parametrize("tree", ["tree", "chain8"])
+def test_full_step_scaled(S, tree):
+    """Attention -> LM head -> acceptance -> compaction on a scaled copy of the full-step
+    workload (vocab 8192 instead of 152064 so the oracle covers every node).  Two passes, as in
+    the benchmark: pass 1 yields the target ids, the host plants draft ids along a seeded path,
+    pass 2 is the step under test."""
+    inp = W.make_config(4, scale_down=8, tree=tree)
+    V = 8192
+    _, weight = W.make_lmhead_inputs(44, 1, inp.Hq * inp.D, V, dtype="bf16")
+    dev = S.to_device(inp)
+    desc = S.desc_for(inp)
+    k_pool0, v_pool0 = bits(dev.k_pool).copy(), bits(dev.v_pool).copy()
+    wdev = weight.cuda()
+    dummy = torch.zeros(inp.total_nodes, dtype=torch.int32, device="cuda")
+    stp = S.VerifyStep(desc, dev, wdev, dummy, inp.max_path)
+    stp.run(compact=False)
+    torch.cuda.synchronize()
+    target = stp.target_ids.cpu().numpy()
+    draft, planted = W.plant_draft_ids(4, inp.trees(), target, V)
+    stp.draft_ids.copy_(torch.from_numpy(draft))
+    stp.run(compact=True)
+    torch.cuda.synchronize()
+
+    # attention against the oracle
+    ref_out, ref_lse = oracle_attn(inp)
+    check_attn(inp, stp.out, None, ref=(ref_out, ref_lse), label="full step attention")
+    # LM head: the oracle is fed the GPU's bf16 hidden states (decouples it from attention rounding)
+    hidden = W.widen(stp.out.view(inp.total_nodes, -1))
+    logits = lmhead_logits_ref(hidden, W.widen(weight))
+    order = np.argsort(-logits, axis=1, kind="stable")[:, :2]
+    r = np.arange(inp.total_nodes)
+    margin = logits[r, order[:, 0]] - logits[r, order[:, 1]]
+    eps = 1e-4 * np.linalg.norm(hidden, axis=1) * 0.02 * np.sqrt(hidden.shape[1])
+    got = stp.target_ids.cpu().numpy()
+    clear = margin > eps
+    assert (got[clear] == order[clear, 0]).all() and clear.mean() > 0.95
+    assert np.logical_or(got == order[:, 0], got == order[:, 1]).all()
+    # acceptance and compaction: bit exact given the same target ids
+    alen, apath, otoks, bonus = tree_accept_ref(inp.node_offset.numpy(), inp.parent.numpy(), draft, got, inp.max_path)
+    assert np.array_equal(stp.accept_len.cpu().numpy(), alen)
+    assert np.array_equal(stp.accept_path.cpu().numpy(), apath)
+    assert np.array_equal(stp.out_tokens.cpu().numpy(), otoks)
+    assert np.array_equal(stp.bonus.cpu().numpy(), bonus)
+    assert list(alen) == [d + 1 for d in planted]
+    rk, rv, rslots, rlen = kv_compact_ref(bits(inp.k_tree), bits(inp.v_tree), k_pool0, v_pool0,
+                                          inp.block_table.numpy(), inp.prefix_len.numpy(),
+                                          inp.node_offset.numpy(), alen, apath)
+    assert np.array_equal(stp.out_slots.cpu().numpy(), rslots)
+    assert np.array_equal(stp.new_len.cpu().numpy(), rlen)
+    assert np.array_equal(bits(dev.k_pool), rk) and np.array_equal(bits(dev.v_pool), rv)
+
+
+@pytest.mark.parametrize("kind", ["random", "replay", "corrupting"])
+@pytest.mark.parametrize("topology", ["tree", "chain4"])
+def test_greedy_losslessness_on_the_toy_decoder(kind, topology):
+    """Speculative decoding with the GPU kernels emits exactly the oracle's plain greedy
+    autoregressive stream (paper Section 1, Section 4.1 'Setup')."""
+    from toy_gpu import ToyDecoderGpu
+    w = W.make_toy_weights(0)
+    ref = ToyDecoderRef(w)
+    prompt = [int(t) for t in np.random.default_rng(100).integers(0, w.vocab, size=40)]
+    n_new = 48
+    stream, margin = ref.greedy_ar(prompt, n_new)
+    assert margin > 1e-3  # fp32 reordering cannot flip an argmax
+    drafter = {
+        "random": W.random_drafter(1, w.vocab),
+        "replay": W.replay_drafter(1, w.vocab, len(prompt), stream),
+        "corrupting": W.replay_drafter(1, w.vocab, len(prompt), stream, wrong_after=(0, 4)),
+    }[kind]
+    tree = (lambda s: W.seeded_tree(s, n_nodes=16, levels=5, root_fanout=3, max_fanout=3)) \
+        if topology == "tree" else (lambda s: W.chain_tree(4))
+    table = np.random.default_rng(3).permutation(16)
+    gpu = ToyDecoderGpu(w, n_blocks=16)
+    out, lens = gpu.spec_decode(prompt, n_new, drafter, tree, table)
+    assert out == stream
+    if kind == "replay":
+        full = 5 if topology == "tree" else 4
+        assert all(l == full for l in lens[:-1])
