@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the full verification step on one MI355X.
+
+A step = tree-verify attention (one layer) + LM head with fused argmax + greedy acceptance +
+KV compaction over the batch-16 full-step workload (ragged prefixes in [1024, 4096], one 60-node
+tree per sequence, hidden 3584 x vocab 152064, bf16).  All inputs are synthetic, seeded, and
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--tree tree|chain8] [--no-attn-extra]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+
+
+def _events(n):
+    import torch
+    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+
+
+def _mean_ms(pairs):
+    return sum(a.elapsed_time(b) for a, b in pairs) / max(len(pairs), 1)
+
+
+def cpu_baseline(inp, weight, draft_ids, sample_per_seq=4):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: `sample_per_seq`
+    nodes of every sequence go through attention and the LM head (weight widened to float64
+    once, as the oracle does), then acceptance and compaction run on the whole batch."""
+    import numpy as np
+    import workloads as W
+    from oracle import tree_attn_ref, lmhead_argmax_ref, tree_accept_ref, kv_compact_ref
+
+    rng = np.random.default_rng(0)
+    off = inp.node_offset.numpy()
+    nodes = sorted(int(off[b] + i) for b in range(inp.B)
+                   for i in rng.choice(off[b + 1] - off[b], size=min(sample_per_seq, off[b + 1] - off[b]),
+                                       replace=False))
+    t0 = time.perf_counter()
+    out, _ = tree_attn_ref(W.widen(inp.q), W.widen(inp.k_tree), W.widen(inp.v_tree), W.widen(inp.k_pool),
+                           W.widen(inp.v_pool), inp.block_table.numpy(), inp.prefix_len.numpy(),
+                           inp.node_offset.numpy(), inp.parent.numpy(), inp.softmax_scale, nodes=nodes)
+    t1 = time.perf_counter()
+    hidden = out.reshape(len(nodes), -1)
+    ids, _ = lmhead_argmax_ref(hidden, W.widen(weight))
+    t2 = time.perf_counter()
+    target = np.zeros(inp.total_nodes, dtype=np.int64)
+    target[nodes] = ids
+    alen, apath, _, _ = tree_accept_ref(off, inp.parent.numpy(), draft_ids, target, inp.max_path)
+    bits = lambda t: t.view(__import__("torch").int16).numpy()
+    kv_compact_ref(bits(inp.k_tree), bits(inp.v_tree), bits(inp.k_pool), bits(inp.v_pool),
+                   inp.block_table.numpy(), inp.prefix_len.numpy(), off, alen, apath)
+    t3 = time.perf_counter()
+    cores = len(os.sched_getaffinity(0))
+    for var in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+        if os.environ.get(var, "").isdigit():
+            cores = min(cores, int(os.environ[var]))
+    total = t3 - t0
+    return {
+        "value": len(nodes) / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+        "sample": f"{len(nodes)} of {inp.total_nodes} tree nodes ({sample_per_seq} per sequence) through "
+                  f"attention ({t1 - t0:.1f} s) and the LM head over the full vocabulary ({t2 - t1:.1f} s, "
+                  f"includes widening the weight to float64 once); acceptance and compaction on the whole "
+                  f"batch ({t3 - t2:.2f} s); float64 numpy",
+        "seconds": total,
+    }
+
+
+def bench_attention_only(cfg, steps, warmup, n_pools=4):
+    """Attention kernel alone on workload `cfg`, rotating over `n_pools` distinct copies of the KV
+    pools so that consecutive launches do not find their KV in the 256 MB last-level cache."""
+    import torch
+    import workloads as W
+    import paper_2509_18824_amd as hb
+    import paper_2509_18824_amd.step as S
+
+    inp = W.make_config(cfg)
+    dev = S.to_device(inp)
+    hint = int(inp.prefix_len.max())
+    desc = S.desc_for(inp, hint=hint)
+    pools = [(dev.k_pool, dev.v_pool)] + [(dev.k_pool.clone(), dev.v_pool.clone()) for _ in range(n_pools - 1)]
+    out = torch.empty_like(dev.q)
+    ws = S.alloc_workspace(hb.hb_tree_verify_attn_workspace_bytes(desc))
+
+    def launch(i):
+        kp, vp = pools[i % n_pools]
+        hb.hb_tree_verify_attn(desc, dev.q, dev.k_tree, dev.v_tree, kp, vp, dev.block_table, dev.prefix_len,
+                               dev.node_offset, dev.parent, out, None, ws)
+
+    for i in range(warmup):
+        launch(i)
+    torch.cuda.synchronize()
+    ev = _events(steps)
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        launch(i)
+        b.record()
+    torch.cuda.synchronize()
+    ms = _mean_ms(ev)
+    kv_bytes = inp.kv_bytes()
+    rows = inp.total_nodes * inp.Hq
+    flops = 4.0 * inp.D * inp.Hq * sum(
+        int(n) * (int(L) + 0) for n, L in zip((inp.node_offset[1:] - inp.node_offset[:-1]).tolist(),
+                                              inp.prefix_len.tolist()))
+    return {
+        "workload": inp.name, "ms": ms, "tree_tokens_per_s": inp.total_nodes / (ms * 1e-3),
+        "kv_bytes": kv_bytes, "kv_GBps": kv_bytes / (ms * 1e-3) / 1e9,
+        "kv_frac_of_hbm_peak": kv_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "attn_TFLOPs": flops / (ms * 1e-3) / 1e12,
+        "attn_frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "splits": hb.hb_tree_verify_attn_num_splits(desc), "rows": rows,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--tree", choices=["tree", "chain8"], default="tree")
+    ap.add_argument("--no-attn-extra", action="store_true", help="skip the attention-only runs of the "
+                    "ragged-batch and long-context workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2509_18824_amd as hb
+    import paper_2509_18824_amd.step as S
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    inp = W.make_config(4, tree=args.tree)
+    V, K = 152064, inp.Hq * inp.D
+    _, weight = W.make_lmhead_inputs(4000, 1, K, V, dtype="bf16")
+    dev = S.to_device(inp)
+    wdev = weight.cuda()
+    hint = int(inp.prefix_len.max())
+    desc = S.desc_for(inp, hint=hint)
+    draft = torch.zeros(inp.total_nodes, dtype=torch.int32, device="cuda")
+    step = S.VerifyStep(desc, dev, wdev, draft, inp.max_path)
+
+    # pass 1: target ids; the host then plants draft ids along a seeded path per sequence
+    step.run(compact=False)
+    torch.cuda.synchronize()
+    target = step.target_ids.cpu().numpy()
+    draft_np, planted = W.plant_draft_ids(4, inp.trees(), target, V)
+    step.draft_ids.copy_(torch.from_numpy(draft_np))
+
+    for _ in range(args.warmup):
+        step.run()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` full steps; HIP events bracket each call inside it
+    ev_attn, ev_lm, ev_acc, ev_cmp = (_events(args.steps) for _ in range(4))
+    dv = step.dev
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev_attn[i][0].record()
+        hb.hb_tree_verify_attn(desc, dv.q, dv.k_tree, dv.v_tree, dv.k_pool, dv.v_pool, dv.block_table,
+                               dv.prefix_len, dv.node_offset, dv.parent, step.out, None, step.ws_attn)
+        ev_attn[i][1].record()
+        ev_lm[i][0].record()
+        hb.hb_lmhead_argmax(step.out.view(inp.total_nodes, -1), wdev, step.target_ids, None, step.ws_lm)
+        ev_lm[i][1].record()
+        ev_acc[i][0].record()
+        hb.hb_tree_accept(desc.batch, desc.max_nodes_per_tree, dv.node_offset, dv.parent, step.draft_ids,
+                          step.target_ids, step.max_path, step.accept_len, step.accept_path, step.out_tokens,
+                          step.bonus)
+        ev_acc[i][1].record()
+        ev_cmp[i][0].record()
+        hb.hb_kv_compact(desc, dv.k_tree, dv.v_tree, dv.k_pool, dv.v_pool, dv.block_table, dv.prefix_len,
+                         dv.node_offset, step.accept_len, step.accept_path, step.max_path, step.out_slots,
+                         step.new_len)
+        ev_cmp[i][1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    ms_attn, ms_lm, ms_acc, ms_cmp = map(_mean_ms, (ev_attn, ev_lm, ev_acc, ev_cmp))
+    accept_len = step.accept_len.cpu().numpy()
+    assert list(accept_len) == [d + 1 for d in planted], "accepted lengths differ from the planted paths"
+
+    M = inp.total_nodes
+    lm_flops = 2.0 * M * K * V
+    lm_tflops = lm_flops / (ms_lm * 1e-3) / 1e12
+    kv_bytes = inp.kv_bytes()
+    result = {
+        "metric": "verified tree-tokens/sec per verify step",
+        "value": M / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{inp.name}: batch 16, ragged prefixes in [1024, 4096] (sum {int(inp.prefix_len.sum())}), "
+                        f"28 q / 4 kv heads, head_dim 128, paged bf16 KV (page 16, permuted), "
+                        f"{'60-node depth-6 trees' if args.tree == 'tree' else '8-node chains'} "
+                        f"({M} nodes), 1 attention layer, LM head 3584 x 152064 with fused argmax, "
+                        f"greedy acceptance, KV compaction",
+            "tree": args.tree, "tree_nodes": M, "layers": 1,
+            "mean_accept_len": float(accept_len.mean()),
+        },
+        "roofline": {
+            "kernel": "lmhead_argmax",
+            "bound": "mfma" if M >= 512 else "hbm",
+            "achieved": lm_tflops if M >= 512 else (V * K * 2 + M * K * 2) / (ms_lm * 1e-3) / 1e9,
+            "peak": PEAK_BF16_TFLOPS if M >= 512 else PEAK_HBM_GBS,
+            "unit": "TFLOP/s" if M >= 512 else "GB/s",
+            "frac": (lm_tflops / PEAK_BF16_TFLOPS) if M >= 512
+            else (V * K * 2 + M * K * 2) / (ms_lm * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "traffic": None,
+            "ms": ms_lm,
+        },
+        "kernels_ms": {"tree_verify_attn": ms_attn, "lmhead_argmax": ms_lm, "tree_accept": ms_acc,
+                       "kv_compact": ms_cmp},
+        "kv_read": {
+            "bytes": kv_bytes, "GBps": kv_bytes / (ms_attn * 1e-3) / 1e9,
+            "frac_of_hbm_peak": kv_bytes / (ms_attn * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "attn_splits": hb.hb_tree_verify_attn_num_splits(desc),
+        },
+    }
+    if not args.no_attn_extra and args.tree == "tree":
+        del step, wdev
+        torch.cuda.empty_cache()
+        result["attention_only"] = [bench_attention_only(c, max(args.steps, 20), args.warmup) for c in (2, 3)]
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(inp, weight, draft_np)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
