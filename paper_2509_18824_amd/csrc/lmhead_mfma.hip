@@ -1,8 +1,233 @@
+// LM head with fused argmax on the bf16 matrix cores of gfx950.
+//
+// Computes C^T[v, m] = sum_k W[v, k] * H[m, k] tile by tile and never stores it: the weight
+// rows are the MFMA "A" operand and the hidden rows the "B" operand, so that one lane's
+// accumulators of a 32x32 tile all belong to ONE hidden row m and 16 different vocabulary
+// entries v.  The row-wise argmax is then an in-register scan, one exchange between the two
+// lane halves, and one 64-bit atomic max per (row, workgroup).
+//
+// Workgroup: 256 threads = 4 wavefronts in a 2 (v) x 2 (m) arrangement; workgroup tile
+// TV = 256 vocabulary rows x TM = 64 * MT hidden rows, K step 64.  Both operands are
+// K-contiguous in memory ([V, K] and [M, K] row-major), which is exactly what the MFMA operand
+// layout wants (8 consecutive k per lane), so tiles go global -> registers -> LDS as 16-byte
+// pieces, XOR-swizzled so that the 16-byte operand reads of 8 consecutive rows hit all banks.
+// LDS is double buffered: the global loads of K step t+1 are issued before the MFMAs of step t
+// and written to the other buffer afterwards; one barrier per K step.
+//
+// Grid order: consecutive workgroup ids go to different XCDs (id % 8).  The m tiles of one v
+// tile are given ids 8 apart, i.e. consecutive slots of the same XCD, so they run together and
+// the weight tile they share is fetched from HBM once and hit in that XCD's L2 afterwards.
 #include "hb_internal.h"
+
 namespace hb {
-bool lmhead_mfma_supports(int32_t, int32_t, int32_t, int32_t) { return false; }
-hipError_t launch_lmhead_mfma(int32_t, int32_t, int32_t, const void *, const void *, unsigned long long *,
-                              hipStream_t) {
-  return hipErrorNotSupported;
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;           // k per step
+constexpr int TV = 256;          // vocabulary rows per workgroup
+constexpr int CH = BK / 8;       // 16-byte pieces per row per step (8)
+constexpr int kXcds = 8;
+
+// Offset (in 16-byte pieces) of piece `c` of row `r` in a swizzled [rows][8] tile.  Rows are
+// 128 bytes; the XOR spreads the same logical piece of 8 consecutive rows, and of 8 consecutive
+// rows of equal parity, over distinct 16-byte bank groups, which keeps the operand reads
+// (lanes = consecutive rows, one piece each) conflict free for 128- and 256-byte wide LDS.
+__device__ inline int swz(int r, int c) { return r * CH + (c ^ ((r & 7) ^ ((r >> 3) & 1))); }
+
+template <int MT>  // 32-row hidden tiles per wavefront (workgroup covers TM = 64 * MT rows)
+__global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles,
+                                                          const uint4 *__restrict__ hidden,
+                                                          const uint4 *__restrict__ weight,
+                                                          unsigned long long *__restrict__ keys) {
+  constexpr int TM = 64 * MT;
+  constexpr int W_PIECES = TV * CH / 256;  // 16-byte pieces of the weight tile per thread (8)
+  constexpr int H_PIECES = TM * CH / 256;  // same for the hidden tile (2 * MT)
+  extern __shared__ uint4 lds[];           // [2][TV*CH] weight, then [2][TM*CH] hidden
+  uint4 *lw = lds;
+  uint4 *lh = lds + 2 * TV * CH;
+  __shared__ unsigned long long row_key[2][TM];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wv = wave >> 1;  // which 128 vocabulary rows of the tile
+  const int wm = wave & 1;   // which 32*MT hidden rows of the tile
+
+  // XCD-aware tile order
+  const int id = blockIdx.x;
+  const int xcd = id % kXcds;
+  const int slot = id / kXcds;
+  const int m_tile = slot % m_tiles;
+  const int v_tile = (slot / m_tiles) * kXcds + xcd;
+  if (v_tile >= v_tiles) return;
+  const int v0 = v_tile * TV;
+  const int m0 = m_tile * TM;
+  const int kp = K / 8;  // 16-byte pieces per matrix row (K % 8 == 0)
+
+  // per-thread global source rows for the staging loads (rows past the end are clamped; their
+  // results are dropped in the epilogue)
+  const int piece = tid & 7;   // piece within the 64-k step
+  const int row_in = tid >> 3; // 0..31
+  const uint4 *w_src[W_PIECES];
+  const uint4 *h_src[H_PIECES];
+#pragma unroll
+  for (int i = 0; i < W_PIECES; ++i) {
+    int r = v0 + row_in + 32 * i;
+    r = r < V ? r : V - 1;
+    w_src[i] = weight + (size_t)r * kp + piece;
+  }
+#pragma unroll
+  for (int i = 0; i < H_PIECES; ++i) {
+    int r = m0 + row_in + 32 * i;
+    r = r < M ? r : M - 1;
+    h_src[i] = hidden + (size_t)r * kp + piece;
+  }
+
+  f32x16 acc[4][MT];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < MT; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  uint4 wreg[W_PIECES], hreg[H_PIECES];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  const int k_steps = (K + BK - 1) / BK;
+
+#define HB_LOAD_GLOBAL(kt_)                                                        \
+  {                                                                               \
+    const int p0 = (kt_) * CH;                                                    \
+    if (p0 + piece < kp) { /* pieces past K contribute zeros */                   \
+      _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i) wreg[i] = w_src[i][p0]; \
+      _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i) hreg[i] = h_src[i][p0]; \
+    } else {                                                                      \
+      _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i) wreg[i] = zero4;        \
+      _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i) hreg[i] = zero4;        \
+    }                                                                             \
+  }
+#define HB_STORE_LDS(buf_)                                                                       \
+  {                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i)                                          \
+        lw[(buf_) * TV * CH + swz(row_in + 32 * i, piece)] = wreg[i];                            \
+    _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i)                                          \
+        lh[(buf_) * TM * CH + swz(row_in + 32 * i, piece)] = hreg[i];                            \
+  }
+
+  HB_LOAD_GLOBAL(0);
+  HB_STORE_LDS(0);
+  __syncthreads();
+
+  const int frag_row = lane & 31;
+  const int frag_half = lane >> 5;
+  for (int kt = 0; kt < k_steps; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < k_steps) HB_LOAD_GLOBAL(kt + 1);
+    const uint4 *cw = lw + buf * TV * CH;
+    const uint4 *chh = lh + buf * TM * CH;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int c = ks * 2 + frag_half;  // this lane's 8-k piece of the 16-k MFMA step
+      bf16x8 a[4], b[MT];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        uint4 t = cw[swz(wv * 128 + i * 32 + frag_row, c)];
+        a[i] = __builtin_bit_cast(bf16x8, t);
+      }
+#pragma unroll
+      for (int j = 0; j < MT; ++j) {
+        uint4 t = chh[swz(wm * 32 * MT + j * 32 + frag_row, c)];
+        b[j] = __builtin_bit_cast(bf16x8, t);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < k_steps) HB_STORE_LDS(buf ^ 1);
+    __syncthreads();
+  }
+
+#undef HB_LOAD_GLOBAL
+#undef HB_STORE_LDS
+
+  // Epilogue.  Accumulator r of lane l in tile (i, j) is C^T[v, m] with
+  //   v = v0 + wv*128 + i*32 + 8*(r/4) + 4*(l/32) + r%4,   m = m0 + wm*32*MT + j*32 + l%32.
+  // Scanning (i, r) in order visits v in increasing order, so a strict '>' keeps the lowest v
+  // among equal values; NaN compares false and never wins.
+#pragma unroll
+  for (int j = 0; j < MT; ++j) {
+    float best = -__builtin_huge_valf();
+    int best_v = -1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int v = v0 + wv * 128 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        float x = acc[i][j][r];
+        bool take = (v < V) && (x > best);
+        best = take ? x : best;
+        best_v = take ? v : best_v;
+      }
+    // a lane that saw nothing above -inf offers no candidate (key 0 loses to every real key)
+    unsigned long long key = best_v >= 0 ? argmax_key(best, (uint32_t)best_v) : 0ull;
+    unsigned long long other = __shfl_xor(key, 32, 64);
+    key = other > key ? other : key;
+    if (lane < 32) row_key[wv][wm * 32 * MT + j * 32 + lane] = key;
+  }
+  __syncthreads();
+  for (int r = tid; r < TM; r += 256) {
+    int m = m0 + r;
+    if (m >= M) continue;
+    unsigned long long key = row_key[0][r] > row_key[1][r] ? row_key[0][r] : row_key[1][r];
+    // skip the atomic when the row already holds something at least as good
+    if (key > __atomic_load_n(&keys[m], __ATOMIC_RELAXED)) atomicMax(&keys[m], key);
+  }
 }
+
+template <int MT>
+hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, unsigned long long *keys,
+                  hipStream_t s) {
+  constexpr int TM = 64 * MT;
+  int m_tiles = (M + TM - 1) / TM;
+  int v_tiles = (V + TV - 1) / TV;
+  int v_groups = (v_tiles + kXcds - 1) / kXcds;
+  size_t lds_bytes = (size_t)2 * (TV + TM) * CH * sizeof(uint4);
+  auto kern = lmhead_mfma_kernel<MT>;
+  hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (e != hipSuccess) return e;
+  dim3 grid((unsigned)(v_groups * m_tiles * kXcds));
+  kern<<<grid, 256, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const uint4 *)hidden, (const uint4 *)weight, keys);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool lmhead_mfma_supports(int32_t dtype, int32_t M, int32_t K, int32_t V) {
+  return dtype == HB_BF16 && K % 8 == 0 && M >= 1 && V >= 1;
+}
+
+hipError_t launch_lmhead_mfma(int32_t M, int32_t K, int32_t V, const void *hidden, const void *weight,
+                              unsigned long long *keys, hipStream_t s) {
+  // hidden tile height: the multiple of 64 (up to 256) that wastes the fewest padded rows,
+  // preferring the taller tile on ties (fewer re-reads of the weight tile)
+  int best_mt = 4;
+  long best_rows = -1;
+  for (int mt = 4; mt >= 1; --mt) {
+    int tm = 64 * mt;
+    long rows = (long)((M + tm - 1) / tm) * tm;
+    if (best_rows < 0 || rows < best_rows) { best_rows = rows; best_mt = mt; }
+  }
+  switch (best_mt) {
+    case 1: return launch<1>(M, K, V, hidden, weight, keys, s);
+    case 2: return launch<2>(M, K, V, hidden, weight, keys, s);
+    case 3: return launch<3>(M, K, V, hidden, weight, keys, s);
+    default: return launch<4>(M, K, V, hidden, weight, keys, s);
+  }
+}
+
 }  // namespace hb
