@@ -1,9 +1,465 @@
+// Tree-verify attention on the bf16 matrix cores of gfx950 (head_dim 128, page size 16).
+//
+// One workgroup (4 wavefronts) owns one (sequence, kv head, KV chunk).  Every KV tile it
+// streams from HBM is staged once in LDS and used by ALL query rows that share it: the rows of
+// every tree node and of every query head of the kv group (N * G rows, 420 for 60 nodes and
+// GQA 7:1), which is what turns the memory-bound decode step into a compute-dense one.
+//
+// Formulation (transposed, so no score ever crosses lanes on its way into the second GEMM):
+//   S^T = K Q^T     MFMA 16x16x32: A = K tile (16 keys x 32 d), B = Q^T (32 d x 16 rows)
+//   O^T = V^T P^T   MFMA 16x16x32: A = V^T (16 d x 32 keys),    B = P^T (32 keys x 16 rows)
+// The S^T accumulator of lane l holds, for query row l%16, the four keys 4*(l/16)+r of a 16-key
+// tile; two such tiles give the eight k-slots that the same lane must supply as the B operand
+// of the second MFMA, provided V^T is laid out in LDS with the matching key permutation.
+// Softmax is online per row in base 2 (scores scaled by softmax_scale*log2 e); the running
+// maximum is shared by the four lane groups of a row (two cross-lane exchanges per 32 keys),
+// row sums stay per lane until the end, and the accumulator is rescaled only when some row's
+// maximum actually moved.
+//
+// Rows: row r = node * G + head_in_group, tiles of 16 rows, tile T belongs to wavefront T % 4;
+// Q fragments and the fp32 O^T accumulators of a wavefront's (at most TPW) tiles live in
+// registers for the whole kernel.
+//
+// Keys: chunk 0 starts with one 64-key tile holding the tree nodes (masked per row by the
+// node's ancestor bitmask), then every chunk streams its share of the prefix through the page
+// table in 64-key tiles, double buffered: global loads of tile i+1 are issued before the MFMAs
+// of tile i and written to the other LDS buffer afterwards.
 #include "hb_internal.h"
+
 namespace hb {
-bool attn_mfma_supports(const hb_attn_desc &) { return false; }
-hipError_t launch_attn_mfma(const hb_attn_desc &, const AttnPlan &, const void *, const void *, const void *,
-                            const void *, const void *, const int32_t *, const int32_t *, const int32_t *,
-                            const int32_t *, void *, float *, float *, float *, hipStream_t) {
-  return hipErrorNotSupported;
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int D = 128;
+constexpr int PAGE = 16;
+constexpr int KT = 64;                 // keys per tile
+constexpr int K_PIECES = KT * 16;      // 16-byte pieces of a K tile (16 per key row)
+constexpr int V_BYTES = 2 * D * 64;    // V^T tile: 2 blocks of 32 keys x 128 d x 64 bytes
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+#define HB_NEG_INF (-__builtin_huge_valf())
+
+__device__ __forceinline__ uint32_t finite_or_zero_bf16x2(uint32_t w) {
+  // a bf16 is non-finite iff its exponent field is all ones
+  uint32_t lo = ((w & 0x7f80u) == 0x7f80u) ? 0u : (w & 0xffffu);
+  uint32_t hi = ((w & 0x7f800000u) == 0x7f800000u) ? 0u : (w & 0xffff0000u);
+  return lo | hi;
 }
+
+// Where one thread's pieces of a 64-key tile come from.  A tile holds either tree nodes (keys =
+// node ids < n_nodes, read from k_tree/v_tree) or prefix positions tile_start + key < end (read
+// through the page table).  Slots that are not valid keys are loaded as zeros: they are masked
+// in the scores, and a zero V keeps 0 * V finite.
+struct TileSrc {
+  const u32x4 *k_tree, *v_tree, *k_pool, *v_pool;
+  const int32_t *bt;  // page table row of the sequence
+  int g, n0, n_nodes, hkv, num_blocks;
+};
+
+// K: piece (tid % 16) of key tid/16 + 16*i
+__device__ __forceinline__ u32x4 load_k_piece(const TileSrc &s, bool tree_tile, int tile_start, int end,
+                                              int tid, int i) {
+  const int piece = tid & 15;
+  const int key = (tid >> 4) + 16 * i;
+  u32x4 x = {0u, 0u, 0u, 0u};
+  if (tree_tile) {
+    if (key < s.n_nodes) x = s.k_tree[((size_t)(s.n0 + key) * s.hkv + s.g) * 16 + piece];
+  } else {
+    int pos = tile_start + key;
+    if (pos < end) {
+      int blk = s.bt[pos / PAGE];
+      blk = blk < 0 ? 0 : (blk >= s.num_blocks ? s.num_blocks - 1 : blk);
+      x = s.k_pool[(((size_t)blk * s.hkv + s.g) * PAGE + (pos % PAGE)) * 16 + piece];
+    }
+  }
+  return x;
+}
+
+// V: d-piece (tid % 16) of key 4*(tid/16) + i
+__device__ __forceinline__ u32x4 load_v_piece(const TileSrc &s, bool tree_tile, int tile_start, int end,
+                                              int tid, int i) {
+  const int piece = tid & 15;
+  const int key = 4 * (tid >> 4) + i;
+  u32x4 x = {0u, 0u, 0u, 0u};
+  if (tree_tile) {
+    if (key < s.n_nodes) {
+      x = s.v_tree[((size_t)(s.n0 + key) * s.hkv + s.g) * 16 + piece];
+      // tree nodes off a row's path get probability 0; their V must not turn 0 * V into NaN
+      x[0] = finite_or_zero_bf16x2(x[0]);
+      x[1] = finite_or_zero_bf16x2(x[1]);
+      x[2] = finite_or_zero_bf16x2(x[2]);
+      x[3] = finite_or_zero_bf16x2(x[3]);
+    }
+  } else {
+    int pos = tile_start + key;
+    if (pos < end) {
+      int blk = s.bt[pos / PAGE];
+      blk = blk < 0 ? 0 : (blk >= s.num_blocks ? s.num_blocks - 1 : blk);
+      x = s.v_pool[(((size_t)blk * s.hkv + s.g) * PAGE + (pos % PAGE)) * 16 + piece];
+    }
+  }
+  return x;
+}
+
+// Registers -> LDS, K.  Rows keep their layout ([key][16 pieces]); the piece index is XORed with
+// the key so that the operand reads of 16 consecutive keys are conflict free.
+__device__ __forceinline__ void store_k(u32x4 *__restrict__ lk, int tid, u32x4 k0, u32x4 k1, u32x4 k2, u32x4 k3) {
+  const int piece = tid & 15;
+  const int krow = tid >> 4;
+  lk[(krow + 0) * 16 + (piece ^ krow)] = k0;   // (krow + 16 i) & 15 == krow
+  lk[(krow + 16) * 16 + (piece ^ krow)] = k1;
+  lk[(krow + 32) * 16 + (piece ^ krow)] = k2;
+  lk[(krow + 48) * 16 + (piece ^ krow)] = k3;
+}
+
+// Registers -> LDS, V, transposed on the way.  Per d row (64 bytes, row index XORed in its low
+// two bits to spread the writes) the 32 keys of a block are stored in the order
+// (key%16)/4, key/16, key%4, so that the eight keys lane group kg needs as MFMA k-slots are the
+// 16 contiguous bytes at offset 16*kg.
+__device__ __forceinline__ void store_v(unsigned char *__restrict__ lv, int tid, u32x4 v0, u32x4 v1, u32x4 v2,
+                                        u32x4 v3) {
+  const int piece = tid & 15;
+  const int q = tid >> 4;                   // key quad: keys 4q .. 4q+3
+  const int blk32 = q >> 3;                 // which 32-key block
+  const int a = (q & 7) >> 2, kg = q & 3;   // key = 32*blk32 + 16*a + 4*kg + c
+  unsigned char *base = lv + blk32 * (D * 64) + 16 * kg + 8 * a;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    // even d = 8*piece + 2p: low halves; odd d: high halves
+    u32x2 even = {(v0[p] & 0xffffu) | (v1[p] << 16), (v2[p] & 0xffffu) | (v3[p] << 16)};
+    u32x2 odd = {(v0[p] >> 16) | (v1[p] & 0xffff0000u), (v2[p] >> 16) | (v3[p] & 0xffff0000u)};
+    int d0 = 8 * piece + 2 * p, d1 = d0 + 1;
+    int r0 = d0 ^ ((d0 >> 3) & 3), r1 = d1 ^ ((d1 >> 3) & 3);
+    *(u32x2 *)(base + r0 * 64) = even;
+    *(u32x2 *)(base + r1 * 64) = odd;
+  }
+}
+
+// 2^x by the hardware instruction: arguments here are <= 0 and results below the normal range
+// may flush to zero, which is what a vanishing softmax weight should do.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float group_max(float x) {
+  // lanes l, l^16, l^32, l^48 hold the four key groups of one query row
+  x = fmaxf(x, __shfl_xor(x, 16, 64));
+  return fmaxf(x, __shfl_xor(x, 32, 64));
+}
+__device__ __forceinline__ float group_sum(float x) {
+  x += __shfl_xor(x, 16, 64);
+  return x + __shfl_xor(x, 32, 64);
+}
+
+template <int TPW>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(
+    hb_attn_desc d, int splits, int chunk_tokens, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
+    const u32x4 *__restrict__ v_tree, const u32x4 *__restrict__ k_pool, const u32x4 *__restrict__ v_pool,
+    const int32_t *__restrict__ block_table, const int32_t *__restrict__ prefix_len,
+    const int32_t *__restrict__ node_offset, const int32_t *__restrict__ parent, bf16_t *__restrict__ out,
+    float *__restrict__ lse, float *__restrict__ part_o, float *__restrict__ part_ml) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // [2][K tile 16 KiB] [2][V^T tile 16 KiB] [64 ancestor masks]
+  u32x4 *lds_k = (u32x4 *)smem;
+  unsigned char *lds_v = smem + 2 * K_PIECES * 16;
+  unsigned long long *anc_lds = (unsigned long long *)(smem + 2 * K_PIECES * 16 + 2 * V_BYTES);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int G = d.num_q_heads / d.num_kv_heads;
+  const int n0 = node_offset[b];
+  int n_nodes = node_offset[b + 1] - n0;
+  n_nodes = n_nodes < 0 ? 0 : (n_nodes > d.max_nodes_per_tree ? d.max_nodes_per_tree : n_nodes);
+  if (n0 < 0 || n0 + n_nodes > d.total_nodes) n_nodes = 0;  // malformed offsets: touch nothing
+  const int R = n_nodes * G;           // query rows of this (sequence, kv head)
+  const int NT = (R + 15) >> 4;        // 16-row tiles; tile T -> wavefront T % 4
+  int L = prefix_len[b];
+  const int cap = d.max_blocks_per_seq * PAGE;
+  L = L < 0 ? 0 : (L > cap ? cap : L);
+
+  // chunks of this sequence: as many as the plan allows, but never shorter than needed
+  int n_chunks = (L + chunk_tokens - 1) / chunk_tokens;
+  n_chunks = n_chunks < 1 ? 1 : (n_chunks > splits ? splits : n_chunks);
+  int chunk = ((L + n_chunks - 1) / n_chunks + KT - 1) / KT * KT;
+  chunk = chunk < KT ? KT : chunk;
+  const int begin = c * chunk;
+  const int end = min(L, begin + chunk);
+  const bool tree_chunk = (c == 0);
+  if (R == 0) return;
+
+  const int j = lane & 15;    // query row within a tile
+  const int kg = lane >> 4;   // key group / k-slot group of this lane
+  const size_t row_base = (size_t)n0 * d.num_q_heads + (size_t)g * G;  // + node*Hq + head_in_group
+
+  if (!tree_chunk && begin >= L) {
+    // an empty chunk only announces itself to the merge
+    for (int r = tid; r < R; r += 256) {
+      size_t rg = row_base + (size_t)(r / G) * d.num_q_heads + (r % G);
+      part_ml[(rg * splits + c) * 2 + 0] = HB_NEG_INF;
+      part_ml[(rg * splits + c) * 2 + 1] = 0.f;
+    }
+    return;
+  }
+
+  if (tree_chunk && tid < 64) {
+    unsigned long long anc = 0ull;
+    if (tid < n_nodes) {
+      anc = 1ull << tid;
+      int x = tid;
+      for (int guard = 0; guard < 64; ++guard) {
+        int px = parent[n0 + x];
+        if (px < 0 || px >= x) break;  // root reached (or malformed parent: stop)
+        anc |= 1ull << px;
+        x = px;
+      }
+    }
+    anc_lds[tid] = anc;
+  }
+
+  // ---- Q fragments (B operand of S^T = K Q^T), kept for the whole kernel -------------------
+  bf16x8 qf[TPW][4];
+  int node_of[TPW];  // tree node of this lane's row in each of the wavefront's tiles
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    int row = (wave + 4 * t) * 16 + j;
+    bool ok = row < R;
+    int node = ok ? row / G : 0;
+    int hg = ok ? row - node * G : 0;
+    node_of[t] = node;
+    const u32x4 *src = q + (row_base + (size_t)node * d.num_q_heads + hg) * 16;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4 x = {0u, 0u, 0u, 0u};
+      if (ok) x = src[4 * ks + kg];
+      qf[t][ks] = __builtin_bit_cast(bf16x8, x);
+    }
+  }
+
+  f32x4 o[TPW][8];
+  float m_run[TPW], l_run[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    m_run[t] = HB_NEG_INF;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[t][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+  const float c1 = d.softmax_scale * kLog2e;
+
+  // tiles: [tree tile] + prefix tiles of this chunk
+  const int n_prefix_tiles = end > begin ? (end - begin + KT - 1) / KT : 0;
+  const int n_tiles = n_prefix_tiles + (tree_chunk ? 1 : 0);
+
+  TileSrc src;
+  src.k_tree = k_tree; src.v_tree = v_tree; src.k_pool = k_pool; src.v_pool = v_pool;
+  src.bt = block_table + (size_t)b * d.max_blocks_per_seq;
+  src.g = g; src.n0 = n0; src.n_nodes = n_nodes; src.hkv = d.num_kv_heads; src.num_blocks = d.num_blocks;
+
+  u32x4 sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3;
+#define HB_STAGE_LOAD(tree_, start_)                            \
+  {                                                             \
+    sk0 = load_k_piece(src, tree_, start_, end, tid, 0);        \
+    sk1 = load_k_piece(src, tree_, start_, end, tid, 1);        \
+    sk2 = load_k_piece(src, tree_, start_, end, tid, 2);        \
+    sk3 = load_k_piece(src, tree_, start_, end, tid, 3);        \
+    sv0 = load_v_piece(src, tree_, start_, end, tid, 0);        \
+    sv1 = load_v_piece(src, tree_, start_, end, tid, 1);        \
+    sv2 = load_v_piece(src, tree_, start_, end, tid, 2);        \
+    sv3 = load_v_piece(src, tree_, start_, end, tid, 3);        \
+  }
+#define HB_STAGE_STORE(buf_)                                     \
+  {                                                              \
+    store_k(lds_k + (buf_) * K_PIECES, tid, sk0, sk1, sk2, sk3); \
+    store_v(lds_v + (buf_) * V_BYTES, tid, sv0, sv1, sv2, sv3);  \
+  }
+
+  HB_STAGE_LOAD(tree_chunk, begin);
+  HB_STAGE_STORE(0);
+  __syncthreads();
+
+  for (int i = 0; i < n_tiles; ++i) {
+    const int buf = i & 1;
+    const bool is_tree = tree_chunk && i == 0;
+    const int tile_start = begin + (i - (tree_chunk ? 1 : 0)) * KT;  // prefix position of key 0
+    if (i + 1 < n_tiles) HB_STAGE_LOAD(false, tile_start + KT);      // the next tile is a prefix tile
+    const int n_valid = is_tree ? n_nodes : min(KT, end - tile_start);  // keys of this tile that exist
+    const u32x4 *lk = lds_k + buf * K_PIECES;
+    const unsigned char *lv = lds_v + buf * V_BYTES;
+
+#pragma unroll
+    for (int blk32 = 0; blk32 < 2; ++blk32) {
+      const bool partial = (32 * blk32 + 32 > n_valid) || is_tree;  // uniform
+      bf16x8 pb[TPW];
+      {
+        // K fragments of the block's two 16-key halves, shared by all row tiles of the wavefront
+        bf16x8 ak[2][4];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            int key = 32 * blk32 + 16 * a + j;
+            ak[a][ks] = __builtin_bit_cast(bf16x8, lk[key * 16 + ((4 * ks + kg) ^ j)]);
+          }
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+          f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][ks], qf[t][ks], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][ks], qf[t][ks], s1, 0, 0, 0);
+          }
+          float sc[8];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            sc[r] = s0[r] * c1;
+            sc[4 + r] = s1[r] * c1;
+          }
+          if (partial) {
+            // key of slot (a, r): 32*blk32 + 16*a + 4*kg + r; select, so NaN/Inf scores of
+            // forbidden keys vanish
+            uint32_t allow = ~0u;  // bit k: key 32*blk32 + k may be seen by this lane's row
+            if (is_tree) allow = (uint32_t)(anc_lds[node_of[t]] >> (32 * blk32));
+            int left = n_valid - 32 * blk32;  // keys of this block that exist
+            allow &= left >= 32 ? ~0u : ((1u << (left < 0 ? 0 : left)) - 1u);
+            allow >>= 4 * kg;
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                sc[4 * a + r] = ((allow >> (16 * a + r)) & 1u) ? sc[4 * a + r] : HB_NEG_INF;
+          }
+          float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
+                           fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+          mx = group_max(mx);
+          const float m_old = m_run[t];
+          const float m_new = fmaxf(m_old, mx);
+          if (__any(m_new > m_old)) {
+            // some row's maximum moved: rescale (rows whose maximum stayed get alpha = 1).
+            // The empty asm keeps this rare path a real branch instead of an unconditional
+            // multiply of the whole accumulator.
+            asm volatile("" ::: "memory");
+            float alpha = (m_old == HB_NEG_INF) ? 0.f : fast_exp2(m_old - m_new);
+            l_run[t] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) o[t][dt] *= alpha;
+            m_run[t] = m_new;
+          }
+          // every row has seen at least one allowed key by now (the first key of a prefix
+          // chunk, the root of the tree), so m_new is finite
+          f32x8 p;
+          float psum = 0.f;
+#pragma unroll
+          for (int r = 0; r < 8; ++r) {
+            p[r] = fast_exp2(sc[r] - m_new);
+            psum += p[r];
+          }
+          l_run[t] += psum;
+          pb[t] = __builtin_convertvector(p, bf16x8);
+          __builtin_amdgcn_sched_barrier(0);  // keep one row tile's softmax temporaries live at a time
+        }
+      }
+      // O^T += V^T P^T, one 16-d slab of V^T at a time for all row tiles
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        int dd = 16 * dt + j;
+        int rr = dd ^ ((dd >> 3) & 3);
+        bf16x8 av = __builtin_bit_cast(bf16x8, *(const u32x4 *)(lv + blk32 * (D * 64) + rr * 64 + 16 * kg));
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+          o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], o[t][dt], 0, 0, 0);
+        }
+        if (dt & 1) __builtin_amdgcn_sched_barrier(0);  // at most two V^T slabs in flight
+      }
+    }
+
+    if (i + 1 < n_tiles) HB_STAGE_STORE(buf ^ 1);
+    __syncthreads();
+  }
+#undef HB_STAGE_LOAD
+#undef HB_STAGE_STORE
+
+  // ---- write out: lane (j, kg) holds O[row j][16*dt + 4*kg + r] ---------------------------
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    int row = (wave + 4 * t) * 16 + j;
+    if ((wave + 4 * t) >= NT) continue;
+    float l_tot = group_sum(l_run[t]);
+    if (row >= R) continue;
+    int node = row / G, hg = row - node * G;
+    size_t rg = row_base + (size_t)node * d.num_q_heads + hg;
+    if (splits == 1) {
+      float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        u32x2 w;
+        w[0] = (uint32_t)f32_to_bf16(o[t][dt][0] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][1] * inv) << 16);
+        w[1] = (uint32_t)f32_to_bf16(o[t][dt][2] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][3] * inv) << 16);
+        *(u32x2 *)(out + rg * D + 16 * dt + 4 * kg) = w;
+      }
+      if (lse && kg == 0) lse[rg] = (m_run[t] + log2f(l_tot)) * kLn2;
+    } else {
+      float *po = part_o + (rg * splits + c) * D;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) *(f32x4 *)(po + 16 * dt + 4 * kg) = o[t][dt];
+      if (kg == 0) {
+        part_ml[(rg * splits + c) * 2 + 0] = m_run[t] * kLn2;  // natural-log units for the merge
+        part_ml[(rg * splits + c) * 2 + 1] = l_tot;
+      }
+    }
+  }
+}
+
+constexpr size_t kLdsBytes = 2 * K_PIECES * 16 + 2 * V_BYTES + 64 * 8;
+
+template <int TPW>
+hipError_t launch(const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
+                  const void *v_tree, const void *k_pool, const void *v_pool, const int32_t *block_table,
+                  const int32_t *prefix_len, const int32_t *node_offset, const int32_t *parent, void *out,
+                  float *lse, float *part_o, float *part_ml, hipStream_t s) {
+  dim3 grid((unsigned)plan.splits, (unsigned)d.num_kv_heads, (unsigned)d.batch);
+  auto kern = attn_mfma_kernel<TPW>;
+  hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+  if (e != hipSuccess) return e;
+  kern<<<grid, 256, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, (const u32x4 *)q, (const u32x4 *)k_tree,
+                                    (const u32x4 *)v_tree, (const u32x4 *)k_pool, (const u32x4 *)v_pool,
+                                    block_table, prefix_len, node_offset, parent, (bf16_t *)out, lse, part_o,
+                                    part_ml);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_mfma_supports(const hb_attn_desc &d) {
+  if (d.dtype != HB_BF16 || d.head_dim != D || d.page_size != PAGE) return false;
+  if (d.num_kv_heads <= 0 || d.num_q_heads % d.num_kv_heads) return false;
+  int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
+  if (d.max_nodes_per_tree > 64 || rows > 448) return false;
+  if (!(d.softmax_scale > 0.f) || !(d.softmax_scale < 1e30f)) return false;  // base-2 max tracking needs scale > 0
+  if (d.batch > 65535 || d.num_kv_heads > 65535) return false;
+  return true;
+}
+
+hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
+                            const void *v_tree, const void *k_pool, const void *v_pool,
+                            const int32_t *block_table, const int32_t *prefix_len,
+                            const int32_t *node_offset, const int32_t *parent, void *out, float *lse,
+                            float *part_o, float *part_ml, hipStream_t s) {
+  int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
+  int tiles = (rows + 15) / 16;
+  int tpw = (tiles + 3) / 4;  // row tiles per wavefront
+#define HB_GO(N) \
+  return launch<N>(d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
+  if (tpw <= 1) HB_GO(1);
+  if (tpw <= 2) HB_GO(2);
+  if (tpw <= 4) HB_GO(4);
+  HB_GO(7);
+#undef HB_GO
+}
+
 }  // namespace hb

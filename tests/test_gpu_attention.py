@@ -39,6 +39,15 @@ def _algos(hb, inp):
     return algos
 
 
+def test_matrix_core_kernel_takes_the_bf16_workloads(hb, step):
+    """The workloads with bf16 KV, head_dim 128 and page 16 must run on the MFMA kernel, both when
+    asked for explicitly and by default (so the parity tests below really cover it)."""
+    for cfg in (1, 2, 3, 4):
+        inp = W.make_config(cfg, scale_down=32)
+        assert hb.HB_ATTN_MFMA in _algos(hb, inp)
+    assert hb.HB_ATTN_MFMA not in _algos(hb, W.make_config(0))
+
+
 def test_config0_fp32_chain(hb, step):
     for peaked in (False, True):
         inp = W.make_config(0, peaked=peaked)
