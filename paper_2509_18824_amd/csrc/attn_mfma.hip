@@ -155,6 +155,115 @@ __device__ __forceinline__ float group_sum(float x) {
   return x + __shfl_xor(x, 32, 64);
 }
 
+// One 32-key block of the current tile against all row tiles of the wavefront.
+//   partial (uniform): some keys of the block do not exist or are masked (chunk tail, tree tile).
+// Row tiles are taken in groups of at most four: scores and softmax for the group (VALU work,
+// QK^T on the matrix cores), then the group's O^T += V^T P^T.  The second product is issued as
+// inline assembly with the accumulator tied in place in the accumulation registers: the fp32
+// O^T of all tiles (224 registers for 7 tiles) never moves.
+template <int TPW>
+__device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restrict__ lk, const unsigned char *__restrict__ lv,
+                                             int blk32, int j, int kg, const bf16x8 (&qf)[TPW][4],
+                                             f32x4 (&o)[TPW][8], float (&m_run)[TPW], float (&l_run)[TPW],
+                                             float c1, int n_valid, bool is_tree, const unsigned long long *anc_lds,
+                                             int wave, int R, int G, f32x4 *fix_slot, uint32_t fix_addr) {
+  // K fragments of the block's two 16-key halves, shared by all row tiles of the wavefront
+  bf16x8 ak[2][4];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      int key = 32 * blk32 + 16 * a + j;
+      ak[a][ks] = __builtin_bit_cast(bf16x8, lk[key * 16 + ((4 * ks + kg) ^ j)]);
+    }
+#pragma unroll
+  for (int t0 = 0; t0 < TPW; t0 += 4) {
+    constexpr int kGroup = 4;
+    bf16x8 pb[kGroup];
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      const int t = t0 + u;
+      if (t >= TPW) break;
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][ks], qf[t][ks], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][ks], qf[t][ks], s1, 0, 0, 0);
+      }
+      float sc[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+      if (partial) {
+        // bit k of `allow`: key 32*blk32 + k exists and may be seen by this lane's row.  A select
+        // (not arithmetic) removes forbidden scores, so NaN/Inf there cannot leak.
+        uint32_t allow = ~0u;
+        if (is_tree) {
+          int row = (wave + 4 * t) * 16 + j;
+          int node = row < R ? row / G : 0;
+          allow = (uint32_t)(anc_lds[node] >> (32 * blk32));
+        }
+        int left = n_valid - 32 * blk32;
+        allow &= left >= 32 ? ~0u : ((1u << (left < 0 ? 0 : left)) - 1u);
+        allow >>= 4 * kg;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            sc[4 * a + r] = ((allow >> (16 * a + r)) & 1u) ? sc[4 * a + r] : HB_NEG_INF;
+      }
+      float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
+                       fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+      mx = group_max(mx) * c1;  // c1 > 0: scaling commutes with the maximum
+      const float m_old = m_run[t];
+      const float m_new = fmaxf(m_old, mx);
+      if (__any(m_new > m_old)) {
+        // Rare: some row's maximum moved, rescale this tile (rows whose maximum stayed get
+        // alpha = 1).  The accumulator lives in accumulation registers that ordinary vector
+        // instructions cannot address, so each 16x16 piece takes a round trip through a per-lane
+        // LDS slot.  The leading nops cover the distance an MFMA result needs before it may be
+        // read by a non-MFMA instruction.
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+        float alpha = (m_old == HB_NEG_INF) ? 0.f : fast_exp2(m_old - m_new);
+        l_run[t] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          asm volatile("ds_write_b128 %1, %0\n\ts_waitcnt lgkmcnt(0)" ::"a"(o[t][dt]), "v"(fix_addr) : "memory");
+          f32x4 tmp = *fix_slot;
+          tmp *= alpha;
+          *fix_slot = tmp;
+          asm volatile("s_waitcnt lgkmcnt(0)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                       : "+a"(o[t][dt])
+                       : "v"(fix_addr)
+                       : "memory");
+        }
+        m_run[t] = m_new;
+      }
+      // every row has seen at least one allowed key by now (the first key of a prefix chunk,
+      // the root of the tree), so m_new is finite
+      f32x8 p;
+      float psum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        p[r] = fast_exp2(fmaf(sc[r], c1, -m_new));
+        psum += p[r];
+      }
+      l_run[t] += psum;
+      pb[u] = __builtin_convertvector(p, bf16x8);
+    }
+    // O^T += V^T P^T for the group, one 16-d slab of V^T at a time
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      int dd = 16 * dt + j;
+      int rr = dd ^ ((dd >> 3) & 3);
+      bf16x8 av = __builtin_bit_cast(bf16x8, *(const u32x4 *)(lv + blk32 * (D * 64) + rr * 64 + 16 * kg));
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const int t = t0 + u;
+        if (t >= TPW) break;
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(o[t][dt]) : "v"(av), "v"(pb[u]));
+      }
+    }
+  }
+}
+
 template <int TPW>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(
     hb_attn_desc d, int splits, int chunk_tokens, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
@@ -163,10 +272,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     const int32_t *__restrict__ node_offset, const int32_t *__restrict__ parent, bf16_t *__restrict__ out,
     float *__restrict__ lse, float *__restrict__ part_o, float *__restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // [2][K tile 16 KiB] [2][V^T tile 16 KiB] [64 ancestor masks]
+  // [2][K tile 16 KiB] [2][V^T tile 16 KiB] [64 ancestor masks] [256 per-lane 16-byte slots]
   u32x4 *lds_k = (u32x4 *)smem;
   unsigned char *lds_v = smem + 2 * K_PIECES * 16;
   unsigned long long *anc_lds = (unsigned long long *)(smem + 2 * K_PIECES * 16 + 2 * V_BYTES);
+  f32x4 *fix_slot = (f32x4 *)(smem + 2 * K_PIECES * 16 + 2 * V_BYTES + 512) + threadIdx.x;
+  const uint32_t fix_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)fix_slot;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -178,7 +289,6 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   n_nodes = n_nodes < 0 ? 0 : (n_nodes > d.max_nodes_per_tree ? d.max_nodes_per_tree : n_nodes);
   if (n0 < 0 || n0 + n_nodes > d.total_nodes) n_nodes = 0;  // malformed offsets: touch nothing
   const int R = n_nodes * G;           // query rows of this (sequence, kv head)
-  const int NT = (R + 15) >> 4;        // 16-row tiles; tile T -> wavefront T % 4
   int L = prefix_len[b];
   const int cap = d.max_blocks_per_seq * PAGE;
   L = L < 0 ? 0 : (L > cap ? cap : L);
@@ -224,14 +334,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 
   // ---- Q fragments (B operand of S^T = K Q^T), kept for the whole kernel -------------------
   bf16x8 qf[TPW][4];
-  int node_of[TPW];  // tree node of this lane's row in each of the wavefront's tiles
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
     int row = (wave + 4 * t) * 16 + j;
     bool ok = row < R;
     int node = ok ? row / G : 0;
     int hg = ok ? row - node * G : 0;
-    node_of[t] = node;
     const u32x4 *src = q + (row_base + (size_t)node * d.num_q_heads + hg) * 16;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -241,14 +349,21 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     }
   }
 
+  // fp32 O^T accumulators: defined (as zero, by a matrix instruction on zero operands) and from
+  // then on modified only by inline assembly with the operand tied in place
   f32x4 o[TPW][8];
   float m_run[TPW], l_run[TPW];
+  {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    const bf16x8 zero = __builtin_bit_cast(bf16x8, z);
 #pragma unroll
-  for (int t = 0; t < TPW; ++t) {
-    m_run[t] = HB_NEG_INF;
-    l_run[t] = 0.f;
+    for (int t = 0; t < TPW; ++t) {
+      m_run[t] = HB_NEG_INF;
+      l_run[t] = 0.f;
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) o[t][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int dt = 0; dt < 8; ++dt)
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %1, 0" : "=a"(o[t][dt]) : "v"(zero));
+    }
   }
   const float c1 = d.softmax_scale * kLog2e;
 
@@ -261,130 +376,96 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   src.bt = block_table + (size_t)b * d.max_blocks_per_seq;
   src.g = g; src.n0 = n0; src.n_nodes = n_nodes; src.hkv = d.num_kv_heads; src.num_blocks = d.num_blocks;
 
+  // Staging registers of the next tile; K and V are in flight at different times (K during the
+  // first 32-key block of the current tile, V during the second).
   u32x4 sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3;
-#define HB_STAGE_LOAD(tree_, start_)                            \
-  {                                                             \
-    sk0 = load_k_piece(src, tree_, start_, end, tid, 0);        \
-    sk1 = load_k_piece(src, tree_, start_, end, tid, 1);        \
-    sk2 = load_k_piece(src, tree_, start_, end, tid, 2);        \
-    sk3 = load_k_piece(src, tree_, start_, end, tid, 3);        \
-    sv0 = load_v_piece(src, tree_, start_, end, tid, 0);        \
-    sv1 = load_v_piece(src, tree_, start_, end, tid, 1);        \
-    sv2 = load_v_piece(src, tree_, start_, end, tid, 2);        \
-    sv3 = load_v_piece(src, tree_, start_, end, tid, 3);        \
+  const int piece = tid & 15, krow = tid >> 4;
+  // fast path for full prefix tiles: the four pages of a tile are looked up once per workgroup
+  // (uniform, scalar loads) and every thread adds its fixed offset
+  const size_t page_stride = (size_t)d.num_kv_heads * PAGE * 16;  // u32x4 units per page
+  const u32x4 *k_lane = k_pool + (size_t)g * PAGE * 16 + krow * 16 + piece;
+  const u32x4 *v_lane = v_pool + (size_t)g * PAGE * 16 + (4 * (krow & 3)) * 16 + piece;
+#define HB_PAGE(idx_)                                                        \
+  ({                                                                         \
+    int blk__ = src.bt[(idx_)];                                              \
+    blk__ = blk__ < 0 ? 0 : (blk__ >= d.num_blocks ? d.num_blocks - 1 : blk__); \
+    blk__;                                                                   \
+  })
+#define HB_LOAD_K(full_, tree_, start_)                                     \
+  if (full_) {                                                              \
+    int p0__ = (start_) / PAGE;                                             \
+    sk0 = k_lane[(size_t)HB_PAGE(p0__ + 0) * page_stride];                  \
+    sk1 = k_lane[(size_t)HB_PAGE(p0__ + 1) * page_stride];                  \
+    sk2 = k_lane[(size_t)HB_PAGE(p0__ + 2) * page_stride];                  \
+    sk3 = k_lane[(size_t)HB_PAGE(p0__ + 3) * page_stride];                  \
+  } else {                                                                  \
+    sk0 = load_k_piece(src, tree_, start_, end, tid, 0);                    \
+    sk1 = load_k_piece(src, tree_, start_, end, tid, 1);                    \
+    sk2 = load_k_piece(src, tree_, start_, end, tid, 2);                    \
+    sk3 = load_k_piece(src, tree_, start_, end, tid, 3);                    \
   }
-#define HB_STAGE_STORE(buf_)                                     \
-  {                                                              \
-    store_k(lds_k + (buf_) * K_PIECES, tid, sk0, sk1, sk2, sk3); \
-    store_v(lds_v + (buf_) * V_BYTES, tid, sv0, sv1, sv2, sv3);  \
+#define HB_LOAD_V(full_, tree_, start_)                                     \
+  if (full_) {                                                              \
+    const u32x4 *vp__ = v_lane + (size_t)HB_PAGE((start_) / PAGE + (krow >> 2)) * page_stride; \
+    sv0 = vp__[0];                                                          \
+    sv1 = vp__[16];                                                         \
+    sv2 = vp__[32];                                                         \
+    sv3 = vp__[48];                                                         \
+  } else {                                                                  \
+    sv0 = load_v_piece(src, tree_, start_, end, tid, 0);                    \
+    sv1 = load_v_piece(src, tree_, start_, end, tid, 1);                    \
+    sv2 = load_v_piece(src, tree_, start_, end, tid, 2);                    \
+    sv3 = load_v_piece(src, tree_, start_, end, tid, 3);                    \
   }
 
-  HB_STAGE_LOAD(tree_chunk, begin);
-  HB_STAGE_STORE(0);
+  {
+    const bool full0 = !tree_chunk && begin + KT <= end;
+    HB_LOAD_K(full0, tree_chunk, begin);
+    HB_LOAD_V(full0, tree_chunk, begin);
+    store_k(lds_k, tid, sk0, sk1, sk2, sk3);
+    store_v(lds_v, tid, sv0, sv1, sv2, sv3);
+  }
   __syncthreads();
 
   for (int i = 0; i < n_tiles; ++i) {
     const int buf = i & 1;
     const bool is_tree = tree_chunk && i == 0;
     const int tile_start = begin + (i - (tree_chunk ? 1 : 0)) * KT;  // prefix position of key 0
-    if (i + 1 < n_tiles) HB_STAGE_LOAD(false, tile_start + KT);      // the next tile is a prefix tile
+    const int next_start = tile_start + KT;                          // the next tile is a prefix tile
+    const bool has_next = i + 1 < n_tiles;
+    const bool next_full = next_start + KT <= end;
     const int n_valid = is_tree ? n_nodes : min(KT, end - tile_start);  // keys of this tile that exist
     const u32x4 *lk = lds_k + buf * K_PIECES;
     const unsigned char *lv = lds_v + buf * V_BYTES;
+    const bool partial = is_tree || n_valid < KT;  // uniform
 
-#pragma unroll
+#pragma unroll 1
     for (int blk32 = 0; blk32 < 2; ++blk32) {
-      const bool partial = (32 * blk32 + 32 > n_valid) || is_tree;  // uniform
-      bf16x8 pb[TPW];
-      {
-        // K fragments of the block's two 16-key halves, shared by all row tiles of the wavefront
-        bf16x8 ak[2][4];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-          for (int ks = 0; ks < 4; ++ks) {
-            int key = 32 * blk32 + 16 * a + j;
-            ak[a][ks] = __builtin_bit_cast(bf16x8, lk[key * 16 + ((4 * ks + kg) ^ j)]);
-          }
-#pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-          f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int ks = 0; ks < 4; ++ks) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][ks], qf[t][ks], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][ks], qf[t][ks], s1, 0, 0, 0);
-          }
-          float sc[8];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            sc[r] = s0[r] * c1;
-            sc[4 + r] = s1[r] * c1;
-          }
-          if (partial) {
-            // key of slot (a, r): 32*blk32 + 16*a + 4*kg + r; select, so NaN/Inf scores of
-            // forbidden keys vanish
-            uint32_t allow = ~0u;  // bit k: key 32*blk32 + k may be seen by this lane's row
-            if (is_tree) allow = (uint32_t)(anc_lds[node_of[t]] >> (32 * blk32));
-            int left = n_valid - 32 * blk32;  // keys of this block that exist
-            allow &= left >= 32 ? ~0u : ((1u << (left < 0 ? 0 : left)) - 1u);
-            allow >>= 4 * kg;
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-              for (int r = 0; r < 4; ++r)
-                sc[4 * a + r] = ((allow >> (16 * a + r)) & 1u) ? sc[4 * a + r] : HB_NEG_INF;
-          }
-          float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
-                           fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-          mx = group_max(mx);
-          const float m_old = m_run[t];
-          const float m_new = fmaxf(m_old, mx);
-          if (__any(m_new > m_old)) {
-            // some row's maximum moved: rescale (rows whose maximum stayed get alpha = 1).
-            // The empty asm keeps this rare path a real branch instead of an unconditional
-            // multiply of the whole accumulator.
-            asm volatile("" ::: "memory");
-            float alpha = (m_old == HB_NEG_INF) ? 0.f : fast_exp2(m_old - m_new);
-            l_run[t] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) o[t][dt] *= alpha;
-            m_run[t] = m_new;
-          }
-          // every row has seen at least one allowed key by now (the first key of a prefix
-          // chunk, the root of the tree), so m_new is finite
-          f32x8 p;
-          float psum = 0.f;
-#pragma unroll
-          for (int r = 0; r < 8; ++r) {
-            p[r] = fast_exp2(sc[r] - m_new);
-            psum += p[r];
-          }
-          l_run[t] += psum;
-          pb[t] = __builtin_convertvector(p, bf16x8);
-          __builtin_amdgcn_sched_barrier(0);  // keep one row tile's softmax temporaries live at a time
+      if (has_next) {
+        if (blk32 == 0) {
+          HB_LOAD_K(next_full, false, next_start);
+        } else {
+          store_k(lds_k + (buf ^ 1) * K_PIECES, tid, sk0, sk1, sk2, sk3);
+          HB_LOAD_V(next_full, false, next_start);
         }
       }
-      // O^T += V^T P^T, one 16-d slab of V^T at a time for all row tiles
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        int dd = 16 * dt + j;
-        int rr = dd ^ ((dd >> 3) & 3);
-        bf16x8 av = __builtin_bit_cast(bf16x8, *(const u32x4 *)(lv + blk32 * (D * 64) + rr * 64 + 16 * kg));
-#pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-          o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], o[t][dt], 0, 0, 0);
-        }
-        if (dt & 1) __builtin_amdgcn_sched_barrier(0);  // at most two V^T slabs in flight
-      }
+      if (32 * blk32 < n_valid)
+        attend_block<TPW>(partial, lk, lv, blk32, j, kg, qf, o, m_run, l_run, c1, n_valid, is_tree, anc_lds, wave,
+                          R, G, fix_slot, fix_addr);
     }
-
-    if (i + 1 < n_tiles) HB_STAGE_STORE(buf ^ 1);
+    if (has_next) store_v(lds_v + (buf ^ 1) * V_BYTES, tid, sv0, sv1, sv2, sv3);
     __syncthreads();
   }
-#undef HB_STAGE_LOAD
-#undef HB_STAGE_STORE
+#undef HB_PAGE
+#undef HB_LOAD_K
+#undef HB_LOAD_V
+
+  // The accumulators were last written by matrix instructions the compiler cannot see; give
+  // the last of them time to land before ordinary instructions read the registers.
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
 
   // ---- write out: lane (j, kg) holds O[row j][16*dt + 4*kg + r] ---------------------------
+  const int NT = (R + 15) >> 4;
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
     int row = (wave + 4 * t) * 16 + j;
@@ -397,9 +478,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
       float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) {
+        f32x4 v = o[t][dt];
         u32x2 w;
-        w[0] = (uint32_t)f32_to_bf16(o[t][dt][0] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][1] * inv) << 16);
-        w[1] = (uint32_t)f32_to_bf16(o[t][dt][2] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][3] * inv) << 16);
+        w[0] = (uint32_t)f32_to_bf16(v[0] * inv) | ((uint32_t)f32_to_bf16(v[1] * inv) << 16);
+        w[1] = (uint32_t)f32_to_bf16(v[2] * inv) | ((uint32_t)f32_to_bf16(v[3] * inv) << 16);
         *(u32x2 *)(out + rg * D + 16 * dt + 4 * kg) = w;
       }
       if (lse && kg == 0) lse[rg] = (m_run[t] + log2f(l_tot)) * kLn2;
@@ -415,7 +497,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   }
 }
 
-constexpr size_t kLdsBytes = 2 * K_PIECES * 16 + 2 * V_BYTES + 64 * 8;
+constexpr size_t kLdsBytes = 2 * K_PIECES * 16 + 2 * V_BYTES + 64 * 8 + 256 * 16;
 
 template <int TPW>
 hipError_t launch(const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
