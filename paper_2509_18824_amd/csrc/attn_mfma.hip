@@ -24,6 +24,7 @@
 // node's ancestor bitmask), then every chunk streams its share of the prefix through the page
 // table in 64-key tiles, double buffered: global loads of tile i+1 are issued before the MFMAs
 // of tile i and written to the other LDS buffer afterwards.
+#include <stdlib.h>
 #include "hb_internal.h"
 
 namespace hb {
@@ -158,15 +159,16 @@ __device__ __forceinline__ float group_sum(float x) {
 // One 32-key block of the current tile against all row tiles of the wavefront.
 //   partial (uniform): some keys of the block do not exist or are masked (chunk tail, tree tile).
 // Row tiles are taken in groups of at most four: scores and softmax for the group (VALU work,
-// QK^T on the matrix cores), then the group's O^T += V^T P^T.  The second product is issued as
-// inline assembly with the accumulator tied in place in the accumulation registers: the fp32
-// O^T of all tiles (224 registers for 7 tiles) never moves.
+// QK^T on the matrix cores), then the group's O^T += V^T P^T.  After every instruction that
+// defines an O^T accumulator an empty asm statement with an "a" constraint pins the value to the
+// accumulation registers; with that the fp32 O^T of all tiles (224 registers for 7 tiles) stays
+// in place there instead of being shuffled through the vector registers every iteration.
 template <int TPW>
 __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restrict__ lk, const unsigned char *__restrict__ lv,
                                              int blk32, int j, int kg, const bf16x8 (&qf)[TPW][4],
                                              f32x4 (&o)[TPW][8], float (&m_run)[TPW], float (&l_run)[TPW],
                                              float c1, int n_valid, bool is_tree, const unsigned long long *anc_lds,
-                                             int wave, int R, int G, f32x4 *fix_slot, uint32_t fix_addr) {
+                                             int wave, int R, int G) {
   // K fragments of the block's two 16-key halves, shared by all row tiles of the wavefront
   bf16x8 ak[2][4];
 #pragma unroll
@@ -196,7 +198,7 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
         // (not arithmetic) removes forbidden scores, so NaN/Inf there cannot leak.
         uint32_t allow = ~0u;
         if (is_tree) {
-          int row = (wave + 4 * t) * 16 + j;
+          int row = (wave + 4 * t) * 16 + j;  // `wave` here: the wavefront's first tile
           int node = row < R ? row / G : 0;
           allow = (uint32_t)(anc_lds[node] >> (32 * blk32));
         }
@@ -216,23 +218,16 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       const float m_new = fmaxf(m_old, mx);
       if (__any(m_new > m_old)) {
         // Rare: some row's maximum moved, rescale this tile (rows whose maximum stayed get
-        // alpha = 1).  The accumulator lives in accumulation registers that ordinary vector
-        // instructions cannot address, so each 16x16 piece takes a round trip through a per-lane
-        // LDS slot.  The leading nops cover the distance an MFMA result needs before it may be
-        // read by a non-MFMA instruction.
-        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+        // alpha = 1).  The asm statement keeps this a real branch: without it the multiply of
+        // the whole accumulator is speculated into every iteration.
+        asm volatile("" ::: "memory");
         float alpha = (m_old == HB_NEG_INF) ? 0.f : fast_exp2(m_old - m_new);
         l_run[t] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-          asm volatile("ds_write_b128 %1, %0\n\ts_waitcnt lgkmcnt(0)" ::"a"(o[t][dt]), "v"(fix_addr) : "memory");
-          f32x4 tmp = *fix_slot;
-          tmp *= alpha;
-          *fix_slot = tmp;
-          asm volatile("s_waitcnt lgkmcnt(0)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                       : "+a"(o[t][dt])
-                       : "v"(fix_addr)
-                       : "memory");
+          asm volatile("" : "+a"(o[t][dt]));
+          o[t][dt] *= alpha;
+          asm volatile("" : "+a"(o[t][dt]));
         }
         m_run[t] = m_new;
       }
@@ -258,7 +253,8 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       for (int u = 0; u < kGroup; ++u) {
         const int t = t0 + u;
         if (t >= TPW) break;
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(o[t][dt]) : "v"(av), "v"(pb[u]));
+        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[u], o[t][dt], 0, 0, 0);
+        asm volatile("" : "+a"(o[t][dt]));
       }
     }
   }
@@ -266,29 +262,42 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
 
 template <int TPW>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(
-    hb_attn_desc d, int splits, int chunk_tokens, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
+    hb_attn_desc d, int splits, int chunk_tokens, int row_groups, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
     const u32x4 *__restrict__ v_tree, const u32x4 *__restrict__ k_pool, const u32x4 *__restrict__ v_pool,
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ prefix_len,
     const int32_t *__restrict__ node_offset, const int32_t *__restrict__ parent, bf16_t *__restrict__ out,
     float *__restrict__ lse, float *__restrict__ part_o, float *__restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // [2][K tile 16 KiB] [2][V^T tile 16 KiB] [64 ancestor masks] [256 per-lane 16-byte slots]
+  // [2][K tile 16 KiB] [2][V^T tile 16 KiB] [64 ancestor masks]
   u32x4 *lds_k = (u32x4 *)smem;
   unsigned char *lds_v = smem + 2 * K_PIECES * 16;
   unsigned long long *anc_lds = (unsigned long long *)(smem + 2 * K_PIECES * 16 + 2 * V_BYTES);
-  f32x4 *fix_slot = (f32x4 *)(smem + 2 * K_PIECES * 16 + 2 * V_BYTES + 512) + threadIdx.x;
-  const uint32_t fix_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)fix_slot;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Work item = (sequence b, kv head g, chunk c, row group).  Consecutive workgroup ids land on
+  // different XCDs (id % 8); the row groups of one (b, g, c) get ids 8 apart, i.e. neighbouring
+  // slots of the same XCD, so the KV tiles they both read are shared in that XCD's L2.
+  const int id = blockIdx.x;
+  const int xcd = id & 7, slot = id >> 3;
+  const int rgi = slot % row_groups;
+  const int item = (slot / row_groups) * 8 + xcd;
+  if (item >= d.batch * d.num_kv_heads * splits) return;
+  const int c = item % splits;
+  const int g = (item / splits) % d.num_kv_heads;
+  const int b = item / (splits * d.num_kv_heads);
   const int G = d.num_q_heads / d.num_kv_heads;
   const int n0 = node_offset[b];
   int n_nodes = node_offset[b + 1] - n0;
   n_nodes = n_nodes < 0 ? 0 : (n_nodes > d.max_nodes_per_tree ? d.max_nodes_per_tree : n_nodes);
   if (n0 < 0 || n0 + n_nodes > d.total_nodes) n_nodes = 0;  // malformed offsets: touch nothing
   const int R = n_nodes * G;           // query rows of this (sequence, kv head)
+  const int NT = (R + 15) >> 4;        // 16-row tiles
+  const int tiles_per_group = (NT + row_groups - 1) / row_groups;
+  const int tile_lo = rgi * tiles_per_group;                     // this workgroup's tiles
+  const int tile_hi = min(NT, tile_lo + tiles_per_group);
+  const int wtile = tile_lo + wave;    // the wavefront's tiles: wtile + 4*t < tile_hi
   int L = prefix_len[b];
   const int cap = d.max_blocks_per_seq * PAGE;
   L = L < 0 ? 0 : (L > cap ? cap : L);
@@ -301,7 +310,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   const int begin = c * chunk;
   const int end = min(L, begin + chunk);
   const bool tree_chunk = (c == 0);
-  if (R == 0) return;
+  if (tile_lo >= tile_hi) return;
 
   const int j = lane & 15;    // query row within a tile
   const int kg = lane >> 4;   // key group / k-slot group of this lane
@@ -309,7 +318,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 
   if (!tree_chunk && begin >= L) {
     // an empty chunk only announces itself to the merge
-    for (int r = tid; r < R; r += 256) {
+    for (int r = tile_lo * 16 + tid; r < min(R, tile_hi * 16); r += 256) {
       size_t rg = row_base + (size_t)(r / G) * d.num_q_heads + (r % G);
       part_ml[(rg * splits + c) * 2 + 0] = HB_NEG_INF;
       part_ml[(rg * splits + c) * 2 + 1] = 0.f;
@@ -336,8 +345,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   bf16x8 qf[TPW][4];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
-    int row = (wave + 4 * t) * 16 + j;
-    bool ok = row < R;
+    int row = (wtile + 4 * t) * 16 + j;
+    bool ok = row < R && (wtile + 4 * t) < tile_hi;
     int node = ok ? row / G : 0;
     int hg = ok ? row - node * G : 0;
     const u32x4 *src = q + (row_base + (size_t)node * d.num_q_heads + hg) * 16;
@@ -349,20 +358,17 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     }
   }
 
-  // fp32 O^T accumulators: defined (as zero, by a matrix instruction on zero operands) and from
-  // then on modified only by inline assembly with the operand tied in place
+  // fp32 O^T accumulators, pinned to the accumulation registers
   f32x4 o[TPW][8];
   float m_run[TPW], l_run[TPW];
-  {
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    const bf16x8 zero = __builtin_bit_cast(bf16x8, z);
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) {
-      m_run[t] = HB_NEG_INF;
-      l_run[t] = 0.f;
+  for (int t = 0; t < TPW; ++t) {
+    m_run[t] = HB_NEG_INF;
+    l_run[t] = 0.f;
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt)
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %1, 0" : "=a"(o[t][dt]) : "v"(zero));
+    for (int dt = 0; dt < 8; ++dt) {
+      o[t][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      asm volatile("" : "+a"(o[t][dt]));
     }
   }
   const float c1 = d.softmax_scale * kLog2e;
@@ -380,60 +386,75 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   // first 32-key block of the current tile, V during the second).
   u32x4 sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3;
   const int piece = tid & 15, krow = tid >> 4;
-  // fast path for full prefix tiles: the four pages of a tile are looked up once per workgroup
-  // (uniform, scalar loads) and every thread adds its fixed offset
   const size_t page_stride = (size_t)d.num_kv_heads * PAGE * 16;  // u32x4 units per page
   const u32x4 *k_lane = k_pool + (size_t)g * PAGE * 16 + krow * 16 + piece;
   const u32x4 *v_lane = v_pool + (size_t)g * PAGE * 16 + (4 * (krow & 3)) * 16 + piece;
+  // Prefix tiles: the four pages of a tile are looked up once per workgroup (uniform index,
+  // scalar loads); every thread adds its fixed offset inside the page.  Loads are unconditional
+  // (page ids are clamped into the pool, so every address is valid) and slots at or past `end`
+  // are then replaced by zeros with a select.
+  const int last_page = d.max_blocks_per_seq - 1;
 #define HB_PAGE(idx_)                                                        \
   ({                                                                         \
-    int blk__ = src.bt[(idx_)];                                              \
+    int pg__ = (idx_) < last_page ? (idx_) : last_page;                      \
+    int blk__ = src.bt[pg__];                                                \
     blk__ = blk__ < 0 ? 0 : (blk__ >= d.num_blocks ? d.num_blocks - 1 : blk__); \
     blk__;                                                                   \
   })
-#define HB_LOAD_K(full_, tree_, start_)                                     \
-  if (full_) {                                                              \
-    int p0__ = (start_) / PAGE;                                             \
+#define HB_LOAD_K(start_)                                                   \
+  {                                                                         \
+    const int p0__ = (start_) / PAGE;                                       \
+    const int left__ = end - (start_) - krow; /* key krow+16i valid iff 16i < left */ \
+    const u32x4 z__ = {0u, 0u, 0u, 0u};                                     \
     sk0 = k_lane[(size_t)HB_PAGE(p0__ + 0) * page_stride];                  \
     sk1 = k_lane[(size_t)HB_PAGE(p0__ + 1) * page_stride];                  \
     sk2 = k_lane[(size_t)HB_PAGE(p0__ + 2) * page_stride];                  \
     sk3 = k_lane[(size_t)HB_PAGE(p0__ + 3) * page_stride];                  \
-  } else {                                                                  \
-    sk0 = load_k_piece(src, tree_, start_, end, tid, 0);                    \
-    sk1 = load_k_piece(src, tree_, start_, end, tid, 1);                    \
-    sk2 = load_k_piece(src, tree_, start_, end, tid, 2);                    \
-    sk3 = load_k_piece(src, tree_, start_, end, tid, 3);                    \
+    sk0 = left__ > 0 ? sk0 : z__;                                           \
+    sk1 = left__ > 16 ? sk1 : z__;                                          \
+    sk2 = left__ > 32 ? sk2 : z__;                                          \
+    sk3 = left__ > 48 ? sk3 : z__;                                          \
   }
-#define HB_LOAD_V(full_, tree_, start_)                                     \
-  if (full_) {                                                              \
-    const u32x4 *vp__ = v_lane + (size_t)HB_PAGE((start_) / PAGE + (krow >> 2)) * page_stride; \
+#define HB_LOAD_V(start_)                                                   \
+  {                                                                         \
+    const u32x4 *vp__ = v_lane + (size_t)HB_PAGE((start_) / PAGE + wave) /* krow >> 2 == wave */ * page_stride; \
+    const int left__ = end - (start_) - 4 * krow; /* key 4*krow+i valid iff i < left */ \
+    const u32x4 z__ = {0u, 0u, 0u, 0u};                                     \
     sv0 = vp__[0];                                                          \
     sv1 = vp__[16];                                                         \
     sv2 = vp__[32];                                                         \
     sv3 = vp__[48];                                                         \
-  } else {                                                                  \
-    sv0 = load_v_piece(src, tree_, start_, end, tid, 0);                    \
-    sv1 = load_v_piece(src, tree_, start_, end, tid, 1);                    \
-    sv2 = load_v_piece(src, tree_, start_, end, tid, 2);                    \
-    sv3 = load_v_piece(src, tree_, start_, end, tid, 3);                    \
+    sv0 = left__ > 0 ? sv0 : z__;                                           \
+    sv1 = left__ > 1 ? sv1 : z__;                                           \
+    sv2 = left__ > 2 ? sv2 : z__;                                           \
+    sv3 = left__ > 3 ? sv3 : z__;                                           \
   }
 
-  {
-    const bool full0 = !tree_chunk && begin + KT <= end;
-    HB_LOAD_K(full0, tree_chunk, begin);
-    HB_LOAD_V(full0, tree_chunk, begin);
-    store_k(lds_k, tid, sk0, sk1, sk2, sk3);
-    store_v(lds_v, tid, sv0, sv1, sv2, sv3);
+  if (tree_chunk) {
+    // the tree tile: keys are node ids, read straight from k_tree / v_tree (once per workgroup)
+    sk0 = load_k_piece(src, true, 0, 0, tid, 0);
+    sk1 = load_k_piece(src, true, 0, 0, tid, 1);
+    sk2 = load_k_piece(src, true, 0, 0, tid, 2);
+    sk3 = load_k_piece(src, true, 0, 0, tid, 3);
+    sv0 = load_v_piece(src, true, 0, 0, tid, 0);
+    sv1 = load_v_piece(src, true, 0, 0, tid, 1);
+    sv2 = load_v_piece(src, true, 0, 0, tid, 2);
+    sv3 = load_v_piece(src, true, 0, 0, tid, 3);
+  } else {
+    HB_LOAD_K(begin);
+    HB_LOAD_V(begin);
   }
+  store_k(lds_k, tid, sk0, sk1, sk2, sk3);
+  store_v(lds_v, tid, sv0, sv1, sv2, sv3);
   __syncthreads();
 
+#pragma unroll 1  // also keeps the compiler from peeling the tree tile's iteration into a second copy
   for (int i = 0; i < n_tiles; ++i) {
     const int buf = i & 1;
     const bool is_tree = tree_chunk && i == 0;
     const int tile_start = begin + (i - (tree_chunk ? 1 : 0)) * KT;  // prefix position of key 0
     const int next_start = tile_start + KT;                          // the next tile is a prefix tile
     const bool has_next = i + 1 < n_tiles;
-    const bool next_full = next_start + KT <= end;
     const int n_valid = is_tree ? n_nodes : min(KT, end - tile_start);  // keys of this tile that exist
     const u32x4 *lk = lds_k + buf * K_PIECES;
     const unsigned char *lv = lds_v + buf * V_BYTES;
@@ -443,15 +464,15 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     for (int blk32 = 0; blk32 < 2; ++blk32) {
       if (has_next) {
         if (blk32 == 0) {
-          HB_LOAD_K(next_full, false, next_start);
+          HB_LOAD_K(next_start);
         } else {
           store_k(lds_k + (buf ^ 1) * K_PIECES, tid, sk0, sk1, sk2, sk3);
-          HB_LOAD_V(next_full, false, next_start);
+          HB_LOAD_V(next_start);
         }
       }
       if (32 * blk32 < n_valid)
-        attend_block<TPW>(partial, lk, lv, blk32, j, kg, qf, o, m_run, l_run, c1, n_valid, is_tree, anc_lds, wave,
-                          R, G, fix_slot, fix_addr);
+        attend_block<TPW>(partial, lk, lv, blk32, j, kg, qf, o, m_run, l_run, c1, n_valid, is_tree, anc_lds, wtile,
+                          R, G);
     }
     if (has_next) store_v(lds_v + (buf ^ 1) * V_BYTES, tid, sv0, sv1, sv2, sv3);
     __syncthreads();
@@ -460,16 +481,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 #undef HB_LOAD_K
 #undef HB_LOAD_V
 
-  // The accumulators were last written by matrix instructions the compiler cannot see; give
-  // the last of them time to land before ordinary instructions read the registers.
-  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-
   // ---- write out: lane (j, kg) holds O[row j][16*dt + 4*kg + r] ---------------------------
-  const int NT = (R + 15) >> 4;
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
-    int row = (wave + 4 * t) * 16 + j;
-    if ((wave + 4 * t) >= NT) continue;
+    int row = (wtile + 4 * t) * 16 + j;
+    if ((wtile + 4 * t) >= tile_hi) continue;
     float l_tot = group_sum(l_run[t]);
     if (row >= R) continue;
     int node = row / G, hg = row - node * G;
@@ -497,18 +513,19 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   }
 }
 
-constexpr size_t kLdsBytes = 2 * K_PIECES * 16 + 2 * V_BYTES + 64 * 8 + 256 * 16;
+constexpr size_t kLdsBytes = 2 * K_PIECES * 16 + 2 * V_BYTES + 64 * 8;
 
 template <int TPW>
-hipError_t launch(const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
+hipError_t launch(int row_groups, const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
                   const void *v_tree, const void *k_pool, const void *v_pool, const int32_t *block_table,
                   const int32_t *prefix_len, const int32_t *node_offset, const int32_t *parent, void *out,
                   float *lse, float *part_o, float *part_ml, hipStream_t s) {
-  dim3 grid((unsigned)plan.splits, (unsigned)d.num_kv_heads, (unsigned)d.batch);
+  const int items = d.batch * d.num_kv_heads * plan.splits;
+  dim3 grid((unsigned)((items + 7) / 8 * 8 * row_groups));
   auto kern = attn_mfma_kernel<TPW>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
-  kern<<<grid, 256, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, (const u32x4 *)q, (const u32x4 *)k_tree,
+  kern<<<grid, 256, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, row_groups, (const u32x4 *)q, (const u32x4 *)k_tree,
                                     (const u32x4 *)v_tree, (const u32x4 *)k_pool, (const u32x4 *)v_pool,
                                     block_table, prefix_len, node_offset, parent, (bf16_t *)out, lse, part_o,
                                     part_ml);
@@ -534,9 +551,14 @@ hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const v
                             float *part_o, float *part_ml, hipStream_t s) {
   int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
   int tiles = (rows + 15) / 16;
-  int tpw = (tiles + 3) / 4;  // row tiles per wavefront
+  // Row tiles per wavefront.  Up to 7 fit the register file of one wavefront per SIMD; trees
+  // are split into row groups (separate workgroups sharing the KV stream through L2) when that
+  // keeps the kernel free of register spills.
+  int row_groups = 1;
+  if (const char *e = getenv("HB_ATTN_ROW_GROUPS")) row_groups = atoi(e) > 0 ? atoi(e) : 1;
+  int tpw = ((tiles + row_groups - 1) / row_groups + 3) / 4;
 #define HB_GO(N) \
-  return launch<N>(d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
+  return launch<N>(row_groups, d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
   if (tpw <= 1) HB_GO(1);
   if (tpw <= 2) HB_GO(2);
   if (tpw <= 4) HB_GO(4);
