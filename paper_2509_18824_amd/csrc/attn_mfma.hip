@@ -11,10 +11,13 @@
 // The S^T accumulator of lane l holds, for query row l%16, the four keys 4*(l/16)+r of a 16-key
 // tile; two such tiles give the eight k-slots that the same lane must supply as the B operand
 // of the second MFMA, provided V^T is laid out in LDS with the matching key permutation.
-// Softmax is online per row in base 2 (scores scaled by softmax_scale*log2 e); the running
-// maximum is shared by the four lane groups of a row (two cross-lane exchanges per 32 keys),
-// row sums stay per lane until the end, and the accumulator is rescaled only when some row's
-// maximum actually moved.
+// Softmax is online per row in base 2 (scores scaled by softmax_scale*log2 e) against a
+// reference exponent per row that is shared by the four lane groups of the row (two cross-lane
+// exchanges per 32 keys).  The reference is the first block maximum the row sees and moves
+// only when a later maximum exceeds it by more than 8 (a factor 256): row maxima of real score
+// distributions creep up by small steps all the time, and rescaling the whole accumulator at
+// every step would cost more vector work than the attention itself.  Row sums stay per lane
+// until the end.
 //
 // Rows: row r = node * G + head_in_group, tiles of 16 rows, tile T belongs to wavefront T % 4;
 // Q fragments and the fp32 O^T accumulators of a wavefront's (at most TPW) tiles live in
@@ -44,6 +47,7 @@ constexpr int K_PIECES = KT * 16;      // 16-byte pieces of a K tile (16 per key
 constexpr int V_BYTES = 2 * D * 64;    // V^T tile: 2 blocks of 32 keys x 128 d x 64 bytes
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kSlack = 8.f;  // log2 units a row maximum may exceed its reference exponent
 #define HB_NEG_INF (-__builtin_huge_valf())
 
 __device__ __forceinline__ uint32_t finite_or_zero_bf16x2(uint32_t w) {
@@ -181,7 +185,11 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
 #pragma unroll
   for (int t0 = 0; t0 < TPW; t0 += 4) {
     constexpr int kGroup = 4;
-    bf16x8 pb[kGroup];
+    // -- scores of the group's tiles, masks, new running maxima (no branches: the matrix and
+    //    vector work of different tiles can be interleaved by the scheduler)
+    float sc[kGroup][8];
+    float m_new[kGroup], mx_keep[kGroup];
+    bool moved = false;
 #pragma unroll
     for (int u = 0; u < kGroup; ++u) {
       const int t = t0 + u;
@@ -192,7 +200,11 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
         s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][ks], qf[t][ks], s0, 0, 0, 0);
         s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][ks], qf[t][ks], s1, 0, 0, 0);
       }
-      float sc[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        sc[u][r] = s0[r];
+        sc[u][4 + r] = s1[r];
+      }
       if (partial) {
         // bit k of `allow`: key 32*blk32 + k exists and may be seen by this lane's row.  A select
         // (not arithmetic) removes forbidden scores, so NaN/Inf there cannot leak.
@@ -209,19 +221,33 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
         for (int a = 0; a < 2; ++a)
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            sc[4 * a + r] = ((allow >> (16 * a + r)) & 1u) ? sc[4 * a + r] : HB_NEG_INF;
+            sc[u][4 * a + r] = ((allow >> (16 * a + r)) & 1u) ? sc[u][4 * a + r] : HB_NEG_INF;
       }
-      float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
-                       fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+      float mx = fmaxf(fmaxf(fmaxf(sc[u][0], sc[u][1]), fmaxf(sc[u][2], sc[u][3])),
+                       fmaxf(fmaxf(sc[u][4], sc[u][5]), fmaxf(sc[u][6], sc[u][7])));
       mx = group_max(mx) * c1;  // c1 > 0: scaling commutes with the maximum
+      // Reference exponent of the row: the first maximum seen, replaced only when a later
+      // maximum exceeds it by more than kSlack (then exp2(score - reference) <= 2^kSlack stays
+      // far from overflow and the accumulators need no rescaling in between).
       const float m_old = m_run[t];
-      const float m_new = fmaxf(m_old, mx);
-      if (__any(m_new > m_old)) {
-        // Rare: some row's maximum moved, rescale this tile (rows whose maximum stayed get
-        // alpha = 1).  The asm statement keeps this a real branch: without it the multiply of
-        // the whole accumulator is speculated into every iteration.
-        asm volatile("" ::: "memory");
-        float alpha = (m_old == HB_NEG_INF) ? 0.f : fast_exp2(m_old - m_new);
+      m_new[u] = (m_old == HB_NEG_INF) ? mx : m_old;  // nothing accumulated yet: adopt, no rescale
+      moved |= mx > m_new[u] + kSlack;
+      m_run[t] = m_new[u];
+      mx_keep[u] = mx;
+    }
+    // -- rare: some row's maximum outgrew its reference; rescale the group's accumulators (rows
+    //    that stay get alpha = 1).  One uniform branch per group; the asm statement keeps it a
+    //    real branch, otherwise the multiply of the whole accumulator is speculated into every
+    //    pass.
+    if (__any(moved)) {
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const int t = t0 + u;
+        if (t >= TPW) break;
+        const bool grow = mx_keep[u] > m_new[u] + kSlack;
+        const float alpha = grow ? fast_exp2(m_new[u] - mx_keep[u]) : 1.f;
+        m_new[u] = grow ? mx_keep[u] : m_new[u];
         l_run[t] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
@@ -229,33 +255,46 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
           o[t][dt] *= alpha;
           asm volatile("" : "+a"(o[t][dt]));
         }
-        m_run[t] = m_new;
+        m_run[t] = m_new[u];
       }
-      // every row has seen at least one allowed key by now (the first key of a prefix chunk,
-      // the root of the tree), so m_new is finite
+    }
+    // -- probabilities.  Every row has seen at least one allowed key by now (the first key of a
+    //    prefix chunk, the root of the tree), so its reference is finite.
+    bf16x8 pb[kGroup];
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      const int t = t0 + u;
+      if (t >= TPW) break;
       f32x8 p;
       float psum = 0.f;
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
-        p[r] = fast_exp2(fmaf(sc[r], c1, -m_new));
+        p[r] = fast_exp2(fmaf(sc[u][r], c1, -m_new[u]));
         psum += p[r];
       }
       l_run[t] += psum;
       pb[u] = __builtin_convertvector(p, bf16x8);
     }
-    // O^T += V^T P^T for the group, one 16-d slab of V^T at a time
+    // -- O^T += V^T P^T for the group, one 16-d slab of V^T at a time; the slab for step dt+1 is
+    //    fetched from LDS before the matrix instructions of step dt are issued
+    const unsigned char *vbase = lv + blk32 * (D * 64) + 16 * kg;
+    bf16x8 av[2];
+    av[0] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vbase + (j ^ ((j >> 3) & 3)) * 64));
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
-      int dd = 16 * dt + j;
-      int rr = dd ^ ((dd >> 3) & 3);
-      bf16x8 av = __builtin_bit_cast(bf16x8, *(const u32x4 *)(lv + blk32 * (D * 64) + rr * 64 + 16 * kg));
+      if (dt < 7) {
+        int dd = 16 * (dt + 1) + j;
+        av[(dt + 1) & 1] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vbase + (dd ^ ((dd >> 3) & 3)) * 64));
+      }
 #pragma unroll
       for (int u = 0; u < kGroup; ++u) {
         const int t = t0 + u;
         if (t >= TPW) break;
-        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[u], o[t][dt], 0, 0, 0);
+        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dt & 1], pb[u], o[t][dt], 0, 0, 0);
         asm volatile("" : "+a"(o[t][dt]));
       }
+      // nothing moves across: the LDS read of the next slab stays ahead of its use by one step
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
@@ -391,8 +430,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   const u32x4 *v_lane = v_pool + (size_t)g * PAGE * 16 + (4 * (krow & 3)) * 16 + piece;
   // Prefix tiles: the four pages of a tile are looked up once per workgroup (uniform index,
   // scalar loads); every thread adds its fixed offset inside the page.  Loads are unconditional
-  // (page ids are clamped into the pool, so every address is valid) and slots at or past `end`
-  // are then replaced by zeros with a select.
+  // (page ids are clamped into the pool, so every address is valid); slots at or past `end` are
+  // replaced by zeros only when the registers are written to LDS, so that nothing touches the
+  // loaded registers (and waits for memory) while the matrix work of the current tile runs.
+  int k_left = 64, v_left = 4;  // validity bounds of the staged tile, see HB_LOAD_K / HB_LOAD_V
   const int last_page = d.max_blocks_per_seq - 1;
 #define HB_PAGE(idx_)                                                        \
   ({                                                                         \
@@ -405,29 +446,21 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   {                                                                         \
     const int p0__ = (start_) / PAGE;                                       \
     const int left__ = end - (start_) - krow; /* key krow+16i valid iff 16i < left */ \
-    const u32x4 z__ = {0u, 0u, 0u, 0u};                                     \
     sk0 = k_lane[(size_t)HB_PAGE(p0__ + 0) * page_stride];                  \
     sk1 = k_lane[(size_t)HB_PAGE(p0__ + 1) * page_stride];                  \
     sk2 = k_lane[(size_t)HB_PAGE(p0__ + 2) * page_stride];                  \
     sk3 = k_lane[(size_t)HB_PAGE(p0__ + 3) * page_stride];                  \
-    sk0 = left__ > 0 ? sk0 : z__;                                           \
-    sk1 = left__ > 16 ? sk1 : z__;                                          \
-    sk2 = left__ > 32 ? sk2 : z__;                                          \
-    sk3 = left__ > 48 ? sk3 : z__;                                          \
+    k_left = left__;                                                        \
   }
 #define HB_LOAD_V(start_)                                                   \
   {                                                                         \
     const u32x4 *vp__ = v_lane + (size_t)HB_PAGE((start_) / PAGE + wave) /* krow >> 2 == wave */ * page_stride; \
     const int left__ = end - (start_) - 4 * krow; /* key 4*krow+i valid iff i < left */ \
-    const u32x4 z__ = {0u, 0u, 0u, 0u};                                     \
     sv0 = vp__[0];                                                          \
     sv1 = vp__[16];                                                         \
     sv2 = vp__[32];                                                         \
     sv3 = vp__[48];                                                         \
-    sv0 = left__ > 0 ? sv0 : z__;                                           \
-    sv1 = left__ > 1 ? sv1 : z__;                                           \
-    sv2 = left__ > 2 ? sv2 : z__;                                           \
-    sv3 = left__ > 3 ? sv3 : z__;                                           \
+    v_left = left__;                                                        \
   }
 
   if (tree_chunk) {
@@ -444,8 +477,20 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     HB_LOAD_K(begin);
     HB_LOAD_V(begin);
   }
-  store_k(lds_k, tid, sk0, sk1, sk2, sk3);
-  store_v(lds_v, tid, sv0, sv1, sv2, sv3);
+#define HB_STORE_K(dst_)                                                                      \
+  {                                                                                           \
+    const u32x4 z__ = {0u, 0u, 0u, 0u};                                                       \
+    store_k(dst_, tid, k_left > 0 ? sk0 : z__, k_left > 16 ? sk1 : z__, k_left > 32 ? sk2 : z__, \
+            k_left > 48 ? sk3 : z__);                                                         \
+  }
+#define HB_STORE_V(dst_)                                                                      \
+  {                                                                                           \
+    const u32x4 z__ = {0u, 0u, 0u, 0u};                                                       \
+    store_v(dst_, tid, v_left > 0 ? sv0 : z__, v_left > 1 ? sv1 : z__, v_left > 2 ? sv2 : z__,   \
+            v_left > 3 ? sv3 : z__);                                                          \
+  }
+  HB_STORE_K(lds_k);
+  HB_STORE_V(lds_v);
   __syncthreads();
 
 #pragma unroll 1  // also keeps the compiler from peeling the tree tile's iteration into a second copy
@@ -466,7 +511,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
         if (blk32 == 0) {
           HB_LOAD_K(next_start);
         } else {
-          store_k(lds_k + (buf ^ 1) * K_PIECES, tid, sk0, sk1, sk2, sk3);
+          HB_STORE_K(lds_k + (buf ^ 1) * K_PIECES);
           HB_LOAD_V(next_start);
         }
       }
@@ -474,12 +519,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
         attend_block<TPW>(partial, lk, lv, blk32, j, kg, qf, o, m_run, l_run, c1, n_valid, is_tree, anc_lds, wtile,
                           R, G);
     }
-    if (has_next) store_v(lds_v + (buf ^ 1) * V_BYTES, tid, sv0, sv1, sv2, sv3);
+    if (has_next) HB_STORE_V(lds_v + (buf ^ 1) * V_BYTES);
     __syncthreads();
   }
 #undef HB_PAGE
 #undef HB_LOAD_K
 #undef HB_LOAD_V
+#undef HB_STORE_K
+#undef HB_STORE_V
 
   // ---- write out: lane (j, kg) holds O[row j][16*dt + 4*kg + r] ---------------------------
 #pragma unroll
