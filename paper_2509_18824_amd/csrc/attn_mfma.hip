@@ -1,9 +1,11 @@
 // Tree-verify attention on the bf16 matrix cores of gfx950 (head_dim 128, page size 16).
 //
-// One workgroup (4 wavefronts) owns one (sequence, kv head, KV chunk).  Every KV tile it
-// streams from HBM is staged once in LDS and used by ALL query rows that share it: the rows of
-// every tree node and of every query head of the kv group (N * G rows, 420 for 60 nodes and
-// GQA 7:1), which is what turns the memory-bound decode step into a compute-dense one.
+// One workgroup (4 wavefronts) owns one (sequence, kv head, KV chunk, row group).  Every KV
+// tile it streams is staged once in LDS and used by all query rows of the group: rows of many
+// tree nodes and of every query head of the kv group (N * G rows in all, 420 for 60 nodes and
+// GQA 7:1, split into row groups of at most 128 rows whose workgroups sit on one XCD and share
+// the KV stream in its L2), which is what turns the memory-bound decode step into a
+// compute-dense one.
 //
 // Formulation (transposed, so no score ever crosses lanes on its way into the second GEMM):
 //   S^T = K Q^T     MFMA 16x16x32: A = K tile (16 keys x 32 d), B = Q^T (32 d x 16 rows)
@@ -19,15 +21,15 @@
 // every step would cost more vector work than the attention itself.  Row sums stay per lane
 // until the end.
 //
-// Rows: row r = node * G + head_in_group, tiles of 16 rows, tile T belongs to wavefront T % 4;
-// Q fragments and the fp32 O^T accumulators of a wavefront's (at most TPW) tiles live in
-// registers for the whole kernel.
+// Rows: row r = node * G + head_in_group, tiles of 16 rows dealt round-robin to the four
+// wavefronts; Q fragments and the fp32 O^T accumulators of a wavefront's (at most TPW = 2) tiles
+// live in registers for the whole kernel, within 256 registers so that two workgroups share a
+// CU and one's matrix work overlaps the other's vector work and waits.
 //
 // Keys: chunk 0 starts with one 64-key tile holding the tree nodes (masked per row by the
 // node's ancestor bitmask), then every chunk streams its share of the prefix through the page
 // table in 64-key tiles, double buffered: global loads of tile i+1 are issued before the MFMAs
 // of tile i and written to the other LDS buffer afterwards.
-#include <stdlib.h>
 #include "hb_internal.h"
 
 namespace hb {
@@ -150,14 +152,23 @@ __device__ __forceinline__ void store_v(unsigned char *__restrict__ lv, int tid,
 // may flush to zero, which is what a vanishing softmax weight should do.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Reductions over the four lanes l, l^16, l^32, l^48 that hold the four key groups of one query
+// row.  v_permlane16_swap exchanges rows 1<->0 and 3<->2 (rows of 16 lanes) between its two
+// operands, v_permlane32_swap the upper half of one with the lower half of the other: fed the
+// same value twice they hand every lane its partner's value next to its own, without the LDS
+// round trip of a bpermute.
+typedef unsigned int swap2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float group_max(float x) {
-  // lanes l, l^16, l^32, l^48 hold the four key groups of one query row
-  x = fmaxf(x, __shfl_xor(x, 16, 64));
-  return fmaxf(x, __shfl_xor(x, 32, 64));
+  swap2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float group_sum(float x) {
-  x += __shfl_xor(x, 16, 64);
-  return x + __shfl_xor(x, 32, 64);
+  swap2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 // One 32-key block of the current tile against all row tiles of the wavefront.
@@ -300,7 +311,7 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
 }
 
 template <int TPW>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
     hb_attn_desc d, int splits, int chunk_tokens, int row_groups, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
     const u32x4 *__restrict__ v_tree, const u32x4 *__restrict__ k_pool, const u32x4 *__restrict__ v_pool,
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ prefix_len,
@@ -585,10 +596,21 @@ bool attn_mfma_supports(const hb_attn_desc &d) {
   if (d.dtype != HB_BF16 || d.head_dim != D || d.page_size != PAGE) return false;
   if (d.num_kv_heads <= 0 || d.num_q_heads % d.num_kv_heads) return false;
   int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
-  if (d.max_nodes_per_tree > 64 || rows > 448) return false;
+  if (d.max_nodes_per_tree > 64 || rows > 512) return false;  // at most 4 row groups of 8 tiles
   if (!(d.softmax_scale > 0.f) || !(d.softmax_scale < 1e30f)) return false;  // base-2 max tracking needs scale > 0
   if (d.batch > 65535 || d.num_kv_heads > 65535) return false;
   return true;
+}
+
+// Row groups: workgroups that split the 16-row tiles of one (sequence, kv head, chunk) among
+// them and stream the same KV (shared through the XCD's L2).  Two tiles per wavefront (eight per
+// workgroup) keep a wavefront within 256 registers, so two workgroups fit a CU and one's matrix
+// work overlaps the other's vector work and waits.
+int32_t attn_mfma_row_groups(const hb_attn_desc &d) {
+  int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
+  int tiles = (rows + 15) / 16;
+  int groups = (tiles + 7) / 8;
+  return groups < 1 ? 1 : groups;
 }
 
 hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
@@ -598,18 +620,12 @@ hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const v
                             float *part_o, float *part_ml, hipStream_t s) {
   int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
   int tiles = (rows + 15) / 16;
-  // Row tiles per wavefront.  Up to 7 fit the register file of one wavefront per SIMD; trees
-  // are split into row groups (separate workgroups sharing the KV stream through L2) when that
-  // keeps the kernel free of register spills.
-  int row_groups = 1;
-  if (const char *e = getenv("HB_ATTN_ROW_GROUPS")) row_groups = atoi(e) > 0 ? atoi(e) : 1;
-  int tpw = ((tiles + row_groups - 1) / row_groups + 3) / 4;
+  const int row_groups = plan.row_groups;
+  int tpw = ((tiles + row_groups - 1) / row_groups + 3) / 4;  // row tiles per wavefront
 #define HB_GO(N) \
   return launch<N>(row_groups, d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
   if (tpw <= 1) HB_GO(1);
-  if (tpw <= 2) HB_GO(2);
-  if (tpw <= 4) HB_GO(4);
-  HB_GO(7);
+  HB_GO(2);  // attn_mfma_row_groups keeps a workgroup at eight tiles or fewer
 #undef HB_GO
 }
 

@@ -134,7 +134,10 @@ __global__ __launch_bounds__(64) void attn_scalar_kernel(
 }
 
 // out[row] = sum_c O_c e^{m_c - m} / sum_c l_c e^{m_c - m}; chunks with l_c == 0 are empty and
-// their O_c was never written.
+// their O_c was never written.  One wavefront per row; the loads of up to kMergeBatch chunks are
+// issued together before any arithmetic, so the kernel runs at memory rate instead of one chunk
+// latency at a time.
+constexpr int kMergeBatch = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void attn_merge_kernel(int rows, int D, int splits,
                                                          const float *__restrict__ part_o,
@@ -145,21 +148,32 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(int rows, int D, int sp
   if (row >= rows) return;
   const float *ml = part_ml + (size_t)row * splits * 2;
   float m = -__builtin_huge_valf();
-  for (int c = 0; c < splits; ++c)
+  for (int c = lane; c < splits; c += 64)
     if (ml[c * 2 + 1] > 0.f) m = fmaxf(m, ml[c * 2]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
   float l = 0.f;
   float acc[kMaxPerLane] = {0.f, 0.f, 0.f, 0.f};
-  for (int c = 0; c < splits; ++c) {
-    float lc = ml[c * 2 + 1];
-    if (!(lc > 0.f)) continue;
-    float w = expf(ml[c * 2] - m);
-    l += lc * w;
-    const float *o = part_o + ((size_t)row * splits + c) * D;
+  for (int c0 = 0; c0 < splits; c0 += kMergeBatch) {
+    float w[kMergeBatch], o[kMergeBatch][kMaxPerLane];
 #pragma unroll
-    for (int e = 0; e < kMaxPerLane; ++e) {
-      int dd = lane + 64 * e;
-      if (dd < D) acc[e] += o[dd] * w;
+    for (int i = 0; i < kMergeBatch; ++i) {
+      const int c = c0 + i;
+      float lc = c < splits ? ml[c * 2 + 1] : 0.f;
+      const bool live = lc > 0.f;
+      w[i] = live ? expf(ml[c * 2] - m) : 0.f;
+      l += live ? lc * w[i] : 0.f;
+      const float *po = part_o + ((size_t)row * splits + (live ? c : 0)) * D;
+#pragma unroll
+      for (int e = 0; e < kMaxPerLane; ++e) {
+        int dd = lane + 64 * e;
+        o[i][e] = (live && dd < D) ? po[dd] : 0.f;  // select: an empty chunk's slot is never read
+      }
     }
+#pragma unroll
+    for (int i = 0; i < kMergeBatch; ++i)
+#pragma unroll
+      for (int e = 0; e < kMaxPerLane; ++e) acc[e] = fmaf(o[i][e], w[i], acc[e]);
   }
   float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll

@@ -53,8 +53,9 @@ int32_t make_attn_plan(const hb_attn_desc *d, AttnPlan *plan) {
   bool can_mfma = attn_mfma_supports(*d);
   if (d->algo == HB_ATTN_MFMA && !can_mfma)
     return fail(HB_ERR_UNSUPPORTED,
-                "HB_ATTN_MFMA needs bf16, head_dim 128, page_size 16 and (Hq/Hkv)*max_nodes_per_tree <= 448");
+                "HB_ATTN_MFMA needs bf16, head_dim 128, page_size 16 and (Hq/Hkv)*max_nodes_per_tree <= 512");
   plan->mfma = (d->algo == HB_ATTN_MFMA) || (d->algo == HB_ATTN_AUTO && can_mfma);
+  plan->row_groups = plan->mfma ? attn_mfma_row_groups(*d) : 1;
   int64_t span = (int64_t)d->page_size * d->max_blocks_per_seq;
   if (d->max_prefix_len_hint > 0 && d->max_prefix_len_hint < span) span = d->max_prefix_len_hint;
   if (span < 1) span = 1;
@@ -62,9 +63,9 @@ int32_t make_attn_plan(const hb_attn_desc *d, AttnPlan *plan) {
   int64_t splits = d->num_splits;
   if (splits == 0) {
     if (plan->mfma) {
-      // one workgroup per (sequence, kv head, chunk): aim at ~2 workgroups per CU, but keep a
-      // chunk at 1024 tokens or more so that partial traffic stays below the KV traffic
-      int64_t items = (int64_t)d->batch * d->num_kv_heads;
+      // Parallelism comes first from row groups (they cost no partials), then from KV chunks:
+      // aim at two workgroups per CU, keep a chunk at 1024 tokens or more
+      int64_t items = (int64_t)d->batch * d->num_kv_heads * plan->row_groups;
       splits = items > 0 ? (512 + items - 1) / items : 1;
       int64_t cap = (span + 1023) / 1024;
       if (splits > cap) splits = cap;

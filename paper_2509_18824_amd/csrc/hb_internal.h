@@ -51,6 +51,7 @@ template <> __device__ inline void store_f32<bf16_t>(bf16_t *p, float v) { *p = 
 struct AttnPlan {
   int32_t splits;
   int32_t chunk_tokens;
+  int32_t row_groups;  // MFMA kernel: workgroups that split the query rows of one (sequence, kv head, chunk)
   bool mfma;
   size_t ml_offset;  // byte offset of part_ml in the workspace
   size_t bytes;      // workspace size (0 when splits == 1)
@@ -71,6 +72,7 @@ hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const v
                             const int32_t *parent, void *out, float *lse, float *part_o,
                             float *part_ml, hipStream_t s);
 bool attn_mfma_supports(const hb_attn_desc &d);
+int32_t attn_mfma_row_groups(const hb_attn_desc &d);
 hipError_t launch_attn_merge(const hb_attn_desc &d, const AttnPlan &plan, const float *part_o,
                              const float *part_ml, void *out, float *lse, hipStream_t s);
 
