@@ -126,7 +126,7 @@ int32_t hb_tree_verify_attn_num_splits(const hb_attn_desc *desc);
  *   out_ids   device int32 [M]               out_max  device float32 [M] or NULL: the winning
  *                                                     logit as accumulated in fp32
  *   workspace device, hb_lmhead_argmax_workspace_bytes(M) bytes, 8-byte aligned
- * bf16 inputs with K % 8 == 0 take the MFMA kernel; everything else a scalar fp32 kernel.
+ * bf16 inputs with K % 64 == 0 take the MFMA kernel; everything else a scalar fp32 kernel.
  * Errors: INVALID_ARG, UNSUPPORTED (dtype), WORKSPACE, DEVICE.  M == 0 is a no-op; V >= 1.
  */
 int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,

@@ -11,8 +11,9 @@
 // K-contiguous in memory ([V, K] and [M, K] row-major), which is exactly what the MFMA operand
 // layout wants (8 consecutive k per lane), so tiles go global -> registers -> LDS as 16-byte
 // pieces, XOR-swizzled so that the 16-byte operand reads of 8 consecutive rows hit all banks.
-// LDS is double buffered: the global loads of K step t+1 are issued before the MFMAs of step t
-// and written to the other buffer afterwards; one barrier per K step.
+// LDS is double buffered and the global loads run two K steps ahead through two sets of staging
+// registers: loads of step t+2 are issued before the MFMAs of step t, the registers of step t+1
+// are written to the other LDS buffer after them; one barrier per K step.
 //
 // Grid order: consecutive workgroup ids go to different XCDs (id % 8).  The m tiles of one v
 // tile are given ids 8 apart, i.e. consecutive slots of the same XCD, so they run together and
@@ -25,6 +26,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;           // k per step
 constexpr int TV = 256;          // vocabulary rows per workgroup
@@ -39,15 +41,15 @@ __device__ inline int swz(int r, int c) { return r * CH + (c ^ ((r & 7) ^ ((r >>
 
 template <int MT>  // 32-row hidden tiles per wavefront (workgroup covers TM = 64 * MT rows)
 __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles,
-                                                          const uint4 *__restrict__ hidden,
-                                                          const uint4 *__restrict__ weight,
+                                                          const u32x4 *__restrict__ hidden,
+                                                          const u32x4 *__restrict__ weight,
                                                           unsigned long long *__restrict__ keys) {
   constexpr int TM = 64 * MT;
   constexpr int W_PIECES = TV * CH / 256;  // 16-byte pieces of the weight tile per thread (8)
   constexpr int H_PIECES = TM * CH / 256;  // same for the hidden tile (2 * MT)
-  extern __shared__ uint4 lds[];           // [2][TV*CH] weight, then [2][TM*CH] hidden
-  uint4 *lw = lds;
-  uint4 *lh = lds + 2 * TV * CH;
+  extern __shared__ u32x4 lds[];           // [2][TV*CH] weight, then [2][TM*CH] hidden
+  u32x4 *lw = lds;
+  u32x4 *lh = lds + 2 * TV * CH;
   __shared__ unsigned long long row_key[2][TM];
 
   const int tid = threadIdx.x;
@@ -71,8 +73,8 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
   // results are dropped in the epilogue)
   const int piece = tid & 7;   // piece within the 64-k step
   const int row_in = tid >> 3; // 0..31
-  const uint4 *w_src[W_PIECES];
-  const uint4 *h_src[H_PIECES];
+  const u32x4 *w_src[W_PIECES];
+  const u32x4 *h_src[H_PIECES];
 #pragma unroll
   for (int i = 0; i < W_PIECES; ++i) {
     int r = v0 + row_in + 32 * i;
@@ -94,66 +96,74 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  uint4 wreg[W_PIECES], hreg[H_PIECES];
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  const int k_steps = (K + BK - 1) / BK;
+  // Two sets of staging registers: the global loads of K step t+2 are issued before the MFMAs of
+  // step t, so a load has two full steps (about 1.7 us of matrix work) to arrive from HBM before
+  // its registers are written to LDS.
+  u32x4 wregA[W_PIECES], hregA[H_PIECES], wregB[W_PIECES], hregB[H_PIECES];
+  const int k_steps = K / BK;
 
-#define HB_LOAD_GLOBAL(kt_)                                                        \
+#define HB_LOAD_GLOBAL(kt_, wreg, hreg)                                            \
   {                                                                               \
-    const int p0 = (kt_) * CH;                                                    \
-    if (p0 + piece < kp) { /* pieces past K contribute zeros */                   \
-      _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i) wreg[i] = w_src[i][p0]; \
-      _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i) hreg[i] = h_src[i][p0]; \
-    } else {                                                                      \
-      _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i) wreg[i] = zero4;        \
-      _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i) hreg[i] = zero4;        \
-    }                                                                             \
+    /* K is a multiple of BK; steps past the end reload the last one and are never stored */ \
+    const int p0 = ((kt_) < k_steps ? (kt_) : k_steps - 1) * CH;                  \
+    _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i) wreg[i] = w_src[i][p0];   \
+    _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i) hreg[i] = h_src[i][p0];   \
   }
-#define HB_STORE_LDS(buf_)                                                                       \
+#define HB_STORE_LDS(buf_, wreg, hreg)                                                           \
   {                                                                                              \
     _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i)                                          \
         lw[(buf_) * TV * CH + swz(row_in + 32 * i, piece)] = wreg[i];                            \
     _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i)                                          \
         lh[(buf_) * TM * CH + swz(row_in + 32 * i, piece)] = hreg[i];                            \
   }
-
-  HB_LOAD_GLOBAL(0);
-  HB_STORE_LDS(0);
-  __syncthreads();
+#define HB_COMPUTE(buf_)                                                                         \
+  {                                                                                              \
+    const u32x4 *cw = lw + (buf_) * TV * CH;                                                     \
+    const u32x4 *chh = lh + (buf_) * TM * CH;                                                    \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
+      const int c = ks * 2 + frag_half; /* this lane's 8-k piece of the 16-k MFMA step */        \
+      bf16x8 a[4], b[MT];                                                                        \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+        a[i] = __builtin_bit_cast(bf16x8, cw[swz(wv * 128 + i * 32 + frag_row, c)]);                \
+                                                         \
+      }                                                                                          \
+      _Pragma("unroll") for (int j = 0; j < MT; ++j) {                                            \
+        b[j] = __builtin_bit_cast(bf16x8, chh[swz(wm * 32 * MT + j * 32 + frag_row, c)]);           \
+                                                         \
+      }                                                                                          \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
+        _Pragma("unroll") for (int j = 0; j < MT; ++j)                                            \
+          {                                                                                      \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0); \
+            asm volatile("" : "+a"(acc[i][j])); /* keep the accumulator in place in AGPRs */   \
+          }                                                                                      \
+    }                                                                                            \
+  }
 
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
-  for (int kt = 0; kt < k_steps; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < k_steps) HB_LOAD_GLOBAL(kt + 1);
-    const uint4 *cw = lw + buf * TV * CH;
-    const uint4 *chh = lh + buf * TM * CH;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int c = ks * 2 + frag_half;  // this lane's 8-k piece of the 16-k MFMA step
-      bf16x8 a[4], b[MT];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        uint4 t = cw[swz(wv * 128 + i * 32 + frag_row, c)];
-        a[i] = __builtin_bit_cast(bf16x8, t);
-      }
-#pragma unroll
-      for (int j = 0; j < MT; ++j) {
-        uint4 t = chh[swz(wm * 32 * MT + j * 32 + frag_row, c)];
-        b[j] = __builtin_bit_cast(bf16x8, t);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < MT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < k_steps) HB_STORE_LDS(buf ^ 1);
+  HB_LOAD_GLOBAL(0, wregA, hregA);
+  HB_STORE_LDS(0, wregA, hregA);
+  HB_LOAD_GLOBAL(1, wregB, hregB);
+  __syncthreads();
+
+  // step kt computes from LDS[kt & 1]; set A carries the even steps, set B the odd ones
+  int kt = 0;
+  for (; kt + 1 < k_steps; kt += 2) {
+    HB_LOAD_GLOBAL(kt + 2, wregA, hregA);
+    HB_COMPUTE(0);
+    HB_STORE_LDS(1, wregB, hregB);
+    __syncthreads();
+    HB_LOAD_GLOBAL(kt + 3, wregB, hregB);
+    HB_COMPUTE(1);
+    HB_STORE_LDS(0, wregA, hregA);  // past the last step: a reload of it, stored but never used
     __syncthreads();
   }
+  if (kt < k_steps) HB_COMPUTE(0);  // odd number of steps: the last one sits in buffer 0
 
 #undef HB_LOAD_GLOBAL
 #undef HB_STORE_LDS
+#undef HB_COMPUTE
 
   // Epilogue.  Accumulator r of lane l in tile (i, j) is C^T[v, m] with
   //   v = v0 + wv*128 + i*32 + 8*(r/4) + 4*(l/32) + r%4,   m = m0 + wm*32*MT + j*32 + l%32.
@@ -196,19 +206,19 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, u
   int m_tiles = (M + TM - 1) / TM;
   int v_tiles = (V + TV - 1) / TV;
   int v_groups = (v_tiles + kXcds - 1) / kXcds;
-  size_t lds_bytes = (size_t)2 * (TV + TM) * CH * sizeof(uint4);
+  size_t lds_bytes = (size_t)2 * (TV + TM) * CH * sizeof(u32x4);
   auto kern = lmhead_mfma_kernel<MT>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)(v_groups * m_tiles * kXcds));
-  kern<<<grid, 256, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const uint4 *)hidden, (const uint4 *)weight, keys);
+  kern<<<grid, 256, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const u32x4 *)hidden, (const u32x4 *)weight, keys);
   return hipGetLastError();
 }
 
 }  // namespace
 
 bool lmhead_mfma_supports(int32_t dtype, int32_t M, int32_t K, int32_t V) {
-  return dtype == HB_BF16 && K % 8 == 0 && M >= 1 && V >= 1;
+  return dtype == HB_BF16 && K % BK == 0 && M >= 1 && V >= 1;  // other K: the scalar kernel
 }
 
 hipError_t launch_lmhead_mfma(int32_t M, int32_t K, int32_t V, const void *hidden, const void *weight,
