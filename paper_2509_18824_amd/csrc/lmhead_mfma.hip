@@ -116,27 +116,32 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
     _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i)                                          \
         lh[(buf_) * TM * CH + swz(row_in + 32 * i, piece)] = hreg[i];                            \
   }
+#define HB_LOAD_FRAGS(ks_, slot_)                                                                \
+  {                                                                                              \
+    const int c = (ks_) * 2 + frag_half; /* this lane's 8-k piece of the 16-k MFMA step */       \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                 \
+        a[slot_][i] = __builtin_bit_cast(bf16x8, cw[swz(wv * 128 + i * 32 + frag_row, c)]);      \
+    _Pragma("unroll") for (int j = 0; j < MT; ++j)                                                \
+        b[slot_][j] = __builtin_bit_cast(bf16x8, chh[swz(wm * 32 * MT + j * 32 + frag_row, c)]); \
+  }
+  // One K step from LDS buffer buf_: the operand fragments of MFMA step ks+1 are read from LDS
+  // before the MFMAs of step ks are issued (two fragment sets), and nothing is scheduled across
+  // the step boundaries, so an LDS read always has a full step of matrix work to complete.
 #define HB_COMPUTE(buf_)                                                                         \
   {                                                                                              \
     const u32x4 *cw = lw + (buf_) * TV * CH;                                                     \
     const u32x4 *chh = lh + (buf_) * TM * CH;                                                    \
+    bf16x8 a[2][4], b[2][MT];                                                                    \
+    HB_LOAD_FRAGS(0, 0);                                                                         \
     _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
-      const int c = ks * 2 + frag_half; /* this lane's 8-k piece of the 16-k MFMA step */        \
-      bf16x8 a[4], b[MT];                                                                        \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
-        a[i] = __builtin_bit_cast(bf16x8, cw[swz(wv * 128 + i * 32 + frag_row, c)]);                \
-                                                         \
-      }                                                                                          \
-      _Pragma("unroll") for (int j = 0; j < MT; ++j) {                                            \
-        b[j] = __builtin_bit_cast(bf16x8, chh[swz(wm * 32 * MT + j * 32 + frag_row, c)]);           \
-                                                         \
-      }                                                                                          \
+      if (ks + 1 < BK / 16) HB_LOAD_FRAGS(ks + 1, (ks + 1) & 1);                                 \
       _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
         _Pragma("unroll") for (int j = 0; j < MT; ++j)                                            \
           {                                                                                      \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0); \
-            asm volatile("" : "+a"(acc[i][j])); /* keep the accumulator in place in AGPRs */   \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0); \
+            asm volatile("" : "+a"(acc[i][j])); /* keep the accumulator in place in AGPRs */     \
           }                                                                                      \
+      __builtin_amdgcn_sched_barrier(0);                                                         \
     }                                                                                            \
   }
 
@@ -164,6 +169,7 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
 #undef HB_LOAD_GLOBAL
 #undef HB_STORE_LDS
 #undef HB_COMPUTE
+#undef HB_LOAD_FRAGS
 
   // Epilogue.  Accumulator r of lane l in tile (i, j) is C^T[v, m] with
   //   v = v0 + wv*128 + i*32 + 8*(r/4) + 4*(l/32) + r%4,   m = m0 + wm*32*MT + j*32 + l%32.
