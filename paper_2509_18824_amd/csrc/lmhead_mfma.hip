@@ -39,23 +39,30 @@ constexpr int kXcds = 8;
 // (lanes = consecutive rows, one piece each) conflict free for 128- and 256-byte wide LDS.
 __device__ inline int swz(int r, int c) { return r * CH + (c ^ ((r & 7) ^ ((r >> 3) & 1))); }
 
-template <int MT>  // 32-row hidden tiles per wavefront (workgroup covers TM = 64 * MT rows)
-__global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles,
+// MT: 32-row hidden tiles per wavefront (the workgroup covers TM = 64 * MT hidden rows).
+// WV: wavefront rows along the vocabulary (2 or 4); the workgroup has 2 * WV wavefronts, each
+// with VT = 8 / WV vocabulary tiles of 32 rows.  WV = 4 (eight wavefronts, two per SIMD, at most
+// 256 registers each) lets one wavefront's matrix work cover the other's LDS, barrier and
+// memory waits.
+template <int MT, int WV>
+__global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles,
                                                           const u32x4 *__restrict__ hidden,
                                                           const u32x4 *__restrict__ weight,
                                                           unsigned long long *__restrict__ keys) {
   constexpr int TM = 64 * MT;
-  constexpr int W_PIECES = TV * CH / 256;  // 16-byte pieces of the weight tile per thread (8)
-  constexpr int H_PIECES = TM * CH / 256;  // same for the hidden tile (2 * MT)
+  constexpr int NT = 128 * WV;             // threads
+  constexpr int VT = 8 / WV;               // 32-row vocabulary tiles per wavefront
+  constexpr int W_PIECES = TV * CH / NT;   // 16-byte pieces of the weight tile per thread
+  constexpr int H_PIECES = TM * CH / NT;   // same for the hidden tile
   extern __shared__ u32x4 lds[];           // [2][TV*CH] weight, then [2][TM*CH] hidden
   u32x4 *lw = lds;
   u32x4 *lh = lds + 2 * TV * CH;
-  __shared__ unsigned long long row_key[2][TM];
+  __shared__ unsigned long long row_key[WV][TM];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wv = wave >> 1;  // which 128 vocabulary rows of the tile
+  const int wv = wave >> 1;  // which 32*VT vocabulary rows of the tile
   const int wm = wave & 1;   // which 32*MT hidden rows of the tile
 
   // XCD-aware tile order
@@ -72,25 +79,25 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
   // per-thread global source rows for the staging loads (rows past the end are clamped; their
   // results are dropped in the epilogue)
   const int piece = tid & 7;   // piece within the 64-k step
-  const int row_in = tid >> 3; // 0..31
+  const int row_in = tid >> 3; // 0 .. NT/8-1
   const u32x4 *w_src[W_PIECES];
   const u32x4 *h_src[H_PIECES];
 #pragma unroll
   for (int i = 0; i < W_PIECES; ++i) {
-    int r = v0 + row_in + 32 * i;
+    int r = v0 + row_in + (NT / 8) * i;
     r = r < V ? r : V - 1;
     w_src[i] = weight + (size_t)r * kp + piece;
   }
 #pragma unroll
   for (int i = 0; i < H_PIECES; ++i) {
-    int r = m0 + row_in + 32 * i;
+    int r = m0 + row_in + (NT / 8) * i;
     r = r < M ? r : M - 1;
     h_src[i] = hidden + (size_t)r * kp + piece;
   }
 
-  f32x16 acc[4][MT];
+  f32x16 acc[VT][MT];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < VT; ++a)
 #pragma unroll
     for (int b = 0; b < MT; ++b)
 #pragma unroll
@@ -112,15 +119,15 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
 #define HB_STORE_LDS(buf_, wreg, hreg)                                                           \
   {                                                                                              \
     _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i)                                          \
-        lw[(buf_) * TV * CH + swz(row_in + 32 * i, piece)] = wreg[i];                            \
+        lw[(buf_) * TV * CH + swz(row_in + (NT / 8) * i, piece)] = wreg[i];                            \
     _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i)                                          \
-        lh[(buf_) * TM * CH + swz(row_in + 32 * i, piece)] = hreg[i];                            \
+        lh[(buf_) * TM * CH + swz(row_in + (NT / 8) * i, piece)] = hreg[i];                            \
   }
 #define HB_LOAD_FRAGS(ks_, slot_)                                                                \
   {                                                                                              \
     const int c = (ks_) * 2 + frag_half; /* this lane's 8-k piece of the 16-k MFMA step */       \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                 \
-        a[slot_][i] = __builtin_bit_cast(bf16x8, cw[swz(wv * 128 + i * 32 + frag_row, c)]);      \
+    _Pragma("unroll") for (int i = 0; i < VT; ++i)                                                \
+        a[slot_][i] = __builtin_bit_cast(bf16x8, cw[swz(wv * 32 * VT + i * 32 + frag_row, c)]);  \
     _Pragma("unroll") for (int j = 0; j < MT; ++j)                                                \
         b[slot_][j] = __builtin_bit_cast(bf16x8, chh[swz(wm * 32 * MT + j * 32 + frag_row, c)]); \
   }
@@ -131,11 +138,11 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
   {                                                                                              \
     const u32x4 *cw = lw + (buf_) * TV * CH;                                                     \
     const u32x4 *chh = lh + (buf_) * TM * CH;                                                    \
-    bf16x8 a[2][4], b[2][MT];                                                                    \
+    bf16x8 a[2][VT], b[2][MT];                                                                    \
     HB_LOAD_FRAGS(0, 0);                                                                         \
     _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
       if (ks + 1 < BK / 16) HB_LOAD_FRAGS(ks + 1, (ks + 1) & 1);                                 \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
+      _Pragma("unroll") for (int i = 0; i < VT; ++i)                                              \
         _Pragma("unroll") for (int j = 0; j < MT; ++j)                                            \
           {                                                                                      \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0); \
@@ -172,7 +179,7 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
 #undef HB_LOAD_FRAGS
 
   // Epilogue.  Accumulator r of lane l in tile (i, j) is C^T[v, m] with
-  //   v = v0 + wv*128 + i*32 + 8*(r/4) + 4*(l/32) + r%4,   m = m0 + wm*32*MT + j*32 + l%32.
+  //   v = v0 + wv*32*VT + i*32 + 8*(r/4) + 4*(l/32) + r%4,   m = m0 + wm*32*MT + j*32 + l%32.
   // Scanning (i, r) in order visits v in increasing order, so a strict '>' keeps the lowest v
   // among equal values; NaN compares false and never wins.
 #pragma unroll
@@ -180,10 +187,10 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
     float best = -__builtin_huge_valf();
     int best_v = -1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < VT; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        int v = v0 + wv * 128 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        int v = v0 + wv * 32 * VT + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
         float x = acc[i][j][r];
         bool take = (v < V) && (x > best);
         best = take ? x : best;
@@ -196,16 +203,18 @@ __global__ __launch_bounds__(256) void lmhead_mfma_kernel(int M, int K, int V, i
     if (lane < 32) row_key[wv][wm * 32 * MT + j * 32 + lane] = key;
   }
   __syncthreads();
-  for (int r = tid; r < TM; r += 256) {
+  for (int r = tid; r < TM; r += NT) {
     int m = m0 + r;
     if (m >= M) continue;
-    unsigned long long key = row_key[0][r] > row_key[1][r] ? row_key[0][r] : row_key[1][r];
+    unsigned long long key = row_key[0][r];
+#pragma unroll
+    for (int w = 1; w < WV; ++w) key = row_key[w][r] > key ? row_key[w][r] : key;
     // skip the atomic when the row already holds something at least as good
     if (key > __atomic_load_n(&keys[m], __ATOMIC_RELAXED)) atomicMax(&keys[m], key);
   }
 }
 
-template <int MT>
+template <int MT, int WV>
 hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, unsigned long long *keys,
                   hipStream_t s) {
   constexpr int TM = 64 * MT;
@@ -213,11 +222,11 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, u
   int v_tiles = (V + TV - 1) / TV;
   int v_groups = (v_tiles + kXcds - 1) / kXcds;
   size_t lds_bytes = (size_t)2 * (TV + TM) * CH * sizeof(u32x4);
-  auto kern = lmhead_mfma_kernel<MT>;
+  auto kern = lmhead_mfma_kernel<MT, WV>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)(v_groups * m_tiles * kXcds));
-  kern<<<grid, 256, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const u32x4 *)hidden, (const u32x4 *)weight, keys);
+  kern<<<grid, 128 * WV, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const u32x4 *)hidden, (const u32x4 *)weight, keys);
   return hipGetLastError();
 }
 
@@ -239,10 +248,10 @@ hipError_t launch_lmhead_mfma(int32_t M, int32_t K, int32_t V, const void *hidde
     if (best_rows < 0 || rows < best_rows) { best_rows = rows; best_mt = mt; }
   }
   switch (best_mt) {
-    case 1: return launch<1>(M, K, V, hidden, weight, keys, s);
-    case 2: return launch<2>(M, K, V, hidden, weight, keys, s);
-    case 3: return launch<3>(M, K, V, hidden, weight, keys, s);
-    default: return launch<4>(M, K, V, hidden, weight, keys, s);
+    case 1: return launch<1, 4>(M, K, V, hidden, weight, keys, s);
+    case 2: return launch<2, 4>(M, K, V, hidden, weight, keys, s);
+    case 3: return launch<3, 4>(M, K, V, hidden, weight, keys, s);
+    default: return launch<4, 4>(M, K, V, hidden, weight, keys, s);
   }
 }
 
