@@ -446,6 +446,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
   // loaded registers (and waits for memory) while the matrix work of the current tile runs.
   int k_left = 64, v_left = 4;  // validity bounds of the staged tile, see HB_LOAD_K / HB_LOAD_V
   const int last_page = d.max_blocks_per_seq - 1;
+  // Page ids (clamped into the pool) of the tile that is loaded next; fetched one tile ahead so
+  // that the scalar loads are long complete when the addresses are formed.
+  int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0;
 #define HB_PAGE(idx_)                                                        \
   ({                                                                         \
     int pg__ = (idx_) < last_page ? (idx_) : last_page;                      \
@@ -453,25 +456,32 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
     blk__ = blk__ < 0 ? 0 : (blk__ >= d.num_blocks ? d.num_blocks - 1 : blk__); \
     blk__;                                                                   \
   })
-#define HB_LOAD_K(start_)                                                   \
+#define HB_FETCH_PAGES(start_)                                              \
   {                                                                         \
     const int p0__ = (start_) / PAGE;                                       \
-    const int left__ = end - (start_) - krow; /* key krow+16i valid iff 16i < left */ \
-    sk0 = k_lane[(size_t)HB_PAGE(p0__ + 0) * page_stride];                  \
-    sk1 = k_lane[(size_t)HB_PAGE(p0__ + 1) * page_stride];                  \
-    sk2 = k_lane[(size_t)HB_PAGE(p0__ + 2) * page_stride];                  \
-    sk3 = k_lane[(size_t)HB_PAGE(p0__ + 3) * page_stride];                  \
-    k_left = left__;                                                        \
+    pg0 = HB_PAGE(p0__ + 0);                                                \
+    pg1 = HB_PAGE(p0__ + 1);                                                \
+    pg2 = HB_PAGE(p0__ + 2);                                                \
+    pg3 = HB_PAGE(p0__ + 3);                                                \
+  }
+#define HB_LOAD_K(start_)                                                   \
+  {                                                                         \
+    sk0 = k_lane[(size_t)pg0 * page_stride];                                \
+    sk1 = k_lane[(size_t)pg1 * page_stride];                                \
+    sk2 = k_lane[(size_t)pg2 * page_stride];                                \
+    sk3 = k_lane[(size_t)pg3 * page_stride];                                \
+    k_left = end - (start_) - krow; /* key krow+16i valid iff 16i < k_left */ \
   }
 #define HB_LOAD_V(start_)                                                   \
   {                                                                         \
-    const u32x4 *vp__ = v_lane + (size_t)HB_PAGE((start_) / PAGE + wave) /* krow >> 2 == wave */ * page_stride; \
-    const int left__ = end - (start_) - 4 * krow; /* key 4*krow+i valid iff i < left */ \
+    /* keys 4*krow .. 4*krow+3 sit in page krow >> 2 == wave of the tile */  \
+    const int pv__ = wave == 0 ? pg0 : (wave == 1 ? pg1 : (wave == 2 ? pg2 : pg3)); \
+    const u32x4 *vp__ = v_lane + (size_t)pv__ * page_stride;                \
     sv0 = vp__[0];                                                          \
     sv1 = vp__[16];                                                         \
     sv2 = vp__[32];                                                         \
     sv3 = vp__[48];                                                         \
-    v_left = left__;                                                        \
+    v_left = end - (start_) - 4 * krow; /* key 4*krow+i valid iff i < v_left */ \
   }
 
   if (tree_chunk) {
@@ -484,9 +494,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
     sv1 = load_v_piece(src, true, 0, 0, tid, 1);
     sv2 = load_v_piece(src, true, 0, 0, tid, 2);
     sv3 = load_v_piece(src, true, 0, 0, tid, 3);
+    HB_FETCH_PAGES(begin);  // the next tile is the first prefix tile
   } else {
+    HB_FETCH_PAGES(begin);
     HB_LOAD_K(begin);
     HB_LOAD_V(begin);
+    HB_FETCH_PAGES(begin + KT);
   }
 #define HB_STORE_K(dst_)                                                                      \
   {                                                                                           \
@@ -524,6 +537,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
         } else {
           HB_STORE_K(lds_k + (buf ^ 1) * K_PIECES);
           HB_LOAD_V(next_start);
+          HB_FETCH_PAGES(next_start + KT);  // for the tile after the next
         }
       }
       if (32 * blk32 < n_valid)
@@ -534,6 +548,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
     __syncthreads();
   }
 #undef HB_PAGE
+#undef HB_FETCH_PAGES
 #undef HB_LOAD_K
 #undef HB_LOAD_V
 #undef HB_STORE_K
