@@ -9,11 +9,10 @@
 // Workgroup: 256 threads = 4 wavefronts in a 2 (v) x 2 (m) arrangement; workgroup tile
 // TV = 256 vocabulary rows x TM = 64 * MT hidden rows, K step 64.  Both operands are
 // K-contiguous in memory ([V, K] and [M, K] row-major), which is exactly what the MFMA operand
-// layout wants (8 consecutive k per lane), so tiles go global -> registers -> LDS as 16-byte
-// pieces, XOR-swizzled so that the 16-byte operand reads of 8 consecutive rows hit all banks.
-// LDS is double buffered and the global loads run two K steps ahead through two sets of staging
-// registers: loads of step t+2 are issued before the MFMAs of step t, the registers of step t+1
-// are written to the other LDS buffer after them; one barrier per K step.
+// layout wants (8 consecutive k per lane), so tiles go global -> LDS directly as 16-byte pieces
+// (global_load_lds), XOR-swizzled so that the 16-byte operand reads of 8 consecutive rows hit
+// all banks.  LDS is double buffered: the loads of K step t+1 are issued before the MFMAs of
+// step t and fill the other buffer while they run; one barrier per K step.
 //
 // Grid order: consecutive workgroup ids go to different XCDs (id % 8).  The m tiles of one v
 // tile are given ids 8 apart, i.e. consecutive slots of the same XCD, so they run together and
@@ -52,8 +51,6 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   constexpr int TM = 64 * MT;
   constexpr int NT = 128 * WV;             // threads
   constexpr int VT = 8 / WV;               // 32-row vocabulary tiles per wavefront
-  constexpr int W_PIECES = TV * CH / NT;   // 16-byte pieces of the weight tile per thread
-  constexpr int H_PIECES = TM * CH / NT;   // same for the hidden tile
   extern __shared__ u32x4 lds[];           // [2][TV*CH] weight, then [2][TM*CH] hidden
   u32x4 *lw = lds;
   u32x4 *lh = lds + 2 * TV * CH;
@@ -76,23 +73,32 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   const int m0 = m_tile * TM;
   const int kp = K / 8;  // 16-byte pieces per matrix row (K % 8 == 0)
 
-  // per-thread global source rows for the staging loads (rows past the end are clamped; their
-  // results are dropped in the epilogue)
-  const int piece = tid & 7;   // piece within the 64-k step
-  const int row_in = tid >> 3; // 0 .. NT/8-1
-  const u32x4 *w_src[W_PIECES];
-  const u32x4 *h_src[H_PIECES];
+  // Global -> LDS without passing through registers (global_load_lds_dwordx4): one instruction
+  // moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS, i.e. 8 consecutive tile rows of 8
+  // pieces.  The XOR swizzle of the LDS layout is applied on the source side: the lane that fills
+  // physical piece p of row r fetches logical piece p ^ f(r).  Wavefront w moves row groups
+  // w, w + 2*WV, ... of the weight tile and of the hidden tile.  Rows past the end are clamped
+  // (their results are dropped in the epilogue).
+  constexpr int NW = 2 * WV;                 // wavefronts
+  constexpr int W_GROUPS = TV / 8 / NW;      // 8-row groups of the weight tile per wavefront
+  constexpr int H_GROUPS = TM / 8 / NW;      // same for the hidden tile
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const int grow = lane >> 3;                // row inside an 8-row group
+  const u32x4 *w_src[W_GROUPS];
+  const u32x4 *h_src[H_GROUPS];
 #pragma unroll
-  for (int i = 0; i < W_PIECES; ++i) {
-    int r = v0 + row_in + (NT / 8) * i;
+  for (int i = 0; i < W_GROUPS; ++i) {
+    const int grp = uwave + NW * i;
+    int r = v0 + grp * 8 + grow;
     r = r < V ? r : V - 1;
-    w_src[i] = weight + (size_t)r * kp + piece;
+    w_src[i] = weight + (size_t)r * kp + ((lane & 7) ^ (grow ^ (grp & 1)));
   }
 #pragma unroll
-  for (int i = 0; i < H_PIECES; ++i) {
-    int r = m0 + row_in + (NT / 8) * i;
+  for (int i = 0; i < H_GROUPS; ++i) {
+    const int grp = uwave + NW * i;
+    int r = m0 + grp * 8 + grow;
     r = r < M ? r : M - 1;
-    h_src[i] = hidden + (size_t)r * kp + piece;
+    h_src[i] = hidden + (size_t)r * kp + ((lane & 7) ^ (grow ^ (grp & 1)));
   }
 
   f32x16 acc[VT][MT];
@@ -103,25 +109,24 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  // Two sets of staging registers: the global loads of K step t+2 are issued before the MFMAs of
-  // step t, so a load has two full steps (about 1.7 us of matrix work) to arrive from HBM before
-  // its registers are written to LDS.
-  u32x4 wregA[W_PIECES], hregA[H_PIECES], wregB[W_PIECES], hregB[H_PIECES];
   const int k_steps = K / BK;
+  typedef __attribute__((address_space(1))) const void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
 
-#define HB_LOAD_GLOBAL(kt_, wreg, hreg)                                            \
-  {                                                                               \
-    /* K is a multiple of BK; steps past the end reload the last one and are never stored */ \
-    const int p0 = ((kt_) < k_steps ? (kt_) : k_steps - 1) * CH;                  \
-    _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i) wreg[i] = w_src[i][p0];   \
-    _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i) hreg[i] = h_src[i][p0];   \
-  }
-#define HB_STORE_LDS(buf_, wreg, hreg)                                                           \
+#define HB_ISSUE_LOADS(kt_, buf_)                                                                \
   {                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < W_PIECES; ++i)                                          \
-        lw[(buf_) * TV * CH + swz(row_in + (NT / 8) * i, piece)] = wreg[i];                            \
-    _Pragma("unroll") for (int i = 0; i < H_PIECES; ++i)                                          \
-        lh[(buf_) * TM * CH + swz(row_in + (NT / 8) * i, piece)] = hreg[i];                            \
+    _Pragma("unroll") for (int i = 0; i < W_GROUPS; ++i)                                          \
+        __builtin_amdgcn_global_load_lds((gptr_t)(w_src[i] + (kt_) * CH),                        \
+                                         (lptr_t)(lw + (buf_) * TV * CH + (uwave + NW * i) * 64), 16, 0, 0); \
+    _Pragma("unroll") for (int i = 0; i < H_GROUPS; ++i)                                          \
+        __builtin_amdgcn_global_load_lds((gptr_t)(h_src[i] + (kt_) * CH),                        \
+                                         (lptr_t)(lh + (buf_) * TM * CH + (uwave + NW * i) * 64), 16, 0, 0); \
+  }
+  // all of this wavefront's loads have landed in LDS; after the barrier, everybody's have
+#define HB_LOADS_DONE()                            \
+  {                                                \
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); \
+    __syncthreads();                               \
   }
 #define HB_LOAD_FRAGS(ks_, slot_)                                                                \
   {                                                                                              \
@@ -138,7 +143,7 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   {                                                                                              \
     const u32x4 *cw = lw + (buf_) * TV * CH;                                                     \
     const u32x4 *chh = lh + (buf_) * TM * CH;                                                    \
-    bf16x8 a[2][VT], b[2][MT];                                                                    \
+    bf16x8 a[2][VT], b[2][MT];                                                                   \
     HB_LOAD_FRAGS(0, 0);                                                                         \
     _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
       if (ks + 1 < BK / 16) HB_LOAD_FRAGS(ks + 1, (ks + 1) & 1);                                 \
@@ -154,27 +159,23 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
 
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
-  HB_LOAD_GLOBAL(0, wregA, hregA);
-  HB_STORE_LDS(0, wregA, hregA);
-  HB_LOAD_GLOBAL(1, wregB, hregB);
-  __syncthreads();
-
-  // step kt computes from LDS[kt & 1]; set A carries the even steps, set B the odd ones
+  HB_ISSUE_LOADS(0, 0);
+  HB_LOADS_DONE();
+  // step kt computes from LDS buffer kt & 1 while the loads of step kt + 1 fill the other one
+  // (every wavefront left that buffer at the barrier that ended step kt - 1)
   int kt = 0;
   for (; kt + 1 < k_steps; kt += 2) {
-    HB_LOAD_GLOBAL(kt + 2, wregA, hregA);
+    HB_ISSUE_LOADS(kt + 1, 1);
     HB_COMPUTE(0);
-    HB_STORE_LDS(1, wregB, hregB);
-    __syncthreads();
-    HB_LOAD_GLOBAL(kt + 3, wregB, hregB);
+    HB_LOADS_DONE();
+    if (kt + 2 < k_steps) HB_ISSUE_LOADS(kt + 2, 0);
     HB_COMPUTE(1);
-    HB_STORE_LDS(0, wregA, hregA);  // past the last step: a reload of it, stored but never used
-    __syncthreads();
+    HB_LOADS_DONE();
   }
   if (kt < k_steps) HB_COMPUTE(0);  // odd number of steps: the last one sits in buffer 0
 
-#undef HB_LOAD_GLOBAL
-#undef HB_STORE_LDS
+#undef HB_ISSUE_LOADS
+#undef HB_LOADS_DONE
 #undef HB_COMPUTE
 #undef HB_LOAD_FRAGS
 
