@@ -51,10 +51,12 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   constexpr int TM = 64 * MT;
   constexpr int NT = 128 * WV;             // threads
   constexpr int VT = 8 / WV;               // 32-row vocabulary tiles per wavefront
-  extern __shared__ u32x4 lds[];           // [2][TV*CH] weight, then [2][TM*CH] hidden
+  extern __shared__ u32x4 lds[];           // [3][TV*CH] weight, then [2][TM*CH] hidden
   u32x4 *lw = lds;
-  u32x4 *lh = lds + 2 * TV * CH;
-  __shared__ unsigned long long row_key[WV][TM];
+  u32x4 *lh = lds + 3 * TV * CH;
+  // per-row candidates of the epilogue; reuses the weight stages once the K loop is over
+  unsigned long long (*row_key)[TM] = reinterpret_cast<unsigned long long (*)[TM]>(lds);
+  static_assert(WV * TM * 8 <= 3 * TV * CH * 16, "row_key fits in the weight stages");
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -113,21 +115,24 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   typedef __attribute__((address_space(1))) const void *gptr_t;
   typedef __attribute__((address_space(3))) void *lptr_t;
 
-#define HB_ISSUE_LOADS(kt_, buf_)                                                                \
+#define HB_ISSUE_W(kt_, slot_)                                                                   \
   {                                                                                              \
     _Pragma("unroll") for (int i = 0; i < W_GROUPS; ++i)                                          \
         __builtin_amdgcn_global_load_lds((gptr_t)(w_src[i] + (kt_) * CH),                        \
-                                         (lptr_t)(lw + (buf_) * TV * CH + (uwave + NW * i) * 64), 16, 0, 0); \
+                                         (lptr_t)(lw + (slot_) * TV * CH + (uwave + NW * i) * 64), 16, 0, 0); \
+  }
+#define HB_ISSUE_H(kt_, slot_)                                                                   \
+  {                                                                                              \
     _Pragma("unroll") for (int i = 0; i < H_GROUPS; ++i)                                          \
         __builtin_amdgcn_global_load_lds((gptr_t)(h_src[i] + (kt_) * CH),                        \
-                                         (lptr_t)(lh + (buf_) * TM * CH + (uwave + NW * i) * 64), 16, 0, 0); \
+                                         (lptr_t)(lh + (slot_) * TM * CH + (uwave + NW * i) * 64), 16, 0, 0); \
   }
-  // all of this wavefront's loads have landed in LDS; after the barrier, everybody's have
-#define HB_LOADS_DONE()                            \
-  {                                                \
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); \
-    __syncthreads();                               \
-  }
+  // Everything but this wavefront's W_GROUPS newest loads (the weight rows of the step after
+  // next, which stay in flight across the barrier) has landed in LDS; after the barrier,
+  // everybody's has.  Every LDS read of the step has been consumed by an MFMA before this
+  // point, so no LDS counter wait is needed.
+  static_assert(W_GROUPS == 4, "the wait below leaves W_GROUPS loads outstanding");
+#define HB_STEP_DONE() asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory")
 #define HB_LOAD_FRAGS(ks_, slot_)                                                                \
   {                                                                                              \
     const int c = (ks_) * 2 + frag_half; /* this lane's 8-k piece of the 16-k MFMA step */       \
@@ -139,10 +144,10 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   // One K step from LDS buffer buf_: the operand fragments of MFMA step ks+1 are read from LDS
   // before the MFMAs of step ks are issued (two fragment sets), and nothing is scheduled across
   // the step boundaries, so an LDS read always has a full step of matrix work to complete.
-#define HB_COMPUTE(buf_)                                                                         \
+#define HB_COMPUTE(wslot_, hslot_, kw_, wfree_)                                                  \
   {                                                                                              \
-    const u32x4 *cw = lw + (buf_) * TV * CH;                                                     \
-    const u32x4 *chh = lh + (buf_) * TM * CH;                                                    \
+    const u32x4 *cw = lw + (wslot_) * TV * CH;                                                   \
+    const u32x4 *chh = lh + (hslot_) * TM * CH;                                                  \
     bf16x8 a[2][VT], b[2][MT];                                                                   \
     HB_LOAD_FRAGS(0, 0);                                                                         \
     _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
@@ -154,28 +159,46 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
             asm volatile("" : "+a"(acc[i][j])); /* keep the accumulator in place in AGPRs */     \
           }                                                                                      \
       __builtin_amdgcn_sched_barrier(0);                                                         \
+      if (ks == kWIssueAt) {                                                                     \
+        HB_ISSUE_W(kw_, wfree_);                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
+      }                                                                                          \
     }                                                                                            \
   }
 
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
-  HB_ISSUE_LOADS(0, 0);
-  HB_LOADS_DONE();
-  // step kt computes from LDS buffer kt & 1 while the loads of step kt + 1 fill the other one
-  // (every wavefront left that buffer at the barrier that ended step kt - 1)
-  int kt = 0;
-  for (; kt + 1 < k_steps; kt += 2) {
-    HB_ISSUE_LOADS(kt + 1, 1);
-    HB_COMPUTE(0);
-    HB_LOADS_DONE();
-    if (kt + 2 < k_steps) HB_ISSUE_LOADS(kt + 2, 0);
-    HB_COMPUTE(1);
-    HB_LOADS_DONE();
+  // Weight tiles (mostly from HBM) are fetched two K steps ahead into a ring of three LDS
+  // stages, hidden tiles (cache resident) one step ahead into two: at any time a wavefront has
+  // loads in flight, also across the barrier, and a weight load has two steps of matrix work to
+  // hide behind.  A fetch past the end repeats the last step (no branch in the loop); nothing
+  // reads it.
+  // The hidden loads of the next step go first, at the start of a step, and the weight loads
+  // of the step after next follow after kWIssueAt + 1 of the 4 MFMA sub-steps: the urgent loads
+  // get the CU's memory pipeline to themselves, and the pipeline has work throughout the step.
+  constexpr int kWIssueAt = 1;
+  const int last = k_steps - 1;
+  HB_ISSUE_H(0, 0);
+  HB_ISSUE_W(0, 0);
+  HB_ISSUE_W((1 < last ? 1 : last), 1);
+  HB_STEP_DONE();
+  int w_cur = 0, w_nxt = 1, w_free = 2;  // weight stages of steps kt, kt + 1 and the free one
+#pragma unroll 1
+  for (int kt = 0; kt < k_steps; ++kt) {
+    HB_ISSUE_H((kt + 1 < last ? kt + 1 : last), (kt + 1) & 1);
+    HB_COMPUTE(w_cur, kt & 1, (kt + 2 < last ? kt + 2 : last), w_free);
+    HB_STEP_DONE();
+    const int t = w_cur;
+    w_cur = w_nxt;
+    w_nxt = w_free;
+    w_free = t;
   }
-  if (kt < k_steps) HB_COMPUTE(0);  // odd number of steps: the last one sits in buffer 0
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();  // all tile loads landed, all operand reads done: LDS is free for row_key
 
-#undef HB_ISSUE_LOADS
-#undef HB_LOADS_DONE
+#undef HB_ISSUE_W
+#undef HB_ISSUE_H
+#undef HB_STEP_DONE
 #undef HB_COMPUTE
 #undef HB_LOAD_FRAGS
 
@@ -222,7 +245,7 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, u
   int m_tiles = (M + TM - 1) / TM;
   int v_tiles = (V + TV - 1) / TV;
   int v_groups = (v_tiles + kXcds - 1) / kXcds;
-  size_t lds_bytes = (size_t)2 * (TV + TM) * CH * sizeof(u32x4);
+  size_t lds_bytes = (size_t)(3 * TV + 2 * TM) * CH * sizeof(u32x4);
   auto kern = lmhead_mfma_kernel<MT, WV>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
