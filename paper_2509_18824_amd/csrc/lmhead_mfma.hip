@@ -44,7 +44,7 @@ __device__ inline int swz(int r, int c) { return r * CH + (c ^ ((r & 7) ^ ((r >>
 // 256 registers each) lets one wavefront's matrix work cover the other's LDS, barrier and
 // memory waits.
 template <int MT, int WV>
-__global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles,
+__global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles, int groups,
                                                           const u32x4 *__restrict__ hidden,
                                                           const u32x4 *__restrict__ weight,
                                                           unsigned long long *__restrict__ keys) {
@@ -64,16 +64,21 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   const int wv = wave >> 1;  // which 32*VT vocabulary rows of the tile
   const int wm = wave & 1;   // which 32*MT hidden rows of the tile
 
-  // XCD-aware tile order
+  // Persistent workgroups in lockstep groups.  Workgroup ids go round-robin to the XCDs
+  // (id % 8); on each XCD the grid places `groups` groups of m_tiles workgroups, one workgroup
+  // per CU.  The workgroups of a group take the same sequence of vocabulary tiles, one hidden
+  // tile each; having identical work they advance together, so the weight tile they share is
+  // fetched from HBM once and found in the XCD's L2 by the others, and the groups of an XCD read
+  // the same K range of the hidden rows at about the same time.
   const int id = blockIdx.x;
   const int xcd = id % kXcds;
   const int slot = id / kXcds;
   const int m_tile = slot % m_tiles;
-  const int v_tile = (slot / m_tiles) * kXcds + xcd;
-  if (v_tile >= v_tiles) return;
-  const int v0 = v_tile * TV;
   const int m0 = m_tile * TM;
   const int kp = K / 8;  // 16-byte pieces per matrix row (K % 8 == 0)
+#pragma unroll 1
+  for (int v_tile = (slot / m_tiles) * kXcds + xcd; v_tile < v_tiles; v_tile += groups * kXcds) {
+  const int v0 = v_tile * TV;
 
   // Global -> LDS without passing through registers (global_load_lds_dwordx4): one instruction
   // moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS, i.e. 8 consecutive tile rows of 8
@@ -129,8 +134,7 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   }
   // Everything but this wavefront's W_GROUPS newest loads (the weight rows of the step after
   // next, which stay in flight across the barrier) has landed in LDS; after the barrier,
-  // everybody's has.  Every LDS read of the step has been consumed by an MFMA before this
-  // point, so no LDS counter wait is needed.
+  // everybody's has.
   static_assert(W_GROUPS == 4, "the wait below leaves W_GROUPS loads outstanding");
 #define HB_STEP_DONE() asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory")
 #define HB_LOAD_FRAGS(ks_, slot_)                                                                \
@@ -141,57 +145,70 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
     _Pragma("unroll") for (int j = 0; j < MT; ++j)                                                \
         b[slot_][j] = __builtin_bit_cast(bf16x8, chh[swz(wm * 32 * MT + j * 32 + frag_row, c)]); \
   }
-  // One K step from LDS buffer buf_: the operand fragments of MFMA step ks+1 are read from LDS
-  // before the MFMAs of step ks are issued (two fragment sets), and nothing is scheduled across
-  // the step boundaries, so an LDS read always has a full step of matrix work to complete.
-#define HB_COMPUTE(wslot_, hslot_, kw_, wfree_)                                                  \
+  // The MFMAs of one 16-k sub-step from fragment set set_.
+#define HB_MFMAS(set_)                                                                           \
   {                                                                                              \
-    const u32x4 *cw = lw + (wslot_) * TV * CH;                                                   \
-    const u32x4 *chh = lh + (hslot_) * TM * CH;                                                  \
-    bf16x8 a[2][VT], b[2][MT];                                                                   \
-    HB_LOAD_FRAGS(0, 0);                                                                         \
-    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
-      if (ks + 1 < BK / 16) HB_LOAD_FRAGS(ks + 1, (ks + 1) & 1);                                 \
-      _Pragma("unroll") for (int i = 0; i < VT; ++i)                                              \
-        _Pragma("unroll") for (int j = 0; j < MT; ++j)                                            \
-          {                                                                                      \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0); \
-            asm volatile("" : "+a"(acc[i][j])); /* keep the accumulator in place in AGPRs */     \
-          }                                                                                      \
-      __builtin_amdgcn_sched_barrier(0);                                                         \
-      if (ks == kWIssueAt) {                                                                     \
-        HB_ISSUE_W(kw_, wfree_);                                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                       \
-      }                                                                                          \
-    }                                                                                            \
+    _Pragma("unroll") for (int i = 0; i < VT; ++i)                                                \
+      _Pragma("unroll") for (int j = 0; j < MT; ++j)                                              \
+        {                                                                                        \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set_][i], b[set_][j], acc[i][j], 0, 0, 0); \
+          asm volatile("" : "+a"(acc[i][j])); /* keep the accumulator in place in AGPRs */       \
+        }                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
   }
 
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
-  // Weight tiles (mostly from HBM) are fetched two K steps ahead into a ring of three LDS
-  // stages, hidden tiles (cache resident) one step ahead into two: at any time a wavefront has
-  // loads in flight, also across the barrier, and a weight load has two steps of matrix work to
-  // hide behind.  A fetch past the end repeats the last step (no branch in the loop); nothing
-  // reads it.
-  // The hidden loads of the next step go first, at the start of a step, and the weight loads
-  // of the step after next follow after kWIssueAt + 1 of the 4 MFMA sub-steps: the urgent loads
-  // get the CU's memory pipeline to themselves, and the pipeline has work throughout the step.
-  constexpr int kWIssueAt = 1;
+  // Pipeline.  Weight tiles (mostly from HBM) are fetched two K steps ahead into a ring of three
+  // LDS stages, hidden tiles (cache resident) one step ahead into two; a fetch past the end
+  // repeats the last step (no branch in the loop) and nothing reads it.  A K step is four 16-k
+  // MFMA sub-steps with two operand fragment sets: the fragments of sub-step s + 1 are read from
+  // LDS before the MFMAs of sub-step s are issued.  The barrier that ends step t sits BEFORE the
+  // MFMAs of its last sub-step, whose fragments are in registers by then: a wavefront is done
+  // with stage t at that point, and behind the barrier it first reads the fragments of
+  // (t + 1, sub-step 0) and then issues the remaining MFMAs of step t, which cover that read.
+  // Between two barriers a wavefront issues the hidden loads of step t + 2 (first, right after
+  // the barrier: they are needed at the next one) and the weight loads of step t + 2 (mid-step);
+  // the wait before a barrier leaves the newest W_GROUPS loads, those weight rows, in flight.
   const int last = k_steps - 1;
   HB_ISSUE_H(0, 0);
   HB_ISSUE_W(0, 0);
   HB_ISSUE_W((1 < last ? 1 : last), 1);
   HB_STEP_DONE();
+  HB_ISSUE_H((1 < last ? 1 : last), 1);
   int w_cur = 0, w_nxt = 1, w_free = 2;  // weight stages of steps kt, kt + 1 and the free one
+  const u32x4 *cw = lw;
+  const u32x4 *chh = lh;
+  bf16x8 a[2][VT], b[2][MT];
+  HB_LOAD_FRAGS(0, 0);
 #pragma unroll 1
   for (int kt = 0; kt < k_steps; ++kt) {
-    HB_ISSUE_H((kt + 1 < last ? kt + 1 : last), (kt + 1) & 1);
-    HB_COMPUTE(w_cur, kt & 1, (kt + 2 < last ? kt + 2 : last), w_free);
+    HB_LOAD_FRAGS(1, 1);
+    HB_MFMAS(0);
+    HB_LOAD_FRAGS(2, 0);
+    HB_MFMAS(1);
+    HB_ISSUE_W((kt + 2 < last ? kt + 2 : last), w_free);
+    __builtin_amdgcn_sched_barrier(0);
+    HB_LOAD_FRAGS(3, 1);
+    HB_MFMAS(0);
+    // Every LDS read of step kt must have returned before the barrier frees its stage.  Naming
+    // the last fragment set as an asm operand makes the compiler wait for it here, and lets it
+    // know that the MFMAs behind the barrier have nothing to wait for.
+#pragma unroll
+    for (int i = 0; i < VT; ++i) asm volatile("" : "+v"(a[1][i]));
+#pragma unroll
+    for (int j = 0; j < MT; ++j) asm volatile("" : "+v"(b[1][j]));
     HB_STEP_DONE();
+    HB_ISSUE_H((kt + 2 < last ? kt + 2 : last), kt & 1);
     const int t = w_cur;
     w_cur = w_nxt;
     w_nxt = w_free;
     w_free = t;
+    cw = lw + w_cur * TV * CH;
+    chh = lh + ((kt + 1) & 1) * TM * CH;
+    HB_LOAD_FRAGS(0, 0);  // of step kt + 1 (after the last step: unused)
+    __builtin_amdgcn_sched_barrier(0);
+    HB_MFMAS(1);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();  // all tile loads landed, all operand reads done: LDS is free for row_key
@@ -199,7 +216,7 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
 #undef HB_ISSUE_W
 #undef HB_ISSUE_H
 #undef HB_STEP_DONE
-#undef HB_COMPUTE
+#undef HB_MFMAS
 #undef HB_LOAD_FRAGS
 
   // Epilogue.  Accumulator r of lane l in tile (i, j) is C^T[v, m] with
@@ -236,6 +253,8 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
     // skip the atomic when the row already holds something at least as good
     if (key > __atomic_load_n(&keys[m], __ATOMIC_RELAXED)) atomicMax(&keys[m], key);
   }
+  __syncthreads();  // row_key shares LDS with the stages the next vocabulary tile fills
+  }  // vocabulary tiles of this workgroup
 }
 
 template <int MT, int WV>
@@ -244,13 +263,18 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, u
   constexpr int TM = 64 * MT;
   int m_tiles = (M + TM - 1) / TM;
   int v_tiles = (V + TV - 1) / TV;
-  int v_groups = (v_tiles + kXcds - 1) / kXcds;
+  // groups per XCD: as many as its 32 CUs hold with one workgroup per CU, but no more than
+  // there are vocabulary tiles to hand out
+  int groups = 32 / m_tiles;
+  if (groups < 1) groups = 1;
+  int need = (v_tiles + kXcds - 1) / kXcds;
+  if (groups > need) groups = need;
   size_t lds_bytes = (size_t)(3 * TV + 2 * TM) * CH * sizeof(u32x4);
   auto kern = lmhead_mfma_kernel<MT, WV>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
-  dim3 grid((unsigned)(v_groups * m_tiles * kXcds));
-  kern<<<grid, 128 * WV, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const u32x4 *)hidden, (const u32x4 *)weight, keys);
+  dim3 grid((unsigned)(groups * m_tiles * kXcds));
+  kern<<<grid, 128 * WV, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, groups, (const u32x4 *)hidden, (const u32x4 *)weight, keys);
   return hipGetLastError();
 }
 
