@@ -23,6 +23,25 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 
+# HBM traffic of one LM-head launch on this workload, from hardware counters (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB device copy in the same
+# run: `--copy-probe`).  Valid only for the kernel source it was measured on: keyed by the
+# first 16 hex digits of the SHA-256 of csrc/lmhead_mfma.hip, anything else reports null.
+LMHEAD_TRAFFIC = {
+    "f4252b4ce74ce736": {"fetch_bytes": 1.8068e9, "write_bytes": 2.06e5, "bytes": 1.8070e9,
+                         "algorithmic_bytes": 152064 * 3584 * 2 + 960 * 3584 * 2},
+}
+
+
+def _lmhead_traffic():
+    import hashlib
+    path = os.path.join(ROOT, "paper_2509_18824_amd", "csrc", "lmhead_mfma.hip")
+    try:
+        key = hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return LMHEAD_TRAFFIC.get(key)
+
 
 def _events(n):
     import torch
@@ -33,10 +52,11 @@ def _mean_ms(pairs):
     return sum(a.elapsed_time(b) for a, b in pairs) / max(len(pairs), 1)
 
 
-def cpu_baseline(inp, weight, draft_ids, sample_per_seq=4):
+def cpu_baseline(inp, weight, draft_ids, sample_per_seq=60, passes=3):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: `sample_per_seq`
-    nodes of every sequence go through attention and the LM head (weight widened to float64
-    once, as the oracle does), then acceptance and compaction run on the whole batch."""
+    nodes of every sequence (all 60 by default) go through attention and the LM head (weight
+    widened to float64 every pass, as the oracle does), then acceptance and compaction run on
+    the whole batch; `passes` such passes (about 10-20 s of CPU work in all)."""
     import numpy as np
     import workloads as W
     from oracle import tree_attn_ref, lmhead_argmax_ref, tree_accept_ref, kv_compact_ref
@@ -46,32 +66,37 @@ def cpu_baseline(inp, weight, draft_ids, sample_per_seq=4):
     nodes = sorted(int(off[b] + i) for b in range(inp.B)
                    for i in rng.choice(off[b + 1] - off[b], size=min(sample_per_seq, off[b + 1] - off[b]),
                                        replace=False))
-    t0 = time.perf_counter()
-    out, _ = tree_attn_ref(W.widen(inp.q), W.widen(inp.k_tree), W.widen(inp.v_tree), W.widen(inp.k_pool),
-                           W.widen(inp.v_pool), inp.block_table.numpy(), inp.prefix_len.numpy(),
-                           inp.node_offset.numpy(), inp.parent.numpy(), inp.softmax_scale, nodes=nodes)
-    t1 = time.perf_counter()
-    hidden = out.reshape(len(nodes), -1)
-    ids, _ = lmhead_argmax_ref(hidden, W.widen(weight))
-    t2 = time.perf_counter()
-    target = np.zeros(inp.total_nodes, dtype=np.int64)
-    target[nodes] = ids
-    alen, apath, _, _ = tree_accept_ref(off, inp.parent.numpy(), draft_ids, target, inp.max_path)
     bits = lambda t: t.view(__import__("torch").int16).numpy()
-    kv_compact_ref(bits(inp.k_tree), bits(inp.v_tree), bits(inp.k_pool), bits(inp.v_pool),
-                   inp.block_table.numpy(), inp.prefix_len.numpy(), off, alen, apath)
-    t3 = time.perf_counter()
+    t_attn = t_lm = t_rest = 0.0
+    for _ in range(passes):
+        t0 = time.perf_counter()
+        out, _ = tree_attn_ref(W.widen(inp.q), W.widen(inp.k_tree), W.widen(inp.v_tree), W.widen(inp.k_pool),
+                               W.widen(inp.v_pool), inp.block_table.numpy(), inp.prefix_len.numpy(),
+                               inp.node_offset.numpy(), inp.parent.numpy(), inp.softmax_scale, nodes=nodes)
+        t1 = time.perf_counter()
+        hidden = out.reshape(len(nodes), -1)
+        ids, _ = lmhead_argmax_ref(hidden, W.widen(weight))
+        t2 = time.perf_counter()
+        target = np.zeros(inp.total_nodes, dtype=np.int64)
+        target[nodes] = ids
+        alen, apath, _, _ = tree_accept_ref(off, inp.parent.numpy(), draft_ids, target, inp.max_path)
+        kv_compact_ref(bits(inp.k_tree), bits(inp.v_tree), bits(inp.k_pool), bits(inp.v_pool),
+                       inp.block_table.numpy(), inp.prefix_len.numpy(), off, alen, apath)
+        t3 = time.perf_counter()
+        t_attn += t1 - t0
+        t_lm += t2 - t1
+        t_rest += t3 - t2
     cores = len(os.sched_getaffinity(0))
     for var in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
         if os.environ.get(var, "").isdigit():
             cores = min(cores, int(os.environ[var]))
-    total = t3 - t0
+    total = t_attn + t_lm + t_rest
     return {
-        "value": len(nodes) / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-        "sample": f"{len(nodes)} of {inp.total_nodes} tree nodes ({sample_per_seq} per sequence) through "
-                  f"attention ({t1 - t0:.1f} s) and the LM head over the full vocabulary ({t2 - t1:.1f} s, "
-                  f"includes widening the weight to float64 once); acceptance and compaction on the whole "
-                  f"batch ({t3 - t2:.2f} s); float64 numpy",
+        "value": passes * len(nodes) / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+        "sample": f"{passes} passes over {len(nodes)} of {inp.total_nodes} tree nodes ({sample_per_seq} per "
+                  f"sequence): attention ({t_attn:.1f} s), LM head over the full vocabulary ({t_lm:.1f} s, "
+                  f"includes widening the weight to float64), acceptance and compaction on the whole "
+                  f"batch ({t_rest:.2f} s); float64 numpy",
         "seconds": total,
     }
 
@@ -131,6 +156,9 @@ def main():
     ap.add_argument("--no-attn-extra", action="store_true", help="skip the attention-only runs of the "
                     "ragged-batch and long-context workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true", help="also run three 1 GiB device-to-device "
+                    "copies before the timed region: the known-size reference for scaling the "
+                    "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
@@ -166,6 +194,14 @@ def main():
     for _ in range(args.warmup):
         step.run()
     torch.cuda.synchronize()
+
+    if args.copy_probe:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # timed region: exactly `steps` full steps; HIP events bracket each call inside it
     ev_attn, ev_lm, ev_acc, ev_cmp = (_events(args.steps) for _ in range(4))
@@ -230,7 +266,7 @@ def main():
             "unit": "TFLOP/s" if M >= 512 else "GB/s",
             "frac": (lm_tflops / PEAK_BF16_TFLOPS) if M >= 512
             else (V * K * 2 + M * K * 2) / (ms_lm * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "traffic": None,
+            "traffic": _lmhead_traffic() if args.tree == "tree" else None,
             "ms": ms_lm,
         },
         "kernels_ms": {"tree_verify_attn": ms_attn, "lmhead_argmax": ms_lm, "tree_accept": ms_acc,
