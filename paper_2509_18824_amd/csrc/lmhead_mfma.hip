@@ -6,17 +6,23 @@
 // entries v.  The row-wise argmax is then an in-register scan, one exchange between the two
 // lane halves, and one 64-bit atomic max per (row, workgroup).
 //
-// Workgroup: 256 threads = 4 wavefronts in a 2 (v) x 2 (m) arrangement; workgroup tile
-// TV = 256 vocabulary rows x TM = 64 * MT hidden rows, K step 64.  Both operands are
+// Workgroup: 512 threads = 8 wavefronts (two per SIMD) in a 4 (v) x 2 (m) arrangement; workgroup
+// tile TV = 256 vocabulary rows x TM = 64 * MT hidden rows, K step 64.  Both operands are
 // K-contiguous in memory ([V, K] and [M, K] row-major), which is exactly what the MFMA operand
 // layout wants (8 consecutive k per lane), so tiles go global -> LDS directly as 16-byte pieces
 // (global_load_lds), XOR-swizzled so that the 16-byte operand reads of 8 consecutive rows hit
-// all banks.  LDS is double buffered: the loads of K step t+1 are issued before the MFMAs of
-// step t and fill the other buffer while they run; one barrier per K step.
+// all banks.  Weight tiles sit in a ring of three LDS stages and are fetched two K steps ahead,
+// hidden tiles in two stages one step ahead; one barrier per K step, placed before the step's
+// last MFMAs (see the pipeline comment in the kernel).
 //
-// Grid order: consecutive workgroup ids go to different XCDs (id % 8).  The m tiles of one v
-// tile are given ids 8 apart, i.e. consecutive slots of the same XCD, so they run together and
-// the weight tile they share is fetched from HBM once and hit in that XCD's L2 afterwards.
+// What bounds the kernel is the path L2 -> LDS: a 256 x 192 tile needs one operand byte per 110
+// flop, and all CUs together draw about 10 KB per clock from the L2s at best, so operand
+// delivery and the matrix cores are busy for about the same number of cycles.  Everything here
+// serves to keep both going at once: loads in flight across barriers, no burst at a step start,
+// workgroups in lockstep so that shared tiles are fetched from HBM once.
+//
+// Grid: persistent workgroups, one per CU, in groups that walk the vocabulary tiles in lockstep
+// (one hidden tile per member) on one XCD.
 #include "hb_internal.h"
 
 namespace hb {
