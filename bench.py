@@ -150,8 +150,8 @@ def bench_attention_only(cfg, steps, warmup, n_pools=4):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--tree", choices=["tree", "chain8"], default="tree")
     ap.add_argument("--no-attn-extra", action="store_true", help="skip the attention-only runs of the "
                     "ragged-batch and long-context workloads")
