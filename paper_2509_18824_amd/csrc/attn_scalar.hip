@@ -134,54 +134,63 @@ __global__ __launch_bounds__(64) void attn_scalar_kernel(
 }
 
 // out[row] = sum_c O_c e^{m_c - m} / sum_c l_c e^{m_c - m}; chunks with l_c == 0 are empty and
-// their O_c was never written.  One wavefront per row; the loads of up to kMergeBatch chunks are
-// issued together before any arithmetic, so the kernel runs at memory rate instead of one chunk
-// latency at a time.
+// their O_c was never written.  One thread per four consecutive d of a row (D / 4 threads per
+// row, 16-byte loads and stores); every thread reads its row's (m_c, l_c) pairs itself (they are
+// a few cached bytes), and the loads of up to kMergeBatch chunks are issued together before any
+// arithmetic, so the kernel runs at memory rate instead of one chunk latency at a time.
 constexpr int kMergeBatch = 8;
+typedef float merge_f32x4 __attribute__((ext_vector_type(4)));
+typedef float merge_f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t merge_u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ inline void store_row4(float *p, merge_f32x4 v) { *reinterpret_cast<merge_f32x4 *>(p) = v; }
+__device__ inline void store_row4(bf16_t *p, merge_f32x4 v) {
+  merge_u32x2 w;
+  w.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+  w.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+  *reinterpret_cast<merge_u32x2 *>(p) = w;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void attn_merge_kernel(int rows, int D, int splits,
                                                          const float *__restrict__ part_o,
                                                          const float *__restrict__ part_ml,
                                                          T *__restrict__ out, float *__restrict__ lse) {
-  const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
-  const int lane = threadIdx.x & 63;
+  const int tpr = D >> 2;  // threads per row (D % 4 == 0)
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const int row = (int)(gid / tpr);
+  const int piece = (int)(gid - (long)row * tpr);
   if (row >= rows) return;
-  const float *ml = part_ml + (size_t)row * splits * 2;
+  const merge_f32x2 *ml = reinterpret_cast<const merge_f32x2 *>(part_ml) + (size_t)row * splits;
   float m = -__builtin_huge_valf();
-  for (int c = lane; c < splits; c += 64)
-    if (ml[c * 2 + 1] > 0.f) m = fmaxf(m, ml[c * 2]);
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  for (int c = 0; c < splits; ++c) {
+    merge_f32x2 x = ml[c];
+    if (x.y > 0.f) m = fmaxf(m, x.x);
+  }
+  const merge_f32x4 *po = reinterpret_cast<const merge_f32x4 *>(part_o) + (size_t)row * splits * tpr + piece;
   float l = 0.f;
-  float acc[kMaxPerLane] = {0.f, 0.f, 0.f, 0.f};
+  merge_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int c0 = 0; c0 < splits; c0 += kMergeBatch) {
-    float w[kMergeBatch], o[kMergeBatch][kMaxPerLane];
+    float w[kMergeBatch];
+    merge_f32x4 o[kMergeBatch];
 #pragma unroll
     for (int i = 0; i < kMergeBatch; ++i) {
       const int c = c0 + i;
-      float lc = c < splits ? ml[c * 2 + 1] : 0.f;
-      const bool live = lc > 0.f;
-      w[i] = live ? expf(ml[c * 2] - m) : 0.f;
-      l += live ? lc * w[i] : 0.f;
-      const float *po = part_o + ((size_t)row * splits + (live ? c : 0)) * D;
-#pragma unroll
-      for (int e = 0; e < kMaxPerLane; ++e) {
-        int dd = lane + 64 * e;
-        o[i][e] = (live && dd < D) ? po[dd] : 0.f;  // select: an empty chunk's slot is never read
-      }
+      merge_f32x2 x = {0.f, 0.f};
+      if (c < splits) x = ml[c];
+      const bool live = x.y > 0.f;
+      w[i] = live ? expf(x.x - m) : 0.f;
+      l += live ? x.y * w[i] : 0.f;
+      merge_f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (live) v = po[(size_t)c * tpr];  // an empty chunk's slot is never read
+      o[i] = v;
     }
 #pragma unroll
-    for (int i = 0; i < kMergeBatch; ++i)
-#pragma unroll
-      for (int e = 0; e < kMaxPerLane; ++e) acc[e] = fmaf(o[i][e], w[i], acc[e]);
+    for (int i = 0; i < kMergeBatch; ++i) acc += o[i] * w[i];
   }
-  float inv = l > 0.f ? 1.f / l : 0.f;
-#pragma unroll
-  for (int e = 0; e < kMaxPerLane; ++e) {
-    int dd = lane + 64 * e;
-    if (dd < D) store_f32(out + (size_t)row * D + dd, acc[e] * inv);
-  }
-  if (lse && lane == 0) lse[row] = m + logf(l);
+  const float inv = l > 0.f ? 1.f / l : 0.f;
+  store_row4(out + (size_t)row * D + piece * 4, acc * inv);
+  if (lse && piece == 0) lse[row] = m + logf(l);
 }
 
 }  // namespace
@@ -207,7 +216,8 @@ hipError_t launch_attn_scalar(const hb_attn_desc &d, const AttnPlan &plan, const
 hipError_t launch_attn_merge(const hb_attn_desc &d, const AttnPlan &plan, const float *part_o,
                              const float *part_ml, void *out, float *lse, hipStream_t s) {
   int rows = d.total_nodes * d.num_q_heads;
-  dim3 grid((unsigned)((rows + 3) / 4));
+  long threads = (long)rows * (d.head_dim / 4);
+  dim3 grid((unsigned)((threads + 255) / 256));
   if (d.dtype == HB_F32)
     attn_merge_kernel<float><<<grid, 256, 0, s>>>(rows, d.head_dim, plan.splits, part_o, part_ml, (float *)out, lse);
   else
