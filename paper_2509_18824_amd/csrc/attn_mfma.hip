@@ -1,11 +1,12 @@
 // Tree-verify attention on the bf16 matrix cores of gfx950 (head_dim 128, page size 16).
 //
-// One workgroup (4 wavefronts) owns one (sequence, kv head, KV chunk, row group).  Every KV
-// tile it streams is staged once in LDS and used by all query rows of the group: rows of many
-// tree nodes and of every query head of the kv group (N * G rows in all, 420 for 60 nodes and
-// GQA 7:1, split into row groups of at most 128 rows whose workgroups sit on one XCD and share
-// the KV stream in its L2), which is what turns the memory-bound decode step into a
-// compute-dense one.
+// One workgroup owns one (sequence, kv head, KV chunk, row group).  Every KV tile it streams is
+// staged once in LDS and used by all query rows of the group: rows of many tree nodes and of
+// every query head of the kv group (N * G rows in all, 420 for 60 nodes and GQA 7:1), which is
+// what turns the memory-bound decode step into a compute-dense one.  Up to 128 rows: four
+// wavefronts, two workgroups per CU.  More: eight wavefronts and up to 256 rows per workgroup
+// (staging a tile costs as much as the matrix work on 128 rows, so sharing it among twice the
+// rows pays), row groups of one item on one XCD so that they share the KV stream in its L2.
 //
 // Formulation (transposed, so no score ever crosses lanes on its way into the second GEMM):
 //   S^T = K Q^T     MFMA 16x16x32: A = K tile (16 keys x 32 d), B = Q^T (32 d x 16 rows)
@@ -21,10 +22,10 @@
 // every step would cost more vector work than the attention itself.  Row sums stay per lane
 // until the end.
 //
-// Rows: row r = node * G + head_in_group, tiles of 16 rows dealt round-robin to the four
+// Rows: row r = node * G + head_in_group, tiles of 16 rows dealt round-robin to the
 // wavefronts; Q fragments and the fp32 O^T accumulators of a wavefront's (at most TPW = 2) tiles
-// live in registers for the whole kernel, within 256 registers so that two workgroups share a
-// CU and one's matrix work overlaps the other's vector work and waits.
+// live in registers for the whole kernel, within 256 registers so that a CU holds eight
+// wavefronts and one's matrix work overlaps another's vector work and waits.
 //
 // Keys: chunk 0 starts with one 64-key tile holding the tree nodes (masked per row by the
 // node's ancestor bitmask), then every chunk streams its share of the prefix through the page
@@ -125,26 +126,33 @@ __device__ __forceinline__ void store_k(u32x4 *__restrict__ lk, int tid, u32x4 k
   lk[(krow + 48) * 16 + (piece ^ krow)] = k3;
 }
 
-// Registers -> LDS, V, transposed on the way.  Per d row (64 bytes, row index XORed in its low
-// two bits to spread the writes) the 32 keys of a block are stored in the order
-// (key%16)/4, key/16, key%4, so that the eight keys lane group kg needs as MFMA k-slots are the
-// 16 contiguous bytes at offset 16*kg.
+// Byte offset, inside a 32-key block of the V^T tile, of the 16 bytes that hold the eight keys
+// of lane group kg for head dimension d.  A d row is 64 bytes (four 16-byte slots, one per lane
+// group); the row index is XORed in its low two bits and the slot index with bits 2..3 of d, so
+// that the 16 lanes of a lane group, which read 16 consecutive d, cover all sixteen 16-byte bank
+// groups of the LDS instead of piling up on four of them.
+__device__ __forceinline__ int vt_offset(int d, int kg) {
+  return (d ^ ((d >> 3) & 3)) * 64 + 16 * (kg ^ ((d >> 2) & 3));
+}
+
+// Registers -> LDS, V, transposed on the way.  Per d row the 32 keys of a block are stored in
+// the order (key%16)/4, key/16, key%4, so that the eight keys lane group kg needs as MFMA
+// k-slots are 16 contiguous bytes (slot kg of the row, permuted as vt_offset says).
 __device__ __forceinline__ void store_v(unsigned char *__restrict__ lv, int tid, u32x4 v0, u32x4 v1, u32x4 v2,
                                         u32x4 v3) {
   const int piece = tid & 15;
   const int q = tid >> 4;                   // key quad: keys 4q .. 4q+3
   const int blk32 = q >> 3;                 // which 32-key block
   const int a = (q & 7) >> 2, kg = q & 3;   // key = 32*blk32 + 16*a + 4*kg + c
-  unsigned char *base = lv + blk32 * (D * 64) + 16 * kg + 8 * a;
+  unsigned char *base = lv + blk32 * (D * 64) + 8 * a;
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     // even d = 8*piece + 2p: low halves; odd d: high halves
     u32x2 even = {(v0[p] & 0xffffu) | (v1[p] << 16), (v2[p] & 0xffffu) | (v3[p] << 16)};
     u32x2 odd = {(v0[p] >> 16) | (v1[p] & 0xffff0000u), (v2[p] >> 16) | (v3[p] & 0xffff0000u)};
     int d0 = 8 * piece + 2 * p, d1 = d0 + 1;
-    int r0 = d0 ^ ((d0 >> 3) & 3), r1 = d1 ^ ((d1 >> 3) & 3);
-    *(u32x2 *)(base + r0 * 64) = even;
-    *(u32x2 *)(base + r1 * 64) = odd;
+    *(u32x2 *)(base + vt_offset(d0, kg)) = even;
+    *(u32x2 *)(base + vt_offset(d1, kg)) = odd;
   }
 }
 
@@ -178,7 +186,7 @@ __device__ __forceinline__ float group_sum(float x) {
 // defines an O^T accumulator an empty asm statement with an "a" constraint pins the value to the
 // accumulation registers; with that the fp32 O^T of all tiles (224 registers for 7 tiles) stays
 // in place there instead of being shuffled through the vector registers every iteration.
-template <int TPW>
+template <int TPW, int NW>
 __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restrict__ lk, const unsigned char *__restrict__ lv,
                                              int blk32, int j, int kg, const bf16x8 (&qf)[TPW][4],
                                              f32x4 (&o)[TPW][8], float (&m_run)[TPW], float (&l_run)[TPW],
@@ -221,7 +229,7 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
         // (not arithmetic) removes forbidden scores, so NaN/Inf there cannot leak.
         uint32_t allow = ~0u;
         if (is_tree) {
-          int row = (wave + 4 * t) * 16 + j;  // `wave` here: the wavefront's first tile
+          int row = (wave + NW * t) * 16 + j;  // `wave` here: the wavefront's first tile
           int node = row < R ? row / G : 0;
           allow = (uint32_t)(anc_lds[node] >> (32 * blk32));
         }
@@ -246,6 +254,13 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       m_run[t] = m_new[u];
       mx_keep[u] = mx;
     }
+    // -- all V^T fragments of the block, issued now so that they arrive during the vector work
+    //    below (they take over the registers of the K fragments, which are done)
+    const unsigned char *vbase = lv + blk32 * (D * 64);
+    bf16x8 av[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) av[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vbase + vt_offset(16 * dt + j, kg)));
+    __builtin_amdgcn_sched_barrier(0);
     // -- rare: some row's maximum outgrew its reference; rescale the group's accumulators (rows
     //    that stay get alpha = 1).  One uniform branch per group; the asm statement keeps it a
     //    real branch, otherwise the multiply of the whole accumulator is speculated into every
@@ -286,32 +301,25 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       l_run[t] += psum;
       pb[u] = __builtin_convertvector(p, bf16x8);
     }
-    // -- O^T += V^T P^T for the group, one 16-d slab of V^T at a time; the slab for step dt+1 is
-    //    fetched from LDS before the matrix instructions of step dt are issued
-    const unsigned char *vbase = lv + blk32 * (D * 64) + 16 * kg;
-    bf16x8 av[2];
-    av[0] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vbase + (j ^ ((j >> 3) & 3)) * 64));
+    // -- O^T += V^T P^T for the group, one 16-d slab of V^T at a time
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
-      if (dt < 7) {
-        int dd = 16 * (dt + 1) + j;
-        av[(dt + 1) & 1] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vbase + (dd ^ ((dd >> 3) & 3)) * 64));
-      }
 #pragma unroll
       for (int u = 0; u < kGroup; ++u) {
         const int t = t0 + u;
         if (t >= TPW) break;
-        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dt & 1], pb[u], o[t][dt], 0, 0, 0);
+        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dt], pb[u], o[t][dt], 0, 0, 0);
         asm volatile("" : "+a"(o[t][dt]));
       }
-      // nothing moves across: the LDS read of the next slab stays ahead of its use by one step
-      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
 
-template <int TPW>
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
+// NW = 4: every thread stages four pieces of K and four of V per tile; two workgroups per CU.
+// NW = 8: wavefronts 0-3 stage K, wavefronts 4-7 stage V (in the same registers), one workgroup
+// per CU with twice the rows sharing each staged tile.
+template <int TPW, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     hb_attn_desc d, int splits, int chunk_tokens, int row_groups, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
     const u32x4 *__restrict__ v_tree, const u32x4 *__restrict__ k_pool, const u32x4 *__restrict__ v_pool,
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ prefix_len,
@@ -347,7 +355,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
   const int tiles_per_group = (NT + row_groups - 1) / row_groups;
   const int tile_lo = rgi * tiles_per_group;                     // this workgroup's tiles
   const int tile_hi = min(NT, tile_lo + tiles_per_group);
-  const int wtile = tile_lo + wave;    // the wavefront's tiles: wtile + 4*t < tile_hi
+  const int wtile = tile_lo + wave;    // the wavefront's tiles: wtile + NW*t < tile_hi
   int L = prefix_len[b];
   const int cap = d.max_blocks_per_seq * PAGE;
   L = L < 0 ? 0 : (L > cap ? cap : L);
@@ -368,7 +376,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
 
   if (!tree_chunk && begin >= L) {
     // an empty chunk only announces itself to the merge
-    for (int r = tile_lo * 16 + tid; r < min(R, tile_hi * 16); r += 256) {
+    for (int r = tile_lo * 16 + tid; r < min(R, tile_hi * 16); r += 64 * NW) {
       size_t rg = row_base + (size_t)(r / G) * d.num_q_heads + (r % G);
       part_ml[(rg * splits + c) * 2 + 0] = HB_NEG_INF;
       part_ml[(rg * splits + c) * 2 + 1] = 0.f;
@@ -395,8 +403,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
   bf16x8 qf[TPW][4];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
-    int row = (wtile + 4 * t) * 16 + j;
-    bool ok = row < R && (wtile + 4 * t) < tile_hi;
+    int row = (wtile + NW * t) * 16 + j;
+    bool ok = row < R && (wtile + NW * t) < tile_hi;
     int node = ok ? row / G : 0;
     int hg = ok ? row - node * G : 0;
     const u32x4 *src = q + (row_base + (size_t)node * d.num_q_heads + hg) * 16;
@@ -434,8 +442,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
 
   // Staging registers of the next tile; K and V are in flight at different times (K during the
   // first 32-key block of the current tile, V during the second).
-  u32x4 sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3;
-  const int piece = tid & 15, krow = tid >> 4;
+  u32x4 sk0, sk1, sk2, sk3, sv_own0, sv_own1, sv_own2, sv_own3;
+  u32x4 &sv0 = NW == 8 ? sk0 : sv_own0, &sv1 = NW == 8 ? sk1 : sv_own1, &sv2 = NW == 8 ? sk2 : sv_own2,
+        &sv3 = NW == 8 ? sk3 : sv_own3;
+  const bool do_k = NW == 4 || wave < 4;    // staging role of this wavefront
+  const bool do_v = NW == 4 || wave >= 4;
+  const int stid = tid & 255;               // thread index inside the staging role
+  const int swave = wave & 3;
+  const int piece = stid & 15, krow = stid >> 4;
   const size_t page_stride = (size_t)d.num_kv_heads * PAGE * 16;  // u32x4 units per page
   const u32x4 *k_lane = k_pool + (size_t)g * PAGE * 16 + krow * 16 + piece;
   const u32x4 *v_lane = v_pool + (size_t)g * PAGE * 16 + (4 * (krow & 3)) * 16 + piece;
@@ -474,8 +488,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
   }
 #define HB_LOAD_V(start_)                                                   \
   {                                                                         \
-    /* keys 4*krow .. 4*krow+3 sit in page krow >> 2 == wave of the tile */  \
-    const int pv__ = wave == 0 ? pg0 : (wave == 1 ? pg1 : (wave == 2 ? pg2 : pg3)); \
+    /* keys 4*krow .. 4*krow+3 sit in page krow >> 2 == swave of the tile */  \
+    const int pv__ = swave == 0 ? pg0 : (swave == 1 ? pg1 : (swave == 2 ? pg2 : pg3)); \
     const u32x4 *vp__ = v_lane + (size_t)pv__ * page_stride;                \
     sv0 = vp__[0];                                                          \
     sv1 = vp__[16];                                                         \
@@ -486,35 +500,39 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
 
   if (tree_chunk) {
     // the tree tile: keys are node ids, read straight from k_tree / v_tree (once per workgroup)
-    sk0 = load_k_piece(src, true, 0, 0, tid, 0);
-    sk1 = load_k_piece(src, true, 0, 0, tid, 1);
-    sk2 = load_k_piece(src, true, 0, 0, tid, 2);
-    sk3 = load_k_piece(src, true, 0, 0, tid, 3);
-    sv0 = load_v_piece(src, true, 0, 0, tid, 0);
-    sv1 = load_v_piece(src, true, 0, 0, tid, 1);
-    sv2 = load_v_piece(src, true, 0, 0, tid, 2);
-    sv3 = load_v_piece(src, true, 0, 0, tid, 3);
+    if (do_k) {
+      sk0 = load_k_piece(src, true, 0, 0, stid, 0);
+      sk1 = load_k_piece(src, true, 0, 0, stid, 1);
+      sk2 = load_k_piece(src, true, 0, 0, stid, 2);
+      sk3 = load_k_piece(src, true, 0, 0, stid, 3);
+    }
+    if (do_v) {
+      sv0 = load_v_piece(src, true, 0, 0, stid, 0);
+      sv1 = load_v_piece(src, true, 0, 0, stid, 1);
+      sv2 = load_v_piece(src, true, 0, 0, stid, 2);
+      sv3 = load_v_piece(src, true, 0, 0, stid, 3);
+    }
     HB_FETCH_PAGES(begin);  // the next tile is the first prefix tile
   } else {
     HB_FETCH_PAGES(begin);
-    HB_LOAD_K(begin);
-    HB_LOAD_V(begin);
+    if (do_k) HB_LOAD_K(begin);
+    if (do_v) HB_LOAD_V(begin);
     HB_FETCH_PAGES(begin + KT);
   }
 #define HB_STORE_K(dst_)                                                                      \
   {                                                                                           \
     const u32x4 z__ = {0u, 0u, 0u, 0u};                                                       \
-    store_k(dst_, tid, k_left > 0 ? sk0 : z__, k_left > 16 ? sk1 : z__, k_left > 32 ? sk2 : z__, \
+    store_k(dst_, stid, k_left > 0 ? sk0 : z__, k_left > 16 ? sk1 : z__, k_left > 32 ? sk2 : z__, \
             k_left > 48 ? sk3 : z__);                                                         \
   }
 #define HB_STORE_V(dst_)                                                                      \
   {                                                                                           \
     const u32x4 z__ = {0u, 0u, 0u, 0u};                                                       \
-    store_v(dst_, tid, v_left > 0 ? sv0 : z__, v_left > 1 ? sv1 : z__, v_left > 2 ? sv2 : z__,   \
+    store_v(dst_, stid, v_left > 0 ? sv0 : z__, v_left > 1 ? sv1 : z__, v_left > 2 ? sv2 : z__,   \
             v_left > 3 ? sv3 : z__);                                                          \
   }
-  HB_STORE_K(lds_k);
-  HB_STORE_V(lds_v);
+  if (do_k) HB_STORE_K(lds_k);
+  if (do_v) HB_STORE_V(lds_v);
   __syncthreads();
 
 #pragma unroll 1  // also keeps the compiler from peeling the tree tile's iteration into a second copy
@@ -533,18 +551,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
     for (int blk32 = 0; blk32 < 2; ++blk32) {
       if (has_next) {
         if (blk32 == 0) {
-          HB_LOAD_K(next_start);
+          if (do_k) HB_LOAD_K(next_start);
+          if (NW == 8 && do_v) HB_LOAD_V(next_start);
         } else {
-          HB_STORE_K(lds_k + (buf ^ 1) * K_PIECES);
-          HB_LOAD_V(next_start);
+          if (do_k) HB_STORE_K(lds_k + (buf ^ 1) * K_PIECES);
+          if (NW == 4) HB_LOAD_V(next_start);
           HB_FETCH_PAGES(next_start + KT);  // for the tile after the next
         }
       }
       if (32 * blk32 < n_valid)
-        attend_block<TPW>(partial, lk, lv, blk32, j, kg, qf, o, m_run, l_run, c1, n_valid, is_tree, anc_lds, wtile,
+        attend_block<TPW, NW>(partial, lk, lv, blk32, j, kg, qf, o, m_run, l_run, c1, n_valid, is_tree, anc_lds, wtile,
                           R, G);
     }
-    if (has_next) HB_STORE_V(lds_v + (buf ^ 1) * V_BYTES);
+    if (has_next && do_v) HB_STORE_V(lds_v + (buf ^ 1) * V_BYTES);
     __syncthreads();
   }
 #undef HB_PAGE
@@ -557,8 +576,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
   // ---- write out: lane (j, kg) holds O[row j][16*dt + 4*kg + r] ---------------------------
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
-    int row = (wtile + 4 * t) * 16 + j;
-    if ((wtile + 4 * t) >= tile_hi) continue;
+    int row = (wtile + NW * t) * 16 + j;
+    if ((wtile + NW * t) >= tile_hi) continue;
     float l_tot = group_sum(l_run[t]);
     if (row >= R) continue;
     int node = row / G, hg = row - node * G;
@@ -588,17 +607,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(
 
 constexpr size_t kLdsBytes = 2 * K_PIECES * 16 + 2 * V_BYTES + 64 * 8;
 
-template <int TPW>
+template <int TPW, int NW>
 hipError_t launch(int row_groups, const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
                   const void *v_tree, const void *k_pool, const void *v_pool, const int32_t *block_table,
                   const int32_t *prefix_len, const int32_t *node_offset, const int32_t *parent, void *out,
                   float *lse, float *part_o, float *part_ml, hipStream_t s) {
   const int items = d.batch * d.num_kv_heads * plan.splits;
   dim3 grid((unsigned)((items + 7) / 8 * 8 * row_groups));
-  auto kern = attn_mfma_kernel<TPW>;
+  auto kern = attn_mfma_kernel<TPW, NW>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
-  kern<<<grid, 256, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, row_groups, (const u32x4 *)q, (const u32x4 *)k_tree,
+  kern<<<grid, 64 * NW, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, row_groups, (const u32x4 *)q, (const u32x4 *)k_tree,
                                     (const u32x4 *)v_tree, (const u32x4 *)k_pool, (const u32x4 *)v_pool,
                                     block_table, prefix_len, node_offset, parent, (bf16_t *)out, lse, part_o,
                                     part_ml);
@@ -611,21 +630,27 @@ bool attn_mfma_supports(const hb_attn_desc &d) {
   if (d.dtype != HB_BF16 || d.head_dim != D || d.page_size != PAGE) return false;
   if (d.num_kv_heads <= 0 || d.num_q_heads % d.num_kv_heads) return false;
   int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
-  if (d.max_nodes_per_tree > 64 || rows > 512) return false;  // at most 4 row groups of 8 tiles
+  if (d.max_nodes_per_tree > 64 || rows > 512) return false;  // at most 2 row groups of 16 tiles
   if (!(d.softmax_scale > 0.f) || !(d.softmax_scale < 1e30f)) return false;  // base-2 max tracking needs scale > 0
   if (d.batch > 65535 || d.num_kv_heads > 65535) return false;
   return true;
 }
 
-// Row groups: workgroups that split the 16-row tiles of one (sequence, kv head, chunk) among
-// them and stream the same KV (shared through the XCD's L2).  Two tiles per wavefront (eight per
-// workgroup) keep a wavefront within 256 registers, so two workgroups fit a CU and one's matrix
-// work overlaps the other's vector work and waits.
-int32_t attn_mfma_row_groups(const hb_attn_desc &d) {
+// Workgroup shape.  Up to eight 16-row tiles: four wavefronts (one or two tiles each), two
+// workgroups per CU.  More: eight wavefronts with two tiles each (256 rows share every staged KV
+// tile, which halves the staging work and the L2 -> LDS traffic per row), one workgroup per CU,
+// and as many row groups as that takes; the row groups of one (sequence, kv head, chunk) stream
+// the same KV and share it through their XCD's L2.
+static int tiles_of(const hb_attn_desc &d) {
   int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
-  int tiles = (rows + 15) / 16;
-  int groups = (tiles + 7) / 8;
-  return groups < 1 ? 1 : groups;
+  return (rows + 15) / 16;
+}
+
+int32_t attn_mfma_waves(const hb_attn_desc &d) { return tiles_of(d) > 8 ? 8 : 4; }
+
+int32_t attn_mfma_row_groups(const hb_attn_desc &d) {
+  int tiles = tiles_of(d);
+  return tiles > 8 ? (tiles + 15) / 16 : 1;
 }
 
 hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
@@ -633,14 +658,13 @@ hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const v
                             const int32_t *block_table, const int32_t *prefix_len,
                             const int32_t *node_offset, const int32_t *parent, void *out, float *lse,
                             float *part_o, float *part_ml, hipStream_t s) {
-  int rows = (d.num_q_heads / d.num_kv_heads) * d.max_nodes_per_tree;
-  int tiles = (rows + 15) / 16;
+  const int tiles = tiles_of(d);
   const int row_groups = plan.row_groups;
-  int tpw = ((tiles + row_groups - 1) / row_groups + 3) / 4;  // row tiles per wavefront
-#define HB_GO(N) \
-  return launch<N>(row_groups, d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
-  if (tpw <= 1) HB_GO(1);
-  HB_GO(2);  // attn_mfma_row_groups keeps a workgroup at eight tiles or fewer
+#define HB_GO(N, W) \
+  return launch<N, W>(row_groups, d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
+  if (tiles <= 4) HB_GO(1, 4);
+  if (tiles <= 8) HB_GO(2, 4);
+  HB_GO(2, 8);  // attn_mfma_row_groups keeps a workgroup at sixteen tiles or fewer
 #undef HB_GO
 }
 

@@ -64,9 +64,10 @@ int32_t make_attn_plan(const hb_attn_desc *d, AttnPlan *plan) {
   if (splits == 0) {
     if (plan->mfma) {
       // Parallelism comes first from row groups (they cost no partials), then from KV chunks:
-      // aim at two workgroups per CU, keep a chunk at 1024 tokens or more
+      // aim at eight wavefronts on each of the 256 CUs, keep a chunk at 1024 tokens or more
       int64_t items = (int64_t)d->batch * d->num_kv_heads * plan->row_groups;
-      splits = items > 0 ? (512 + items - 1) / items : 1;
+      int64_t want = 256 * 8 / attn_mfma_waves(*d);
+      splits = items > 0 ? (want + items - 1) / items : 1;
       int64_t cap = (span + 1023) / 1024;
       if (splits > cap) splits = cap;
     } else {

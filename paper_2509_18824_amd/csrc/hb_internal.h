@@ -73,6 +73,7 @@ hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const v
                             float *part_ml, hipStream_t s);
 bool attn_mfma_supports(const hb_attn_desc &d);
 int32_t attn_mfma_row_groups(const hb_attn_desc &d);
+int32_t attn_mfma_waves(const hb_attn_desc &d);  // wavefronts per workgroup (4 or 8)
 hipError_t launch_attn_merge(const hb_attn_desc &d, const AttnPlan &plan, const float *part_o,
                              const float *part_ml, void *out, float *lse, hipStream_t s);
 
