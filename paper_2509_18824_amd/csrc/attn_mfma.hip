@@ -62,8 +62,8 @@ __device__ __forceinline__ uint32_t finite_or_zero_bf16x2(uint32_t w) {
 
 // Where one thread's pieces of a 64-key tile come from.  A tile holds either tree nodes (keys =
 // node ids < n_nodes, read from k_tree/v_tree) or prefix positions tile_start + key < end (read
-// through the page table).  Slots that are not valid keys are loaded as zeros: they are masked
-// in the scores, and a zero V keeps 0 * V finite.
+// through the page table).  Slots that are not valid keys are masked in the scores; their V is
+// staged as zeros, which keeps 0 * V finite.
 struct TileSrc {
   const u32x4 *k_tree, *v_tree, *k_pool, *v_pool;
   const int32_t *bt;  // page table row of the sequence
@@ -460,7 +460,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
   // (page ids are clamped into the pool, so every address is valid); slots at or past `end` are
   // replaced by zeros only when the registers are written to LDS, so that nothing touches the
   // loaded registers (and waits for memory) while the matrix work of the current tile runs.
-  int k_left = 64, v_left = 4;  // validity bounds of the staged tile, see HB_LOAD_K / HB_LOAD_V
+  int v_left = 4;        // validity bound of the staged V pieces, see HB_LOAD_V
+  bool v_tail = false;   // the staged tile has slots at or past `end` (uniform)
   const int last_page = d.max_blocks_per_seq - 1;
   // Page ids (clamped into the pool) of the tile that is loaded next; fetched one tile ahead so
   // that the scalar loads are long complete when the addresses are formed.
@@ -486,7 +487,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     sk1 = k_lane[(size_t)pg1 * page_stride];                                \
     sk2 = k_lane[(size_t)pg2 * page_stride];                                \
     sk3 = k_lane[(size_t)pg3 * page_stride];                                \
-    k_left = end - (start_) - krow; /* key krow+16i valid iff 16i < k_left */ \
   }
 #define HB_LOAD_V(start_)                                                   \
   {                                                                         \
@@ -498,6 +498,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     sv2 = vp__[32];                                                         \
     sv3 = vp__[48];                                                         \
     v_left = end - (start_) - 4 * krow; /* key 4*krow+i valid iff i < v_left */ \
+    v_tail = end - (start_) < KT;                                           \
   }
 
   if (tree_chunk) {
@@ -521,17 +522,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     if (do_v) HB_LOAD_V(begin);
     HB_FETCH_PAGES(begin + KT);
   }
-#define HB_STORE_K(dst_)                                                                      \
-  {                                                                                           \
-    const u32x4 z__ = {0u, 0u, 0u, 0u};                                                       \
-    store_k(dst_, stid, k_left > 0 ? sk0 : z__, k_left > 16 ? sk1 : z__, k_left > 32 ? sk2 : z__, \
-            k_left > 48 ? sk3 : z__);                                                         \
-  }
+  // K slots at or past `end` keep whatever the (valid) address held: their scores are replaced
+  // by a select before anything is computed from them.  V slots there must be zeros (0 * V).
+#define HB_STORE_K(dst_) store_k(dst_, stid, sk0, sk1, sk2, sk3)
 #define HB_STORE_V(dst_)                                                                      \
   {                                                                                           \
-    const u32x4 z__ = {0u, 0u, 0u, 0u};                                                       \
-    store_v(dst_, stid, v_left > 0 ? sv0 : z__, v_left > 1 ? sv1 : z__, v_left > 2 ? sv2 : z__,   \
-            v_left > 3 ? sv3 : z__);                                                          \
+    if (v_tail) { /* only the last tile of a chunk */                                          \
+      const u32x4 z__ = {0u, 0u, 0u, 0u};                                                     \
+      sv0 = v_left > 0 ? sv0 : z__;                                                           \
+      sv1 = v_left > 1 ? sv1 : z__;                                                           \
+      sv2 = v_left > 2 ? sv2 : z__;                                                           \
+      sv3 = v_left > 3 ? sv3 : z__;                                                           \
+    }                                                                                         \
+    store_v(dst_, stid, sv0, sv1, sv2, sv3);                                                  \
   }
   if (do_k) HB_STORE_K(lds_k);
   if (do_v) HB_STORE_V(lds_v);
