@@ -86,7 +86,9 @@ def test_ragged_edges_and_odd_shapes(hb, step):
     trees = [W.chain_tree(1), W.chain_tree(8), W.seeded_tree(1), W.seeded_tree(2, n_nodes=64),
              W.seeded_tree(3, n_nodes=17, levels=4, root_fanout=4), W.chain_tree(3), W.seeded_tree(4)]
     lens = [0, 5, 16, 63, 64, 65, 1000]
-    for dtype, Hq, Hkv, D in [("bf16", 28, 4, 128), ("bf16", 8, 8, 128), ("bf16", 8, 1, 128),
+    # (8, 8), (8, 4) and (28, 4) / (8, 1) give 64, 128 and 448 / 512 query rows per kv head: the
+    # three workgroup shapes of the matrix-core kernel
+    for dtype, Hq, Hkv, D in [("bf16", 28, 4, 128), ("bf16", 8, 8, 128), ("bf16", 8, 4, 128), ("bf16", 8, 1, 128),
                               ("f32", 6, 2, 64), ("bf16", 4, 2, 64), ("f32", 4, 4, 128)]:
         inp = W.make_verify_inputs(77, dtype, Hq, Hkv, D, lens, trees, kv_std=1.0, q_std=1.0)
         ref = oracle_attn(inp)
