@@ -13,7 +13,8 @@
 //   O^T = V^T P^T   MFMA 16x16x32: A = V^T (16 d x 32 keys),    B = P^T (32 keys x 16 rows)
 // The S^T accumulator of lane l holds, for query row l%16, the four keys 4*(l/16)+r of a 16-key
 // tile; two such tiles give the eight k-slots that the same lane must supply as the B operand
-// of the second MFMA, provided V^T is laid out in LDS with the matching key permutation.
+// of the second MFMA, provided the V^T operand is read with the matching key order (the
+// transposing LDS reads of the PV step fetch keys 16h + 4*(l/16) + 0..3 for h = 0, 1).
 // Softmax is online per row in base 2 (scores scaled by softmax_scale*log2 e) against a
 // reference exponent per row that is shared by the four lane groups of the row (two cross-lane
 // exchanges per 32 keys).  The reference is the first block maximum the row sees and moves
@@ -29,8 +30,9 @@
 //
 // Keys: chunk 0 starts with one 64-key tile holding the tree nodes (masked per row by the
 // node's ancestor bitmask), then every chunk streams its share of the prefix through the page
-// table in 64-key tiles, double buffered: global loads of tile i+1 are issued before the MFMAs
-// of tile i and written to the other LDS buffer afterwards.
+// table in 64-key tiles.  Prefix tiles go global -> LDS directly (no staging registers, no
+// transposition in the vector unit) into a ring of LDS stages, several tiles ahead of the one
+// being computed; V stays in memory order in LDS and is transposed by the LDS read itself.
 #include "hb_internal.h"
 
 namespace hb {
@@ -38,6 +40,10 @@ namespace hb {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) bf16x4 *lds_bf16x4_ptr;
+typedef __attribute__((address_space(1))) const void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -47,7 +53,7 @@ constexpr int D = 128;
 constexpr int PAGE = 16;
 constexpr int KT = 64;                 // keys per tile
 constexpr int K_PIECES = KT * 16;      // 16-byte pieces of a K tile (16 per key row)
-constexpr int V_BYTES = 2 * D * 64;    // V^T tile: 2 blocks of 32 keys x 128 d x 64 bytes
+constexpr int V_BYTES = KT * 256;      // V tile: 64 keys x 256 bytes
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 8.f;  // log2 units a row maximum may exceed its reference exponent
@@ -126,36 +132,22 @@ __device__ __forceinline__ void store_k(u32x4 *__restrict__ lk, int tid, u32x4 k
   lk[(krow + 48) * 16 + (piece ^ krow)] = k3;
 }
 
-// Byte offset, inside a 32-key block of the V^T tile, of the 16 bytes that hold the eight keys
-// of lane group kg for head dimension d.  A d row is 64 bytes (four 16-byte slots, one per lane
-// group).  Row and slot index are XORed with bits of d chosen by measurement on gfx950 (all
-// combinations of two shifts each were timed): with these the 16-byte fragment reads (lanes =
-// 16 consecutive d x 4 lane groups) run at the rate of a linear read and the 8-byte transposing
-// stores (lanes = 16 values of d, 8 apart, x 4 lane groups) within 20 % of a linear store; the
-// plain layout costs 1.8x and 4.7x.
-__device__ __forceinline__ int vt_offset(int d, int kg) {
-  return (d ^ ((d >> 4) & 3)) * 64 + 16 * (kg ^ (((d >> 1) ^ (d >> 5)) & 3));
-}
+// V tile in LDS: rows = keys, 256 bytes each, in memory order ([key][d]); the 16-byte piece index is
+// XORed with v_swz(key).  The MFMA wants V^T (8 consecutive keys per lane at one d); the
+// transposing LDS read (ds_read_b64_tr_b16) delivers exactly that from this layout: within 16
+// lanes, lane i receives element i%4 of the 8 bytes addressed by lanes i/4, i/4+4, i/4+8, i/4+12.
+// The swizzle was chosen by timing all XOR patterns of this family on gfx950: with it the
+// transposed reads run conflict free (4x faster than unswizzled).
+__device__ __forceinline__ int v_swz(int key) { return (key & 7) << 1; }
 
-// Registers -> LDS, V, transposed on the way.  Per d row the 32 keys of a block are stored in
-// the order (key%16)/4, key/16, key%4, so that the eight keys lane group kg needs as MFMA
-// k-slots are 16 contiguous bytes (slot kg of the row, permuted as vt_offset says).
-__device__ __forceinline__ void store_v(unsigned char *__restrict__ lv, int tid, u32x4 v0, u32x4 v1, u32x4 v2,
-                                        u32x4 v3) {
+// Registers -> LDS, V rows of the tree tile: d-piece (tid % 16) of keys 4*(tid/16) .. +3.
+__device__ __forceinline__ void store_v(u32x4 *__restrict__ lv, int tid, u32x4 v0, u32x4 v1, u32x4 v2, u32x4 v3) {
   const int piece = tid & 15;
-  const int q = tid >> 4;                   // key quad: keys 4q .. 4q+3
-  const int blk32 = q >> 3;                 // which 32-key block
-  const int a = (q & 7) >> 2, kg = q & 3;   // key = 32*blk32 + 16*a + 4*kg + c
-  unsigned char *base = lv + blk32 * (D * 64) + 8 * a;
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    // even d = 8*piece + 2p: low halves; odd d: high halves
-    u32x2 even = {(v0[p] & 0xffffu) | (v1[p] << 16), (v2[p] & 0xffffu) | (v3[p] << 16)};
-    u32x2 odd = {(v0[p] >> 16) | (v1[p] & 0xffff0000u), (v2[p] >> 16) | (v3[p] & 0xffff0000u)};
-    int d0 = 8 * piece + 2 * p, d1 = d0 + 1;
-    *(u32x2 *)(base + vt_offset(d0, kg)) = even;
-    *(u32x2 *)(base + vt_offset(d1, kg)) = odd;
-  }
+  const int key = 4 * (tid >> 4);
+  lv[(key + 0) * 16 + (piece ^ v_swz(key + 0))] = v0;
+  lv[(key + 1) * 16 + (piece ^ v_swz(key + 1))] = v1;
+  lv[(key + 2) * 16 + (piece ^ v_swz(key + 2))] = v2;
+  lv[(key + 3) * 16 + (piece ^ v_swz(key + 3))] = v3;
 }
 
 // 2^x by the hardware instruction: arguments here are <= 0 and results below the normal range
@@ -257,11 +249,23 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       mx_keep[u] = mx;
     }
     // -- all V^T fragments of the block, issued now so that they arrive during the vector work
-    //    below (they take over the registers of the K fragments, which are done)
-    const unsigned char *vbase = lv + blk32 * (D * 64);
+    //    below (they take over the registers of the K fragments, which are done).  Lane (s, kg)
+    //    of a 16-lane group addresses 8 bytes of key 16h + 4kg + s/4 at d = 16dt + 4(s%4); the
+    //    transposing read hands lane j the four keys 16h + 4kg + 0..3 at d = 16dt + j, i.e. the
+    //    k-slots 4h .. 4h+3 of the lane group in the order the score accumulators have.
     bf16x8 av[8];
+    {
+      const int vkey = 4 * kg + (j >> 2);                       // + 16h + 32 blk32
+      const int vrow = (32 * blk32 + vkey) * 256 + 16 * ((j >> 1) & 1) + 8 * (j & 1);
+      const int vx = v_swz(vkey) * 16;                          // XOR on the piece index, in bytes
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) av[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vbase + vt_offset(16 * dt + j, kg)));
+      for (int dt = 0; dt < 8; ++dt) {
+        const unsigned char *p0 = lv + vrow + ((32 * dt) ^ vx);
+        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
+        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 16 * 256));
+        av[dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    }
     __builtin_amdgcn_sched_barrier(0);
     // -- rare: some row's maximum outgrew its reference; rescale the group's accumulators (rows
     //    that stay get alpha = 1).  One uniform branch per group; the asm statement keeps it a
@@ -320,7 +324,7 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
 // NW = 4: every thread stages four pieces of K and four of V per tile; two workgroups per CU.
 // NW = 8: wavefronts 0-3 stage K, wavefronts 4-7 stage V (in the same registers), one workgroup
 // per CU with twice the rows sharing each staged tile.
-template <int TPW, int NW>
+template <int TPW, int NW, int NS>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     hb_attn_desc d, int splits, int chunk_tokens, int row_groups, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
     const u32x4 *__restrict__ v_tree, const u32x4 *__restrict__ k_pool, const u32x4 *__restrict__ v_pool,
@@ -328,10 +332,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     const int32_t *__restrict__ node_offset, const int32_t *__restrict__ parent, bf16_t *__restrict__ out,
     float *__restrict__ lse, float *__restrict__ part_o, float *__restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // [2][K tile 16 KiB] [2][V^T tile 16 KiB] [64 ancestor masks]
-  u32x4 *lds_k = (u32x4 *)smem;
-  unsigned char *lds_v = smem + 2 * K_PIECES * 16;
-  unsigned long long *anc_lds = (unsigned long long *)(smem + 2 * K_PIECES * 16 + 2 * V_BYTES);
+  // [NS stages][K tile 16 KiB | V tile 16 KiB] [64 ancestor masks]
+  constexpr int kStageBytes = K_PIECES * 16 + V_BYTES;
+  unsigned long long *anc_lds = (unsigned long long *)(smem + NS * kStageBytes);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -433,150 +436,174 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
   }
   const float c1 = d.softmax_scale * kLog2e;
 
-  // tiles: [tree tile] + prefix tiles of this chunk
-  const int n_prefix_tiles = end > begin ? (end - begin + KT - 1) / KT : 0;
-  const int n_tiles = n_prefix_tiles + (tree_chunk ? 1 : 0);
-
-  TileSrc src;
-  src.k_tree = k_tree; src.v_tree = v_tree; src.k_pool = k_pool; src.v_pool = v_pool;
-  src.bt = block_table + (size_t)b * d.max_blocks_per_seq;
-  src.g = g; src.n0 = n0; src.n_nodes = n_nodes; src.hkv = d.num_kv_heads; src.num_blocks = d.num_blocks;
-
-  // Staging registers of the next tile; K and V are in flight at different times (K during the
-  // first 32-key block of the current tile, V during the second).
-  u32x4 sk0, sk1, sk2, sk3, sv_own0, sv_own1, sv_own2, sv_own3;
-  u32x4 &sv0 = NW == 8 ? sk0 : sv_own0, &sv1 = NW == 8 ? sk1 : sv_own1, &sv2 = NW == 8 ? sk2 : sv_own2,
-        &sv3 = NW == 8 ? sk3 : sv_own3;
-  const bool do_k = NW == 4 || wave < 4;    // staging role of this wavefront
+  // ---- KV staging ---------------------------------------------------------------------------
+  // Prefix tiles go global -> LDS directly (global_load_lds_dwordx4, no staging registers): one
+  // instruction moves 64 lanes x 16 bytes = four consecutive keys x 256 bytes of K or of V into
+  // 1 KiB of a stage; the XOR swizzle of the LDS layouts is applied on the source side (the lane
+  // that fills physical piece p of a row fetches logical piece p ^ swizzle(row)).  A tile is 16
+  // such row groups of K and 16 of V; wavefront w issues groups w, w + NW, ... of both, which all
+  // have the same position inside their page, so one offset register each serves.  The page ids
+  // of a tile (wave-uniform scalar loads, clamped into the pool so every address is valid) are
+  // fetched one tile before they are needed.
+  // Tiles are loaded NS - 1 ahead of the one being computed.  Every pipeline step issues one
+  // batch of PER loads per wavefront, also past the end (then it re-fetches the last tile into a
+  // free stage), so that the wait "all but the newest PER * (NS - 2) loads" always means "the
+  // next tile has landed".
+  // Slots of a tile at or past `end`: K keeps whatever the (valid) address held, the scores are
+  // replaced by a select before anything is computed from them; the V rows are overwritten with
+  // zeros once they have landed (0 * V must stay finite).
+  constexpr int PER = 32 / NW;
+  const int stid = tid & 255;               // thread index inside a staging role (tree tile)
+  const bool do_k = NW == 4 || wave < 4;    // tree tile: who stages K, who stages V
   const bool do_v = NW == 4 || wave >= 4;
-  const int stid = tid & 255;               // thread index inside the staging role
-  const int swave = wave & 3;
-  const int piece = stid & 15, krow = stid >> 4;
+  const int lrow = lane >> 4;               // key inside a 4-key row group
+  const bool whi = wave >= 4;               // eight wavefronts: which pair of the tile's pages
+  const int gcls = wave & 3;                // row groups w + NW*i sit at keys 4*gcls .. +3 of their page
+  const int pkey = 4 * gcls + lrow;         // key inside the page
   const size_t page_stride = (size_t)d.num_kv_heads * PAGE * 16;  // u32x4 units per page
-  const u32x4 *k_lane = k_pool + (size_t)g * PAGE * 16 + krow * 16 + piece;
-  const u32x4 *v_lane = v_pool + (size_t)g * PAGE * 16 + (4 * (krow & 3)) * 16 + piece;
-  // Prefix tiles: the four pages of a tile are looked up once per workgroup (uniform index,
-  // scalar loads); every thread adds its fixed offset inside the page.  Loads are unconditional
-  // (page ids are clamped into the pool, so every address is valid); slots at or past `end` are
-  // replaced by zeros only when the registers are written to LDS, so that nothing touches the
-  // loaded registers (and waits for memory) while the matrix work of the current tile runs.
-  int v_left = 4;        // validity bound of the staged V pieces, see HB_LOAD_V
-  bool v_tail = false;   // the staged tile has slots at or past `end` (uniform)
+  const u32x4 *k_lane = k_pool + (size_t)g * PAGE * 16 + pkey * 16 + ((lane & 15) ^ pkey);
+  const u32x4 *v_lane = v_pool + (size_t)g * PAGE * 16 + pkey * 16 + ((lane & 15) ^ v_swz(pkey));
   const int last_page = d.max_blocks_per_seq - 1;
-  // Page ids (clamped into the pool) of the tile that is loaded next; fetched one tile ahead so
-  // that the scalar loads are long complete when the addresses are formed.
-  int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0;
+  const int n_prefix_tiles = end > begin ? (end - begin + KT - 1) / KT : 0;
+  const int tree_off = tree_chunk ? 1 : 0;
+  const int n_tiles = n_prefix_tiles + tree_off;
+  int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0;  // page ids of the batch issued next
 #define HB_PAGE(idx_)                                                        \
   ({                                                                         \
     int pg__ = (idx_) < last_page ? (idx_) : last_page;                      \
-    int blk__ = src.bt[pg__];                                                \
+    pg__ = pg__ < 0 ? 0 : pg__;                                              \
+    int blk__ = bt_row[pg__];                                                \
     blk__ = blk__ < 0 ? 0 : (blk__ >= d.num_blocks ? d.num_blocks - 1 : blk__); \
     blk__;                                                                   \
   })
-#define HB_FETCH_PAGES(start_)                                              \
+  // prefix tile (clamped to the chunk's last one) that pipeline step k_ loads
+#define HB_TILE_OF(k_)                                                       \
+  ({                                                                         \
+    int pt__ = ((k_) < tree_off ? tree_off : (k_)) - tree_off;               \
+    pt__ = pt__ < n_prefix_tiles - 1 ? pt__ : n_prefix_tiles - 1;            \
+    pt__ < 0 ? 0 : pt__;                                                     \
+  })
+#define HB_FETCH_PAGES(k_)                                                  \
   {                                                                         \
-    const int p0__ = (start_) / PAGE;                                       \
+    const int p0__ = (begin + HB_TILE_OF(k_) * KT) / PAGE;                  \
     pg0 = HB_PAGE(p0__ + 0);                                                \
     pg1 = HB_PAGE(p0__ + 1);                                                \
     pg2 = HB_PAGE(p0__ + 2);                                                \
     pg3 = HB_PAGE(p0__ + 3);                                                \
   }
-#define HB_LOAD_K(start_)                                                   \
-  {                                                                         \
-    sk0 = k_lane[(size_t)pg0 * page_stride];                                \
-    sk1 = k_lane[(size_t)pg1 * page_stride];                                \
-    sk2 = k_lane[(size_t)pg2 * page_stride];                                \
-    sk3 = k_lane[(size_t)pg3 * page_stride];                                \
+  // batch k_: the tile of pipeline step max(k_, tree_off) into stage max(k_, tree_off) % NS
+  // (in a tree chunk batch 0 loads the same as batch 1: stage 0 belongs to the tree tile)
+#define HB_ISSUE_BATCH(k_)                                                                     \
+  {                                                                                            \
+    const int t__ = (k_) < tree_off ? tree_off : (k_);                                         \
+    unsigned char *st__ = smem + (t__ % NS) * kStageBytes;                                     \
+    _Pragma("unroll") for (int i__ = 0; i__ < PER; ++i__) {                                     \
+      const int n__ = wave + NW * i__;          /* 0..15: K row group, 16..31: V row group */  \
+      /* page (n__ >> 2) & 3 of the tile: i__ & 3 for four wavefronts, else wave / 4 + 2 * (i__ & 1) */ \
+      const int pg__ = NW == 4 ? ((i__ & 3) == 0 ? pg0 : ((i__ & 3) == 1 ? pg1 : ((i__ & 3) == 2 ? pg2 : pg3))) \
+                               : ((i__ & 1) ? (whi ? pg3 : pg2) : (whi ? pg1 : pg0));                         \
+      const u32x4 *src__ = (n__ < 16 ? k_lane : v_lane) + (size_t)pg__ * page_stride;          \
+      __builtin_amdgcn_global_load_lds((gptr_t)src__, (lptr_t)(st__ + n__ * 1024), 16, 0, 0); \
+    }                                                                                          \
   }
-#define HB_LOAD_V(start_)                                                   \
-  {                                                                         \
-    /* keys 4*krow .. 4*krow+3 sit in page krow >> 2 == swave of the tile */  \
-    const int pv__ = swave == 0 ? pg0 : (swave == 1 ? pg1 : (swave == 2 ? pg2 : pg3)); \
-    const u32x4 *vp__ = v_lane + (size_t)pv__ * page_stride;                \
-    sv0 = vp__[0];                                                          \
-    sv1 = vp__[16];                                                         \
-    sv2 = vp__[32];                                                         \
-    sv3 = vp__[48];                                                         \
-    v_left = end - (start_) - 4 * krow; /* key 4*krow+i valid iff i < v_left */ \
-    v_tail = end - (start_) < KT;                                           \
-  }
+  const int32_t *bt_row = block_table + (size_t)b * d.max_blocks_per_seq;
 
+  // the next tile has landed as far as this wavefront's loads go
+  constexpr int kKeep = PER * (NS - 2);
+  constexpr int kWaitImm = (kKeep & 15) | ((kKeep >> 4) << 14) | (7 << 4) | (15 << 8);  // vmcnt only
+#define HB_NEXT_LANDED() __builtin_amdgcn_s_waitcnt(kWaitImm)
+
+  TileSrc src;
+  src.k_tree = k_tree; src.v_tree = v_tree; src.k_pool = k_pool; src.v_pool = v_pool;
+  src.bt = bt_row;
+  src.g = g; src.n0 = n0; src.n_nodes = n_nodes; src.hkv = d.num_kv_heads; src.num_blocks = d.num_blocks;
+
+  // prologue: the tree tile (keys = node ids, read straight from k_tree / v_tree, non-finite V
+  // zeroed) goes through registers into stage 0; batches 0 .. NS-2 are issued behind its loads
+  u32x4 tk0, tk1, tk2, tk3, tv0, tv1, tv2, tv3;
   if (tree_chunk) {
-    // the tree tile: keys are node ids, read straight from k_tree / v_tree (once per workgroup)
     if (do_k) {
-      sk0 = load_k_piece(src, true, 0, 0, stid, 0);
-      sk1 = load_k_piece(src, true, 0, 0, stid, 1);
-      sk2 = load_k_piece(src, true, 0, 0, stid, 2);
-      sk3 = load_k_piece(src, true, 0, 0, stid, 3);
+      tk0 = load_k_piece(src, true, 0, 0, stid, 0);
+      tk1 = load_k_piece(src, true, 0, 0, stid, 1);
+      tk2 = load_k_piece(src, true, 0, 0, stid, 2);
+      tk3 = load_k_piece(src, true, 0, 0, stid, 3);
     }
     if (do_v) {
-      sv0 = load_v_piece(src, true, 0, 0, stid, 0);
-      sv1 = load_v_piece(src, true, 0, 0, stid, 1);
-      sv2 = load_v_piece(src, true, 0, 0, stid, 2);
-      sv3 = load_v_piece(src, true, 0, 0, stid, 3);
+      tv0 = load_v_piece(src, true, 0, 0, stid, 0);
+      tv1 = load_v_piece(src, true, 0, 0, stid, 1);
+      tv2 = load_v_piece(src, true, 0, 0, stid, 2);
+      tv3 = load_v_piece(src, true, 0, 0, stid, 3);
     }
-    HB_FETCH_PAGES(begin);  // the next tile is the first prefix tile
-  } else {
-    HB_FETCH_PAGES(begin);
-    if (do_k) HB_LOAD_K(begin);
-    if (do_v) HB_LOAD_V(begin);
-    HB_FETCH_PAGES(begin + KT);
   }
-  // K slots at or past `end` keep whatever the (valid) address held: their scores are replaced
-  // by a select before anything is computed from them.  V slots there must be zeros (0 * V).
-#define HB_STORE_K(dst_) store_k(dst_, stid, sk0, sk1, sk2, sk3)
-#define HB_STORE_V(dst_)                                                                      \
-  {                                                                                           \
-    if (v_tail) { /* only the last tile of a chunk */                                          \
-      const u32x4 z__ = {0u, 0u, 0u, 0u};                                                     \
-      sv0 = v_left > 0 ? sv0 : z__;                                                           \
-      sv1 = v_left > 1 ? sv1 : z__;                                                           \
-      sv2 = v_left > 2 ? sv2 : z__;                                                           \
-      sv3 = v_left > 3 ? sv3 : z__;                                                           \
-    }                                                                                         \
-    store_v(dst_, stid, sv0, sv1, sv2, sv3);                                                  \
+  HB_FETCH_PAGES(0);
+#pragma unroll
+  for (int k = 0; k < NS - 1; ++k) {
+    HB_ISSUE_BATCH(k);
+    HB_FETCH_PAGES(k + 1);
   }
-  if (do_k) HB_STORE_K(lds_k);
-  if (do_v) HB_STORE_V(lds_v);
-  __syncthreads();
+  if (tree_chunk) {
+    if (do_k) store_k((u32x4 *)smem, stid, tk0, tk1, tk2, tk3);
+    if (do_v) store_v((u32x4 *)(smem + K_PIECES * 16), stid, tv0, tv1, tv2, tv3);
+  }
+  // V rows past the end of the tile pipeline step t_ holds, zeroed by the wavefront that loaded
+  // them (uniform condition; only a chunk's last prefix tile can be short)
+#define HB_ZERO_V_TAIL(t_)                                                                     \
+  {                                                                                            \
+    const int pt__ = (t_) - tree_off;                                                          \
+    const int nv__ = end - (begin + pt__ * KT);                                                \
+    if (pt__ >= 0 && pt__ == n_prefix_tiles - 1 && nv__ < KT) {                                \
+      unsigned char *st__ = smem + ((t_) % NS) * kStageBytes;                                  \
+      _Pragma("unroll") for (int i__ = 0; i__ < PER; ++i__) {                                   \
+        const int n__ = wave + NW * i__;                                                       \
+        if (n__ >= 16 && 4 * (n__ - 16) + lrow >= nv__)                                        \
+          *(u32x4 *)(st__ + n__ * 1024 + lane * 16) = (u32x4){0u, 0u, 0u, 0u};                 \
+      }                                                                                        \
+      __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0): the zeros are in LDS */               \
+    }                                                                                          \
+  }
+  // Workgroup barrier without the memory fence of __syncthreads(), which would wait for every
+  // load in flight; LDS reads of the finished tile have all been consumed by MFMAs, and what
+  // must be visible behind the barrier has been waited for explicitly.
+#define HB_BARRIER() asm volatile("s_barrier" ::: "memory")
+  // tile 0 is ready: everything but the newest NS - 2 batches has landed
+  HB_NEXT_LANDED();
+  HB_ZERO_V_TAIL(0);
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the tree tile's LDS writes
+  HB_BARRIER();
 
 #pragma unroll 1  // also keeps the compiler from peeling the tree tile's iteration into a second copy
   for (int i = 0; i < n_tiles; ++i) {
-    const int buf = i & 1;
     const bool is_tree = tree_chunk && i == 0;
-    const int tile_start = begin + (i - (tree_chunk ? 1 : 0)) * KT;  // prefix position of key 0
-    const int next_start = tile_start + KT;                          // the next tile is a prefix tile
-    const bool has_next = i + 1 < n_tiles;
+    const int tile_start = begin + (i - tree_off) * KT;                 // prefix position of key 0
     const int n_valid = is_tree ? n_nodes : min(KT, end - tile_start);  // keys of this tile that exist
-    const u32x4 *lk = lds_k + buf * K_PIECES;
-    const unsigned char *lv = lds_v + buf * V_BYTES;
+    const unsigned char *stage = smem + (i % NS) * kStageBytes;
+    const u32x4 *lk = (const u32x4 *)stage;
+    const unsigned char *lv = stage + K_PIECES * 16;
     const bool partial = is_tree || n_valid < KT;  // uniform
+
+    // the stage of tile i - 1 is free (barrier below): fill it with tile i + NS - 1
+    HB_ISSUE_BATCH(i + NS - 1);
+    HB_FETCH_PAGES(i + NS);  // for the batch of the next iteration
 
 #pragma unroll 1
     for (int blk32 = 0; blk32 < 2; ++blk32) {
-      if (has_next) {
-        if (blk32 == 0) {
-          if (do_k) HB_LOAD_K(next_start);
-          if (NW == 8 && do_v) HB_LOAD_V(next_start);
-        } else {
-          if (do_k) HB_STORE_K(lds_k + (buf ^ 1) * K_PIECES);
-          if (NW == 4) HB_LOAD_V(next_start);
-          HB_FETCH_PAGES(next_start + KT);  // for the tile after the next
-        }
-      }
       if (32 * blk32 < n_valid)
         attend_block<TPW, NW>(partial, lk, lv, blk32, j, kg, qf, o, m_run, l_run, c1, n_valid, is_tree, anc_lds, wtile,
-                          R, G);
+                              R, G);
     }
-    if (has_next && do_v) HB_STORE_V(lds_v + (buf ^ 1) * V_BYTES);
-    __syncthreads();
+    HB_NEXT_LANDED();
+    HB_ZERO_V_TAIL(i + 1);
+    HB_BARRIER();
   }
+  // loads past the end are still in flight: let them land before the workgroup gives up its LDS
+  __builtin_amdgcn_s_waitcnt((0 & 15) | (7 << 4) | (15 << 8));
 #undef HB_PAGE
+#undef HB_TILE_OF
 #undef HB_FETCH_PAGES
-#undef HB_LOAD_K
-#undef HB_LOAD_V
-#undef HB_STORE_K
-#undef HB_STORE_V
+#undef HB_ISSUE_BATCH
+#undef HB_NEXT_LANDED
+#undef HB_ZERO_V_TAIL
+#undef HB_BARRIER
 
   // ---- write out: lane (j, kg) holds O[row j][16*dt + 4*kg + r] ---------------------------
 #pragma unroll
@@ -610,16 +637,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
   }
 }
 
-constexpr size_t kLdsBytes = 2 * K_PIECES * 16 + 2 * V_BYTES + 64 * 8;
 
-template <int TPW, int NW>
+template <int TPW, int NW, int NS>
 hipError_t launch(int row_groups, const hb_attn_desc &d, const AttnPlan &plan, const void *q, const void *k_tree,
                   const void *v_tree, const void *k_pool, const void *v_pool, const int32_t *block_table,
                   const int32_t *prefix_len, const int32_t *node_offset, const int32_t *parent, void *out,
                   float *lse, float *part_o, float *part_ml, hipStream_t s) {
   const int items = d.batch * d.num_kv_heads * plan.splits;
   dim3 grid((unsigned)((items + 7) / 8 * 8 * row_groups));
-  auto kern = attn_mfma_kernel<TPW, NW>;
+  constexpr size_t kLdsBytes = (size_t)NS * (K_PIECES * 16 + V_BYTES) + 64 * 8;
+  auto kern = attn_mfma_kernel<TPW, NW, NS>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
   kern<<<grid, 64 * NW, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, row_groups, (const u32x4 *)q, (const u32x4 *)k_tree,
@@ -666,7 +693,7 @@ hipError_t launch_attn_mfma(const hb_attn_desc &d, const AttnPlan &plan, const v
   const int tiles = tiles_of(d);
   const int row_groups = plan.row_groups;
 #define HB_GO(N, W) \
-  return launch<N, W>(row_groups, d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
+  return launch<N, W, (W == 8 ? 4 : 2)>(row_groups, d, plan, q, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, parent, out, lse, part_o, part_ml, s)
   if (tiles <= 4) HB_GO(1, 4);
   if (tiles <= 8) HB_GO(2, 4);
   HB_GO(2, 8);  // attn_mfma_row_groups keeps a workgroup at sixteen tiles or fewer

@@ -64,11 +64,15 @@ int32_t make_attn_plan(const hb_attn_desc *d, AttnPlan *plan) {
   if (splits == 0) {
     if (plan->mfma) {
       // Parallelism comes first from row groups (they cost no partials), then from KV chunks:
-      // aim at eight wavefronts on each of the 256 CUs, keep a chunk at 1024 tokens or more
+      // aim at eight wavefronts on each of the 256 CUs.  A chunk stays at 1024 tokens or more
+      // when many rows share it; with few rows (four-wavefront workgroups) the kernel is bound by
+      // the KV stream, partials are small, and chunks go down to 512 tokens.
       int64_t items = (int64_t)d->batch * d->num_kv_heads * plan->row_groups;
-      int64_t want = 256 * 8 / attn_mfma_waves(*d);
+      const int waves = attn_mfma_waves(*d);
+      int64_t want = 256 * 8 / waves;
       splits = items > 0 ? (want + items - 1) / items : 1;
-      int64_t cap = (span + 1023) / 1024;
+      const int64_t min_chunk = waves == 8 ? 1024 : 512;
+      int64_t cap = (span + min_chunk - 1) / min_chunk;
       if (splits > cap) splits = cap;
     } else {
       int64_t rows = (int64_t)d->total_nodes * d->num_q_heads;
