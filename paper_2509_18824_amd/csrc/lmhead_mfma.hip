@@ -49,7 +49,10 @@ __device__ inline int swz(int r, int c) { return r * CH + (c ^ ((r & 7) ^ ((r >>
 // with VT = 8 / WV vocabulary tiles of 32 rows.  WV = 4 (eight wavefronts, two per SIMD, at most
 // 256 registers each) lets one wavefront's matrix work cover the other's LDS, barrier and
 // memory waits.
-template <int MT, int WV>
+// WNT: weight loads carry the non-temporal hint.  With one hidden tile nobody shares a weight
+// tile, and streaming it through L2 without displacing the hidden rows is worth 5 %; with several
+// hidden tiles the hint evicts weight lines before all sharers have read them.
+template <int MT, int WV, bool WNT>
 __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles, int groups,
                                                           const u32x4 *__restrict__ hidden,
                                                           const u32x4 *__restrict__ weight,
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   {                                                                                              \
     _Pragma("unroll") for (int i = 0; i < W_GROUPS; ++i)                                          \
         __builtin_amdgcn_global_load_lds((gptr_t)(w_src[i] + (kt_) * CH),                        \
-                                         (lptr_t)(lw + (slot_) * TV * CH + (uwave + NW * i) * 64), 16, 0, 0); \
+                                         (lptr_t)(lw + (slot_) * TV * CH + (uwave + NW * i) * 64), 16, 0, WNT ? 2 : 0); \
   }
 #define HB_ISSUE_H(kt_, slot_)                                                                   \
   {                                                                                              \
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   }  // vocabulary tiles of this workgroup
 }
 
-template <int MT, int WV>
+template <int MT, int WV, bool WNT>
 hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, unsigned long long *keys,
                   hipStream_t s) {
   constexpr int TM = 64 * MT;
@@ -276,7 +279,7 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, u
   int need = (v_tiles + kXcds - 1) / kXcds;
   if (groups > need) groups = need;
   size_t lds_bytes = (size_t)(3 * TV + 2 * TM) * CH * sizeof(u32x4);
-  auto kern = lmhead_mfma_kernel<MT, WV>;
+  auto kern = lmhead_mfma_kernel<MT, WV, WNT>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)(groups * m_tiles * kXcds));
@@ -302,10 +305,14 @@ hipError_t launch_lmhead_mfma(int32_t M, int32_t K, int32_t V, const void *hidde
     if (best_rows < 0 || rows < best_rows) { best_rows = rows; best_mt = mt; }
   }
   switch (best_mt) {
-    case 1: return launch<1, 4>(M, K, V, hidden, weight, keys, s);
-    case 2: return launch<2, 4>(M, K, V, hidden, weight, keys, s);
-    case 3: return launch<3, 4>(M, K, V, hidden, weight, keys, s);
-    default: return launch<4, 4>(M, K, V, hidden, weight, keys, s);
+    case 1: return M <= 64 * 1 ? launch<1, 4, true>(M, K, V, hidden, weight, keys, s)
+                            : launch<1, 4, false>(M, K, V, hidden, weight, keys, s);
+    case 2: return M <= 64 * 2 ? launch<2, 4, true>(M, K, V, hidden, weight, keys, s)
+                            : launch<2, 4, false>(M, K, V, hidden, weight, keys, s);
+    case 3: return M <= 64 * 3 ? launch<3, 4, true>(M, K, V, hidden, weight, keys, s)
+                            : launch<3, 4, false>(M, K, V, hidden, weight, keys, s);
+    default: return M <= 64 * 4 ? launch<4, 4, true>(M, K, V, hidden, weight, keys, s)
+                            : launch<4, 4, false>(M, K, V, hidden, weight, keys, s);
   }
 }
 
