@@ -390,16 +390,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
   }
 
   if (tree_chunk && tid < 64) {
-    unsigned long long anc = 0ull;
-    if (tid < n_nodes) {
-      anc = 1ull << tid;
-      int x = tid;
-      for (int guard = 0; guard < 64; ++guard) {
-        int px = parent[n0 + x];
-        if (px < 0 || px >= x) break;  // root reached (or malformed parent: stop)
-        anc |= 1ull << px;
-        x = px;
-      }
+    // Ancestor masks: lane i walks from node i to the root.  The parent array is read once (one
+    // value per lane) and the walk fetches parents from the other lanes' registers, so its length
+    // costs register exchanges, not a chain of dependent memory loads.
+    const int par = tid < n_nodes ? parent[n0 + tid] : -1;
+    unsigned long long anc = tid < n_nodes ? 1ull << tid : 0ull;
+    int x = tid < n_nodes ? tid : -1;
+    for (int guard = 0; guard < 64; ++guard) {
+      const int px = __shfl(par, x < 0 ? 0 : x, 64);
+      const bool up = x >= 0 && px >= 0 && px < x;  // else: root reached (or malformed parent: stop)
+      if (!__any(up)) break;
+      if (up) anc |= 1ull << px;
+      x = up ? px : -1;
     }
     anc_lds[tid] = anc;
   }
