@@ -21,13 +21,22 @@ FLAGS = [
 ]
 
 
+# Per-file code generation options.  The attention kernel reads every MFMA result (the scores)
+# with vector instructions and keeps its accumulators in place anyway: with the matrix
+# instructions selected in their vector-register form there are no accumulation registers and
+# no copies between the two register files.
+FILE_FLAGS = {
+    "attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+}
+
+
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
 def _compile(src: str, verbose: bool) -> str:
     obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)

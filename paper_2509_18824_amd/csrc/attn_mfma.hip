@@ -25,7 +25,7 @@
 //
 // Rows: row r = node * G + head_in_group, tiles of 16 rows dealt round-robin to the
 // wavefronts; Q fragments and the fp32 O^T accumulators of a wavefront's (at most TPW = 2) tiles
-// live in registers for the whole kernel, within 256 registers so that a CU holds eight
+// live in vector registers for the whole kernel, within 256 registers so that a CU holds eight
 // wavefronts and one's matrix work overlaps another's vector work and waits.
 //
 // Keys: chunk 0 starts with one 64-key tile holding the tree nodes (masked per row by the
@@ -176,10 +176,11 @@ __device__ __forceinline__ float group_sum(float x) {
 // One 32-key block of the current tile against all row tiles of the wavefront.
 //   partial (uniform): some keys of the block do not exist or are masked (chunk tail, tree tile).
 // Row tiles are taken in groups of at most four: scores and softmax for the group (VALU work,
-// QK^T on the matrix cores), then the group's O^T += V^T P^T.  After every instruction that
-// defines an O^T accumulator an empty asm statement with an "a" constraint pins the value to the
-// accumulation registers; with that the fp32 O^T of all tiles (224 registers for 7 tiles) stays
-// in place there instead of being shuffled through the vector registers every iteration.
+// QK^T on the matrix cores), then the group's O^T += V^T P^T.  This file is compiled with the
+// matrix instructions in their vector-register form (scores are read by vector instructions
+// right away, so accumulation registers would only add copies); after every instruction that
+// defines an O^T accumulator an empty asm statement with a "v" constraint keeps the value where
+// it is instead of letting it be shuffled around every iteration.
 template <int TPW, int NW>
 __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restrict__ lk, const unsigned char *__restrict__ lv,
                                              int blk32, int j, int kg, const bf16x8 (&qf)[TPW][4],
@@ -283,9 +284,9 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
         l_run[t] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-          asm volatile("" : "+a"(o[t][dt]));
+          asm volatile("" : "+v"(o[t][dt]));
           o[t][dt] *= alpha;
-          asm volatile("" : "+a"(o[t][dt]));
+          asm volatile("" : "+v"(o[t][dt]));
         }
         m_run[t] = m_new[u];
       }
@@ -315,7 +316,7 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
         const int t = t0 + u;
         if (t >= TPW) break;
         o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dt], pb[u], o[t][dt], 0, 0, 0);
-        asm volatile("" : "+a"(o[t][dt]));
+        asm volatile("" : "+v"(o[t][dt]));
       }
     }
   }
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     }
   }
 
-  // fp32 O^T accumulators, pinned to the accumulation registers
+  // fp32 O^T accumulators, kept in place in vector registers
   f32x4 o[TPW][8];
   float m_run[TPW], l_run[TPW];
 #pragma unroll
@@ -433,7 +434,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
       o[t][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      asm volatile("" : "+a"(o[t][dt]));
+      asm volatile("" : "+v"(o[t][dt]));
     }
   }
   const float c1 = d.softmax_scale * kLog2e;
