@@ -20,8 +20,8 @@
 // exchanges per 32 keys).  The reference is the first block maximum the row sees and moves
 // only when a later maximum exceeds it by more than 8 (a factor 256): row maxima of real score
 // distributions creep up by small steps all the time, and rescaling the whole accumulator at
-// every step would cost more vector work than the attention itself.  Row sums stay per lane
-// until the end.
+// every step would cost more vector work than the attention itself.  Row sums are taken on the
+// matrix cores (an all-ones operand against the probabilities).
 //
 // Rows: row r = node * G + head_in_group, tiles of 16 rows dealt round-robin to the
 // wavefronts; Q fragments and the fp32 O^T accumulators of a wavefront's (at most TPW = 2) tiles
@@ -154,7 +154,7 @@ __device__ __forceinline__ void store_v(u32x4 *__restrict__ lv, int tid, u32x4 v
 // may flush to zero, which is what a vanishing softmax weight should do.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Reductions over the four lanes l, l^16, l^32, l^48 that hold the four key groups of one query
+// Maximum over the four lanes l, l^16, l^32, l^48 that hold the four key groups of one query
 // row.  v_permlane16_swap exchanges rows 1<->0 and 3<->2 (rows of 16 lanes) between its two
 // operands, v_permlane32_swap the upper half of one with the lower half of the other: fed the
 // same value twice they hand every lane its partner's value next to its own, without the LDS
@@ -165,12 +165,6 @@ __device__ __forceinline__ float group_max(float x) {
   x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
   r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float group_sum(float x) {
-  swap2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 // One 32-key block of the current tile against all row tiles of the wavefront.
@@ -184,7 +178,7 @@ __device__ __forceinline__ float group_sum(float x) {
 template <int TPW, int NW>
 __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restrict__ lk, const unsigned char *__restrict__ lv,
                                              int blk32, int j, int kg, const bf16x8 (&qf)[TPW][4],
-                                             f32x4 (&o)[TPW][8], float (&m_run)[TPW], float (&l_run)[TPW],
+                                             f32x4 (&o)[TPW][8], float (&m_run)[TPW], f32x4 (&l_run)[TPW],
                                              float c1, int n_valid, bool is_tree, const unsigned long long *anc_lds,
                                              int wave, int R, int G) {
   // K fragments of the block's two 16-key halves, shared by all row tiles of the wavefront
@@ -299,14 +293,22 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       const int t = t0 + u;
       if (t >= TPW) break;
       f32x8 p;
-      float psum = 0.f;
 #pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        p[r] = fast_exp2(fmaf(sc[u][r], c1, -m_new[u]));
-        psum += p[r];
-      }
-      l_run[t] += psum;
+      for (int r = 0; r < 8; ++r) p[r] = fast_exp2(fmaf(sc[u][r], c1, -m_new[u]));
       pb[u] = __builtin_convertvector(p, bf16x8);
+    }
+    // -- row sums on the matrix cores: an all-ones A operand makes every row of the product the
+    //    sum over the block's 32 keys of the (bf16) probabilities, summed across the lane groups
+    //    too; eight vector additions per tile and the final cross-lane sum are saved
+    {
+      const bf16x8 ones = {(__bf16)1.f, (__bf16)1.f, (__bf16)1.f, (__bf16)1.f, (__bf16)1.f, (__bf16)1.f, (__bf16)1.f, (__bf16)1.f};
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const int t = t0 + u;
+        if (t >= TPW) break;
+        l_run[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[u], l_run[t], 0, 0, 0);
+        asm volatile("" : "+v"(l_run[t]));
+      }
     }
     // -- O^T += V^T P^T for the group, one 16-d slab of V^T at a time
 #pragma unroll
@@ -426,11 +428,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
 
   // fp32 O^T accumulators, kept in place in vector registers
   f32x4 o[TPW][8];
-  float m_run[TPW], l_run[TPW];
+  float m_run[TPW];
+  f32x4 l_run[TPW];  // row sums of the probabilities (every element holds the row's sum)
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
     m_run[t] = HB_NEG_INF;
-    l_run[t] = 0.f;
+    l_run[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
       o[t][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -613,7 +616,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
   for (int t = 0; t < TPW; ++t) {
     int row = (wtile + NW * t) * 16 + j;
     if ((wtile + NW * t) >= tile_hi) continue;
-    float l_tot = group_sum(l_run[t]);
+    float l_tot = l_run[t][0];
     if (row >= R) continue;
     int node = row / G, hg = row - node * G;
     size_t rg = row_base + (size_t)node * d.num_q_heads + hg;
