@@ -266,7 +266,8 @@ def main():
             "unit": "TFLOP/s" if M >= 512 else "GB/s",
             "frac": (lm_tflops / PEAK_BF16_TFLOPS) if M >= 512
             else (V * K * 2 + M * K * 2) / (ms_lm * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "traffic": _lmhead_traffic() if args.tree == "tree" else None,
+            "traffic": (_lmhead_traffic() or {}).get("bytes") if args.tree == "tree" else None,
+            "traffic_detail": _lmhead_traffic() if args.tree == "tree" else None,
             "ms": ms_lm,
         },
         "kernels_ms": {"tree_verify_attn": ms_attn, "lmhead_argmax": ms_lm, "tree_accept": ms_acc,
