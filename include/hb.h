@@ -69,7 +69,8 @@ typedef struct hb_attn_desc {
   int32_t max_nodes_per_tree;  /* upper bound on nodes per sequence, at most 64             */
   int32_t num_splits;          /* KV partitions per sequence; 0 = let the library choose    */
   int32_t max_prefix_len_hint; /* upper bound on prefix_len known to the host, 0 = unknown  */
-                               /* (then max_blocks_per_seq * page_size is assumed)          */
+                               /* (then max_blocks_per_seq * page_size is assumed); with a  */
+                               /* prefix longer than a given bound the result is unspecified */
   int32_t algo;                /* hb_attn_algo                                              */
   float softmax_scale;         /* scores are softmax_scale * <q, k>                         */
 } hb_attn_desc;

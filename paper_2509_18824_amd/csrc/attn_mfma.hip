@@ -329,7 +329,7 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
 // per CU with twice the rows sharing each staged tile.
 template <int TPW, int NW, int NS>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
-    hb_attn_desc d, int splits, int chunk_tokens, int row_groups, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
+    hb_attn_desc d, int splits, int chunk_tokens, int workers, int row_groups, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
     const u32x4 *__restrict__ v_tree, const u32x4 *__restrict__ k_pool, const u32x4 *__restrict__ v_pool,
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ prefix_len,
     const int32_t *__restrict__ node_offset, const int32_t *__restrict__ parent, bf16_t *__restrict__ out,
@@ -342,18 +342,146 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // Work item = (sequence b, kv head g, chunk c, row group).  Consecutive workgroup ids land on
-  // different XCDs (id % 8); the row groups of one (b, g, c) get ids 8 apart, i.e. neighbouring
-  // slots of the same XCD, so the KV tiles they both read are shared in that XCD's L2.
+  // Consecutive workgroup ids land on different XCDs (id % 8); the row groups of one unit of work
+  // get ids 8 apart, i.e. neighbouring slots of the same XCD, so the KV tiles they both read are
+  // shared in that XCD's L2.
   const int id = blockIdx.x;
   const int xcd = id & 7, slot = id >> 3;
   const int rgi = slot % row_groups;
-  const int item = (slot / row_groups) * 8 + xcd;
-  if (item >= d.batch * d.num_kv_heads * splits) return;
-  const int c = item % splits;
-  const int g = (item / splits) % d.num_kv_heads;
-  const int b = item / (splits * d.num_kv_heads);
+  const int unit = (slot / row_groups) * 8 + xcd;
   const int G = d.num_q_heads / d.num_kv_heads;
+  const int cap = d.max_blocks_per_seq * PAGE;
+  const int j = lane & 15;    // query row within a tile
+  const int kg = lane >> 4;   // key group / k-slot group of this lane
+
+  // What this workgroup does is a list of segments (sequence b, prefix tokens [begin, end), with
+  // or without the tree tile, partial slot c).
+  //  * workers == 0: one segment, chunk c of sequence b, chunks of equal length within a
+  //    sequence (unit = (b, g, c)).
+  //  * workers > 0 (batch <= 64): work-proportional.  The 64-key tiles of all sequences (tree
+  //    tile first, then the prefix tiles) form one line; worker w of kv head g (unit = (w, g))
+  //    takes tiles [w * per, (w + 1) * per) of it, per = max(kMinPer, ceil(total / workers)),
+  //    whatever sequences they belong to.  Every workgroup finds the line by itself: lane b reads
+  //    prefix_len[b], a prefix sum over the lanes gives each sequence's place.  A sequence cut
+  //    by worker boundaries gets one partial slot per piece (consecutive workers, consecutive
+  //    slots); the piece that ends it announces the unused slots as empty; a sequence that lies
+  //    inside one worker's range is written out directly and slot 0 tells the merge so.
+  constexpr int kMinPer = NW == 8 ? 16 : 8;
+  constexpr int kRestart = 4;
+  int g, seg_b = 0, lo = 0, hi = 0, per = 1, w_id = 0, al_k = 0, al_n = 0;
+  bool aligned = false;
+  int Lb = 0, tb = 0, cum = 0;  // lane b: prefix length, tiles and end of sequence b on the line
+  if (workers == 0) {
+    if (unit >= d.batch * d.num_kv_heads * splits) return;
+    g = (unit / splits) % d.num_kv_heads;
+  } else {
+    if (unit >= d.num_kv_heads * workers) return;
+    g = unit % d.num_kv_heads;
+    w_id = unit / d.num_kv_heads;
+    if (lane < d.batch) {
+      Lb = prefix_len[lane];
+      Lb = Lb < 0 ? 0 : (Lb > cap ? cap : Lb);
+      tb = (Lb + KT - 1) / KT + 1;
+    }
+    cum = tb;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int y = __shfl_up(cum, off, 64);
+      if (lane >= off) cum += y;
+    }
+    const int total = __builtin_amdgcn_readfirstlane(__shfl(cum, 63, 64));
+    per = (total + workers - 1) / workers;
+    per = per < kMinPer ? kMinPer : per;
+    // The alternative: the same number of workers for every sequence, each sequence cut into
+    // pieces of equal length.  No worker then has to start over on a second sequence (which
+    // costs about kRestart tiles' time), but the longest sequence sets the pace.  Both plans
+    // are known here; take the one that finishes first.
+    al_k = workers / d.batch;
+    if (al_k >= 1) {
+      int nb = (tb + kMinPer - 1) / kMinPer;
+      nb = nb < 1 ? 1 : (nb > al_k ? al_k : nb);
+      nb = nb > splits ? splits : nb;
+      al_n = nb;                                   // pieces of sequence `lane`
+      int len = lane < d.batch ? (tb + nb - 1) / nb : 0;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) len = max(len, __shfl_xor(len, off, 64));
+      aligned = __builtin_amdgcn_readfirstlane(len) <= per + kRestart;
+    }
+    if (aligned) {
+      seg_b = w_id / al_k;
+      if (seg_b >= d.batch) return;
+    } else {
+      lo = w_id * per;
+      hi = lo + per < total ? lo + per : total;
+      if (lo >= total) return;
+      const unsigned long long after = __ballot(cum > lo);  // sequences that end behind lo
+      seg_b = after ? __builtin_ctzll(after) : d.batch;
+    }
+  }
+
+#pragma unroll 1
+  for (int seg = 0;; ++seg) {
+  int b, c, L, begin, end;
+  bool tree_chunk, direct_out, ends_seq;
+  if (workers == 0) {
+    if (seg > 0) break;
+    c = unit % splits;
+    b = unit / (splits * d.num_kv_heads);
+    L = prefix_len[b];
+    L = L < 0 ? 0 : (L > cap ? cap : L);
+    // chunks of this sequence: as many as the plan allows, but never shorter than needed
+    int n_chunks = (L + chunk_tokens - 1) / chunk_tokens;
+    n_chunks = n_chunks < 1 ? 1 : (n_chunks > splits ? splits : n_chunks);
+    int chunk = ((L + n_chunks - 1) / n_chunks + KT - 1) / KT * KT;
+    chunk = chunk < KT ? KT : chunk;
+    begin = c * chunk;
+    end = min(L, begin + chunk);
+    tree_chunk = (c == 0);
+    direct_out = splits == 1;
+    ends_seq = false;  // here every chunk, also an empty one, has a workgroup that announces it
+  } else if (aligned) {
+    if (seg > 0) break;
+    b = seg_b;
+    const int piece = w_id - b * al_k;
+    const int t_b = __builtin_amdgcn_readfirstlane(__shfl(tb, b, 64));
+    const int n_b = __builtin_amdgcn_readfirstlane(__shfl(al_n, b, 64));
+    L = __builtin_amdgcn_readfirstlane(__shfl(Lb, b, 64));
+    if (piece >= n_b) break;
+    const int len = (t_b + n_b - 1) / n_b;
+    const int rel_lo = piece * len;
+    const int rel_hi = min(t_b, rel_lo + len);
+    if (rel_lo >= rel_hi && piece > 0) {
+      // pieces of equal length can leave the last ones without tiles: announce them as empty
+      c = piece;
+      begin = end = L;
+      tree_chunk = false;
+      direct_out = false;
+      ends_seq = piece == n_b - 1;
+    } else {
+      tree_chunk = rel_lo == 0;
+      begin = ((rel_lo > 1 ? rel_lo : 1) - 1) * KT;
+      end = min(L, (rel_hi - 1) * KT);
+      c = piece;
+      ends_seq = piece == n_b - 1;
+      direct_out = n_b == 1 || splits == 1;
+    }
+  } else {
+    if (seg_b >= d.batch) break;
+    b = seg_b++;
+    const int t_b = __builtin_amdgcn_readfirstlane(__shfl(tb, b, 64));
+    const int e_b = __builtin_amdgcn_readfirstlane(__shfl(cum, b, 64));
+    L = __builtin_amdgcn_readfirstlane(__shfl(Lb, b, 64));
+    const int s_b = e_b - t_b;                 // the sequence's tiles are [s_b, e_b) of the line
+    if (s_b >= hi) break;
+    const int rel_lo = (lo > s_b ? lo : s_b) - s_b;
+    const int rel_hi = (hi < e_b ? hi : e_b) - s_b;
+    tree_chunk = rel_lo == 0;                  // tile 0 of a sequence is its tree tile
+    begin = ((rel_lo > 1 ? rel_lo : 1) - 1) * KT;
+    end = min(L, (rel_hi - 1) * KT);
+    c = w_id - s_b / per;
+    ends_seq = e_b <= hi;
+    direct_out = (tree_chunk && ends_seq) || splits == 1;
+  }
   const int n0 = node_offset[b];
   int n_nodes = node_offset[b + 1] - n0;
   n_nodes = n_nodes < 0 ? 0 : (n_nodes > d.max_nodes_per_tree ? d.max_nodes_per_tree : n_nodes);
@@ -364,32 +492,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
   const int tile_lo = rgi * tiles_per_group;                     // this workgroup's tiles
   const int tile_hi = min(NT, tile_lo + tiles_per_group);
   const int wtile = tile_lo + wave;    // the wavefront's tiles: wtile + NW*t < tile_hi
-  int L = prefix_len[b];
-  const int cap = d.max_blocks_per_seq * PAGE;
-  L = L < 0 ? 0 : (L > cap ? cap : L);
+  if (tile_lo >= tile_hi) continue;
+  if (c >= splits) continue;           // cannot happen with the planned slot count; never write past it
 
-  // chunks of this sequence: as many as the plan allows, but never shorter than needed
-  int n_chunks = (L + chunk_tokens - 1) / chunk_tokens;
-  n_chunks = n_chunks < 1 ? 1 : (n_chunks > splits ? splits : n_chunks);
-  int chunk = ((L + n_chunks - 1) / n_chunks + KT - 1) / KT * KT;
-  chunk = chunk < KT ? KT : chunk;
-  const int begin = c * chunk;
-  const int end = min(L, begin + chunk);
-  const bool tree_chunk = (c == 0);
-  if (tile_lo >= tile_hi) return;
-
-  const int j = lane & 15;    // query row within a tile
-  const int kg = lane >> 4;   // key group / k-slot group of this lane
   const size_t row_base = (size_t)n0 * d.num_q_heads + (size_t)g * G;  // + node*Hq + head_in_group
 
   if (!tree_chunk && begin >= L) {
-    // an empty chunk only announces itself to the merge
+    // an empty chunk only announces itself to the merge (which stops at the first empty slot)
     for (int r = tile_lo * 16 + tid; r < min(R, tile_hi * 16); r += 64 * NW) {
       size_t rg = row_base + (size_t)(r / G) * d.num_q_heads + (r % G);
       part_ml[(rg * splits + c) * 2 + 0] = HB_NEG_INF;
       part_ml[(rg * splits + c) * 2 + 1] = 0.f;
     }
-    return;
+    continue;
   }
 
   if (tree_chunk && tid < 64) {
@@ -620,7 +735,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     if (row >= R) continue;
     int node = row / G, hg = row - node * G;
     size_t rg = row_base + (size_t)node * d.num_q_heads + hg;
-    if (splits == 1) {
+    if (direct_out) {
       float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) {
@@ -631,6 +746,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
         *(u32x2 *)(out + rg * D + 16 * dt + 4 * kg) = w;
       }
       if (lse && kg == 0) lse[rg] = (m_run[t] + log2f(l_tot)) * kLn2;
+      if (splits > 1 && kg == 0) {  // tell the merge that this row is final
+        part_ml[(rg * splits) * 2 + 0] = 0.f;
+        part_ml[(rg * splits) * 2 + 1] = -1.f;
+      }
     } else {
       float *po = part_o + (rg * splits + c) * D;
 #pragma unroll
@@ -638,9 +757,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
       if (kg == 0) {
         part_ml[(rg * splits + c) * 2 + 0] = m_run[t] * kLn2;  // natural-log units for the merge
         part_ml[(rg * splits + c) * 2 + 1] = l_tot;
+        if (ends_seq && c + 1 < splits) {  // the first empty slot ends the list for the merge
+          part_ml[(rg * splits + c + 1) * 2 + 0] = HB_NEG_INF;
+          part_ml[(rg * splits + c + 1) * 2 + 1] = 0.f;
+        }
       }
     }
   }
+  // the next segment reuses the LDS stages and the ancestor masks
+  asm volatile("s_barrier" ::: "memory");
+  }  // segments
 }
 
 
@@ -649,13 +775,13 @@ hipError_t launch(int row_groups, const hb_attn_desc &d, const AttnPlan &plan, c
                   const void *v_tree, const void *k_pool, const void *v_pool, const int32_t *block_table,
                   const int32_t *prefix_len, const int32_t *node_offset, const int32_t *parent, void *out,
                   float *lse, float *part_o, float *part_ml, hipStream_t s) {
-  const int items = d.batch * d.num_kv_heads * plan.splits;
+  const int items = plan.workers > 0 ? d.num_kv_heads * plan.workers : d.batch * d.num_kv_heads * plan.splits;
   dim3 grid((unsigned)((items + 7) / 8 * 8 * row_groups));
   constexpr size_t kLdsBytes = (size_t)NS * (K_PIECES * 16 + V_BYTES) + 64 * 8;
   auto kern = attn_mfma_kernel<TPW, NW, NS>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
-  kern<<<grid, 64 * NW, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, row_groups, (const u32x4 *)q, (const u32x4 *)k_tree,
+  kern<<<grid, 64 * NW, kLdsBytes, s>>>(d, plan.splits, plan.chunk_tokens, plan.workers, row_groups, (const u32x4 *)q, (const u32x4 *)k_tree,
                                     (const u32x4 *)v_tree, (const u32x4 *)k_pool, (const u32x4 *)v_pool,
                                     block_table, prefix_len, node_offset, parent, (bf16_t *)out, lse, part_o,
                                     part_ml);

@@ -162,27 +162,33 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(int rows, int D, int sp
   const int piece = (int)(gid - (long)row * tpr);
   if (row >= rows) return;
   const merge_f32x2 *ml = reinterpret_cast<const merge_f32x2 *>(part_ml) + (size_t)row * splits;
+  if (ml[0].y < 0.f) return;  // the attention kernel wrote this row out itself (row sums are never negative)
+  // Chunks are filled from slot 0 on and empty ones only follow non-empty ones (a chunk that
+  // holds any key has l > 0), so the first empty slot ends the list; producers need to mark
+  // only that one.
   float m = -__builtin_huge_valf();
-  for (int c = 0; c < splits; ++c) {
-    merge_f32x2 x = ml[c];
-    if (x.y > 0.f) m = fmaxf(m, x.x);
+  int live = 0;
+  for (; live < splits; ++live) {
+    merge_f32x2 x = ml[live];
+    if (!(x.y > 0.f)) break;
+    m = fmaxf(m, x.x);
   }
   const merge_f32x4 *po = reinterpret_cast<const merge_f32x4 *>(part_o) + (size_t)row * splits * tpr + piece;
   float l = 0.f;
   merge_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int c0 = 0; c0 < splits; c0 += kMergeBatch) {
+  for (int c0 = 0; c0 < live; c0 += kMergeBatch) {
     float w[kMergeBatch];
     merge_f32x4 o[kMergeBatch];
 #pragma unroll
     for (int i = 0; i < kMergeBatch; ++i) {
       const int c = c0 + i;
       merge_f32x2 x = {0.f, 0.f};
-      if (c < splits) x = ml[c];
-      const bool live = x.y > 0.f;
-      w[i] = live ? expf(x.x - m) : 0.f;
-      l += live ? x.y * w[i] : 0.f;
+      if (c < live) x = ml[c];
+      const bool ok = c < live;
+      w[i] = ok ? expf(x.x - m) : 0.f;
+      l += ok ? x.y * w[i] : 0.f;
       merge_f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (live) v = po[(size_t)c * tpr];  // an empty chunk's slot is never read
+      if (ok) v = po[(size_t)c * tpr];  // an empty chunk's slot is never read
       o[i] = v;
     }
 #pragma unroll

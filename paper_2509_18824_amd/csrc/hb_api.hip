@@ -61,15 +61,42 @@ int32_t make_attn_plan(const hb_attn_desc *d, AttnPlan *plan) {
   if (span < 1) span = 1;
   int32_t gran = d->page_size * (64 / gcd32(d->page_size, 64));  // multiple of the page and of 64
   int64_t splits = d->num_splits;
+  plan->workers = 0;
   if (splits == 0) {
     if (plan->mfma) {
-      // Parallelism comes first from row groups (they cost no partials), then from KV chunks:
-      // aim at eight wavefronts on each of the 256 CUs.  A chunk stays at 1024 tokens or more
-      // when many rows share it; with few rows (four-wavefront workgroups) the kernel is bound by
-      // the KV stream, partials are small, and chunks go down to 512 tokens.
-      int64_t items = (int64_t)d->batch * d->num_kv_heads * plan->row_groups;
+      // Parallelism comes first from row groups (they cost no partials), then from cutting the
+      // KV: aim at eight wavefronts on each of the 256 CUs.
       const int waves = attn_mfma_waves(*d);
-      int64_t want = 256 * 8 / waves;
+      const int64_t want = 256 * 8 / waves;
+      if (d->batch <= 64) {
+        // Work-proportional schedule, resolved on the device from prefix_len (see the kernel): a
+        // fixed number of workers per kv head share the tiles of all sequences evenly.  What the
+        // host fixes is the number of partial slots per row: a sequence of t tiles is cut into at
+        // most ceil((t - 1) / per) + 1 pieces, per >= kMinPer tiles, and never more than there
+        // are workers.
+        int64_t workers = want / ((int64_t)d->num_kv_heads * plan->row_groups);
+        if (workers < 1) workers = 1;
+        if (workers > 4096) workers = 4096;
+        const int64_t min_per = waves == 8 ? 16 : 8;  // kMinPer of the kernel
+        const int64_t prefix_tiles = (span + 63) / 64;
+        int64_t slots = (prefix_tiles + min_per - 1) / min_per + 1;
+        if (slots > workers) slots = workers;
+        plan->workers = (int32_t)workers;
+        plan->splits = (int32_t)slots;
+        plan->chunk_tokens = 64;  // unused by this schedule
+        size_t rows = (size_t)d->total_nodes * d->num_q_heads;
+        if (slots > 1) {
+          plan->ml_offset = align_up(rows * slots * d->head_dim * sizeof(float), 256);
+          plan->bytes = plan->ml_offset + align_up(rows * slots * 2 * sizeof(float), 256);
+        } else {
+          plan->ml_offset = 0;
+          plan->bytes = 0;
+        }
+        return HB_OK;
+      }
+      // more sequences than one wavefront can schedule: chunks of equal length per sequence; a
+      // chunk stays at 1024 tokens or more when many rows share it, 512 with few rows
+      int64_t items = (int64_t)d->batch * d->num_kv_heads * plan->row_groups;
       splits = items > 0 ? (want + items - 1) / items : 1;
       const int64_t min_chunk = waves == 8 ? 1024 : 512;
       int64_t cap = (span + min_chunk - 1) / min_chunk;

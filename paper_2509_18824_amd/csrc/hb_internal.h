@@ -52,6 +52,7 @@ struct AttnPlan {
   int32_t splits;
   int32_t chunk_tokens;
   int32_t row_groups;  // MFMA kernel: workgroups that split the query rows of one (sequence, kv head, chunk)
+  int32_t workers;     // MFMA kernel: > 0 = work-proportional schedule with this many workers per kv head
   bool mfma;
   size_t ml_offset;  // byte offset of part_ml in the workspace
   size_t bytes;      // workspace size (0 when splits == 1)

@@ -93,9 +93,30 @@ def test_ragged_edges_and_odd_shapes(hb, step):
         inp = W.make_verify_inputs(77, dtype, Hq, Hkv, D, lens, trees, kv_std=1.0, q_std=1.0)
         ref = oracle_attn(inp)
         for algo in _algos(hb, inp):
-            for splits in (1, 4):
+            for splits in (1, 4, 0):
                 out, lse, _ = _run(step, inp, num_splits=splits, algo=algo)
                 check_attn(inp, out, lse, ref=ref, label=f"edges {dtype} Hq={Hq} Hkv={Hkv} D={D} algo={algo} s={splits}")
+
+
+def test_schedules_of_the_matrix_core_kernel(hb, step):
+    """With num_splits = 0 the kernel cuts the KV itself, on the device, from the prefix lengths:
+    work-proportionally when that finishes first (one long sequence among short ones: pieces of
+    several sequences per workgroup, rows written directly next to rows that go through the
+    merge), with equal pieces per sequence otherwise (equal lengths), and with host-planned
+    chunks for more than 64 sequences."""
+    cases = {
+        "one long, many short": ([3000, 0, 70, 1, 130, 64, 17, 300], 8),
+        "equal lengths": ([1536] * 4, 4),
+        "more than 64 sequences": ([33 + 7 * i for i in range(66)], 66),
+    }
+    for name, (lens, B) in cases.items():
+        trees = [W.seeded_tree(10 + i, n_nodes=15 + (i * 11) % 46) for i in range(B)]
+        inp = W.make_verify_inputs(91, "bf16", 28, 4, 128, lens, trees, kv_std=1.0, q_std=1.0)
+        ref = oracle_attn(inp)
+        out, lse, desc = _run(step, inp, num_splits=0, algo=hb.HB_ATTN_MFMA, hint=max(lens))
+        check_attn(inp, out, lse, ref=ref, label=f"schedule: {name}")
+        out2, lse2, _ = _run(step, inp, num_splits=0, algo=hb.HB_ATTN_MFMA)  # no length hint
+        check_attn(inp, out2, lse2, ref=ref, label=f"schedule, no hint: {name}")
 
 
 def test_poisoned_tree_nodes_off_the_path_do_not_leak(hb, step):
