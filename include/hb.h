@@ -68,6 +68,8 @@ typedef struct hb_attn_desc {
   int32_t total_nodes;         /* node_offset[B]                                            */
   int32_t max_nodes_per_tree;  /* upper bound on nodes per sequence, at most 64             */
   int32_t num_splits;          /* KV partitions per sequence; 0 = let the library choose    */
+                               /* (the MFMA kernel then cuts the KV on the device, from the */
+                               /* actual prefix lengths, evenly over the workgroups)        */
   int32_t max_prefix_len_hint; /* upper bound on prefix_len known to the host, 0 = unknown  */
                                /* (then max_blocks_per_seq * page_size is assumed); with a  */
                                /* prefix longer than a given bound the result is unspecified */
@@ -116,7 +118,8 @@ int32_t hb_tree_verify_attn(const hb_attn_desc *desc, const void *q, const void 
 /* Bytes of workspace hb_tree_verify_attn needs for this descriptor (0 on a bad descriptor). */
 size_t hb_tree_verify_attn_workspace_bytes(const hb_attn_desc *desc);
 
-/* The number of KV partitions the library uses for this descriptor (resolves num_splits == 0). */
+/* The number of KV partitions the library uses for this descriptor (resolves num_splits == 0):
+ * the number of partial results per query row that the workspace has room for. */
 int32_t hb_tree_verify_attn_num_splits(const hb_attn_desc *desc);
 
 /*
