@@ -324,9 +324,10 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
   }
 }
 
-// NW = 4: every thread stages four pieces of K and four of V per tile; two workgroups per CU.
-// NW = 8: wavefronts 0-3 stage K, wavefronts 4-7 stage V (in the same registers), one workgroup
-// per CU with twice the rows sharing each staged tile.
+// TPW: 16-row tiles per wavefront (1 or 2).  NW: wavefronts per workgroup: 4 (two workgroups per
+// CU) or 8 (one per CU, twice the rows sharing each staged tile).  NS: LDS stages of the KV ring.
+// The tree tile, which goes through registers, is staged by all threads (NW = 4) or K by
+// wavefronts 0-3 and V by wavefronts 4-7 (NW = 8).
 template <int TPW, int NW, int NS>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(
     hb_attn_desc d, int splits, int chunk_tokens, int workers, int row_groups, const u32x4 *__restrict__ q, const u32x4 *__restrict__ k_tree,
