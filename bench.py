@@ -137,7 +137,14 @@ def bench_attention_only(cfg, steps, warmup, n_pools=4):
     flops = 4.0 * inp.D * inp.Hq * sum(
         int(n) * (int(L) + 0) for n, L in zip((inp.node_offset[1:] - inp.node_offset[:-1]).tolist(),
                                               inp.prefix_len.tolist()))
+    # vector-ALU estimate: per score about 6.5 lane operations (scale, exp2 at quarter rate counted
+    # as 4, max, half a convert) against 256 CUs x 64 lanes x 2.4 GHz
+    scores_per_s = flops / (4.0 * inp.D) / (ms * 1e-3)
+    valu_frac = scores_per_s * 6.5 / (256 * 64 * 2.4e9)
+    fracs = {"hbm": kv_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+             "mfma": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "valu": valu_frac}
     return {
+        "valu_frac_estimate": valu_frac, "nearest_bound": max(fracs, key=fracs.get),
         "workload": inp.name, "ms": ms, "tree_tokens_per_s": inp.total_nodes / (ms * 1e-3),
         "kv_bytes": kv_bytes, "kv_GBps": kv_bytes / (ms * 1e-3) / 1e9,
         "kv_frac_of_hbm_peak": kv_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
