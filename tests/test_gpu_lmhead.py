@@ -42,7 +42,12 @@ def _check(hidden, weight, ids, mx, rows=None):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("M,K,V", [(1, 8, 1), (5, 64, 1000), (60, 136, 777), (128, 512, 4099), (300, 264, 513)])
+# K % 64 == 0 takes the matrix-core kernel: the shapes below cover its four hidden-tile heights
+# (64 .. 256 rows), one and several hidden tiles, odd and even numbers of K steps, and
+# vocabularies below, at and above one 256-row tile
+@pytest.mark.parametrize("M,K,V", [(1, 8, 1), (5, 64, 1000), (60, 136, 777), (128, 512, 4099), (300, 264, 513),
+                                   (250, 192, 1500), (300, 256, 777), (1000, 128, 3000), (380, 64, 600),
+                                   (64, 320, 256), (193, 448, 255)])
 def test_small_shapes(step, dtype, M, K, V):
     hidden, weight = W.make_lmhead_inputs(M * 7 + V, M, K, V, dtype=dtype, w_std=0.05)
     ids, mx = step.lmhead_argmax(hidden.cuda(), weight.cuda())
