@@ -272,12 +272,15 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, u
   constexpr int TM = 64 * MT;
   int m_tiles = (M + TM - 1) / TM;
   int v_tiles = (V + TV - 1) / TV;
-  // groups per XCD: as many as its 32 CUs hold with one workgroup per CU, but no more than
-  // there are vocabulary tiles to hand out
-  int groups = 32 / m_tiles;
-  if (groups < 1) groups = 1;
+  // groups per XCD: at most as many as its 32 CUs hold with one workgroup per CU; then the
+  // fewest that still need the same number of rounds, so that every group gets the same number
+  // of vocabulary tiles (594 tiles of one hidden tile: 25 groups x 3 rounds per XCD instead of 32
+  // groups of which a third work a round longer)
+  int max_groups = 32 / m_tiles;
+  if (max_groups < 1) max_groups = 1;
   int need = (v_tiles + kXcds - 1) / kXcds;
-  if (groups > need) groups = need;
+  int rounds = (need + max_groups - 1) / max_groups;
+  int groups = (need + rounds - 1) / rounds;
   size_t lds_bytes = (size_t)(3 * TV + 2 * TM) * CH * sizeof(u32x4);
   auto kern = lmhead_mfma_kernel<MT, WV, WNT>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
