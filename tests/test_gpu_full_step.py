@@ -95,3 +95,50 @@ def test_greedy_losslessness_on_the_toy_decoder(kind, topology):
     if kind == "replay":
         full = 5 if topology == "tree" else 4
         assert all(l == full for l in lens[:-1])
+
+
+def test_full_step_replays_from_a_hip_graph(S):
+    """The four calls only enqueue kernels on the caller's stream (no allocation, no memset, no
+    host synchronisation), so a step can be captured into a HIP graph.  The graph is replayed
+    several times, with eager steps and synchronisations in between, on inputs that change
+    between replays (the draft ids), and every replay must give what the eager step gives."""
+    inp = W.make_config(4, scale_down=8)
+    V = 8192
+    _, weight = W.make_lmhead_inputs(45, 1, inp.Hq * inp.D, V, dtype="bf16")
+    dev = S.to_device(inp)
+    desc = S.desc_for(inp)
+    wdev = weight.cuda()
+    draft = torch.zeros(inp.total_nodes, dtype=torch.int32, device="cuda")
+    stp = S.VerifyStep(desc, dev, wdev, draft, inp.max_path)
+    stp.run(compact=False)
+    torch.cuda.synchronize()
+    target = stp.target_ids.cpu().numpy()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        stp.run()  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        stp.run()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (stp.out, stp.target_ids, stp.accept_len, stp.accept_path, stp.out_tokens,
+                                    stp.bonus, stp.out_slots, stp.new_len, dev.k_pool, dev.v_pool)]
+
+    for seed in (4, 5, 6):
+        ids, planted = W.plant_draft_ids(seed, inp.trees(), target, V)
+        stp.draft_ids.copy_(torch.from_numpy(ids))
+        stp.run()
+        eager = snapshot()
+        assert list(stp.accept_len.cpu().numpy()) == [d + 1 for d in planted]
+        for t in (stp.out, stp.target_ids, stp.accept_len, stp.accept_path, stp.out_tokens, stp.bonus,
+                  stp.out_slots, stp.new_len):
+            t.fill_(0) if t.dtype != torch.bfloat16 else t.zero_()
+        graph.replay()
+        replayed = snapshot()
+        for a, b in zip(eager, replayed):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
