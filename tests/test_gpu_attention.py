@@ -172,3 +172,19 @@ def test_full_size_workloads_on_sampled_nodes(hb, step, cfg):
     if cfg == 3 and hb.HB_ATTN_MFMA in _algos(hb, inp):
         # only 8 (sequence, kv head) pairs: the KV-sharing kernel must split the long context
         assert hb.hb_tree_verify_attn_num_splits(desc) > 1
+
+
+def test_device_side_cut_on_random_batches(hb, step):
+    """Seeded random batches (1..20 sequences, prefix lengths 0..2500 with a bias to short ones,
+    trees of 15..60 nodes) through the matrix-core kernel with the library's own KV cut."""
+    rng = np.random.default_rng(2024)
+    for case in range(6):
+        B = int(rng.integers(1, 21))
+        lens = [int(x) for x in np.minimum(rng.geometric(1.0 / 400.0, size=B) - 1, 2500)]
+        if case == 0:
+            lens[0] = 2500
+        trees = [W.seeded_tree(1000 * case + i, n_nodes=int(rng.integers(15, 61))) for i in range(B)]
+        inp = W.make_verify_inputs(500 + case, "bf16", 8, 2, 128, lens, trees, kv_std=1.0, q_std=1.0)
+        ref = oracle_attn(inp)
+        out, lse, _ = _run(step, inp, num_splits=0, algo=hb.HB_ATTN_MFMA, hint=max(max(lens), 1))
+        check_attn(inp, out, lse, ref=ref, label=f"random batch {case}: B={B} lens={lens}")
