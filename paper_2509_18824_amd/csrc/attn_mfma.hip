@@ -196,8 +196,8 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
     // -- scores of the group's tiles, masks, new running maxima (no branches: the matrix and
     //    vector work of different tiles can be interleaved by the scheduler)
     float sc[kGroup][8];
-    float m_new[kGroup], mx_keep[kGroup];
-    bool moved = false;
+    float lmax[kGroup];
+    bool need = false;
 #pragma unroll
     for (int u = 0; u < kGroup; ++u) {
       const int t = t0 + u;
@@ -231,17 +231,15 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
           for (int r = 0; r < 4; ++r)
             sc[u][4 * a + r] = ((allow >> (16 * a + r)) & 1u) ? sc[u][4 * a + r] : HB_NEG_INF;
       }
-      float mx = fmaxf(fmaxf(fmaxf(sc[u][0], sc[u][1]), fmaxf(sc[u][2], sc[u][3])),
-                       fmaxf(fmaxf(sc[u][4], sc[u][5]), fmaxf(sc[u][6], sc[u][7])));
-      mx = group_max(mx) * c1;  // c1 > 0: scaling commutes with the maximum
-      // Reference exponent of the row: the first maximum seen, replaced only when a later
-      // maximum exceeds it by more than kSlack (then exp2(score - reference) <= 2^kSlack stays
-      // far from overflow and the accumulators need no rescaling in between).
-      const float m_old = m_run[t];
-      m_new[u] = (m_old == HB_NEG_INF) ? mx : m_old;  // nothing accumulated yet: adopt, no rescale
-      moved |= mx > m_new[u] + kSlack;
-      m_run[t] = m_new[u];
-      mx_keep[u] = mx;
+      // Largest of the lane's own eight scores.  The row's reference exponent stays as it is
+      // unless one of the row's scores exceeds it by more than kSlack (then exp2(score -
+      // reference) <= 2^kSlack stays far from overflow and nothing needs rescaling); the four
+      // lanes that share a row see all of its scores between them, so a per-lane test decides
+      // and the common case needs no maximum across lanes.  A row without reference yet (-inf:
+      // first block) fails the test in every lane that holds an allowed key.
+      float lm = fmaxf(fmaxf(fmaxf(fmaxf(fmaxf(fmaxf(fmaxf(sc[u][0], sc[u][1]), sc[u][2]), sc[u][3]), sc[u][4]), sc[u][5]), sc[u][6]), sc[u][7]);
+      lmax[u] = lm;
+      need |= !(lm * c1 <= m_run[t] + kSlack);
     }
     // -- all V^T fragments of the block, issued now so that they arrive during the vector work
     //    below (they take over the registers of the K fragments, which are done).  Lane (s, kg)
@@ -262,27 +260,31 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    // -- rare: some row's maximum outgrew its reference; rescale the group's accumulators (rows
-    //    that stay get alpha = 1).  One uniform branch per group; the asm statement keeps it a
-    //    real branch, otherwise the multiply of the whole accumulator is speculated into every
-    //    pass.
-    if (__any(moved)) {
+    // -- rare: a row needs its first reference or has outgrown it.  The reference becomes the
+    //    row's maximum over the block and what has been accumulated is rescaled (rows that stay
+    //    get alpha = 1).  Uniform branches; the asm statement keeps the outer one a real branch,
+    //    otherwise the multiply of the whole accumulator is speculated into every pass.
+    if (__any(need)) {
       asm volatile("" ::: "memory");
 #pragma unroll
       for (int u = 0; u < kGroup; ++u) {
         const int t = t0 + u;
         if (t >= TPW) break;
-        const bool grow = mx_keep[u] > m_new[u] + kSlack;
-        const float alpha = grow ? fast_exp2(m_new[u] - mx_keep[u]) : 1.f;
-        m_new[u] = grow ? mx_keep[u] : m_new[u];
-        l_run[t] *= alpha;
+        const float mx = group_max(lmax[u]) * c1;  // c1 > 0: scaling commutes with the maximum
+        const float m_old = m_run[t];
+        const float m_ref = (m_old == HB_NEG_INF) ? mx : m_old;  // nothing accumulated yet: adopt, no rescale
+        const bool grow = mx > m_ref + kSlack;
+        m_run[t] = grow ? mx : m_ref;
+        if (__any(grow)) {
+          const float alpha = grow ? fast_exp2(m_ref - mx) : 1.f;
+          l_run[t] *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-          asm volatile("" : "+v"(o[t][dt]));
-          o[t][dt] *= alpha;
-          asm volatile("" : "+v"(o[t][dt]));
+          for (int dt = 0; dt < 8; ++dt) {
+            asm volatile("" : "+v"(o[t][dt]));
+            o[t][dt] *= alpha;
+            asm volatile("" : "+v"(o[t][dt]));
+          }
         }
-        m_run[t] = m_new[u];
       }
     }
     // -- probabilities.  Every row has seen at least one allowed key by now (the first key of a
@@ -294,7 +296,7 @@ __device__ __forceinline__ void attend_block(bool partial, const u32x4 *__restri
       if (t >= TPW) break;
       f32x8 p;
 #pragma unroll
-      for (int r = 0; r < 8; ++r) p[r] = fast_exp2(fmaf(sc[u][r], c1, -m_new[u]));
+      for (int r = 0; r < 8; ++r) p[r] = fast_exp2(fmaf(sc[u][r], c1, -m_run[t]));
       pb[u] = __builtin_convertvector(p, bf16x8);
     }
     // -- row sums on the matrix cores: an all-ones A operand makes every row of the product the
