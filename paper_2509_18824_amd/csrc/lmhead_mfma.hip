@@ -53,7 +53,7 @@ __device__ inline int swz(int r, int c) { return r * CH + (c ^ ((r & 7) ^ ((r >>
 // tile, and streaming it through L2 without displacing the hidden rows is worth 5 %; with several
 // hidden tiles the hint evicts weight lines before all sharers have read them.
 template <int MT, int WV, bool WNT>
-__global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles, int groups,
+__global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles, int groups, int spare, int spare_tiles,
                                                           const u32x4 *__restrict__ hidden,
                                                           const u32x4 *__restrict__ weight,
                                                           unsigned long long *__restrict__ keys) {
@@ -79,14 +79,32 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   // tile each; having identical work they advance together, so the weight tile they share is
   // fetched from HBM once and found in the XCD's L2 by the others, and the groups of an XCD read
   // the same K range of the hidden rows at about the same time.
+  // When the groups do not fill the XCD's CUs, the `spare` remaining workgroups of each XCD take
+  // the XCD's first `spare_tiles` vocabulary tiles off the groups' hands, as units of one
+  // (vocabulary tile, hidden tile) pair dealt round-robin, so that the groups need one round
+  // fewer; consecutive units share the weight tile, which the spare workgroups therefore read at
+  // about the same time.
   const int id = blockIdx.x;
   const int xcd = id % kXcds;
   const int slot = id / kXcds;
-  const int m_tile = slot % m_tiles;
-  const int m0 = m_tile * TM;
+  const int in_group = groups * m_tiles;
+  const bool is_spare = slot >= in_group;
   const int kp = K / 8;  // 16-byte pieces per matrix row (K % 8 == 0)
 #pragma unroll 1
-  for (int v_tile = (slot / m_tiles) * kXcds + xcd; v_tile < v_tiles; v_tile += groups * kXcds) {
+  for (int it = 0;; ++it) {
+  int nth, m_tile;  // the XCD's nth vocabulary tile against hidden tile m_tile
+  if (!is_spare) {
+    nth = spare_tiles + slot / m_tiles + it * groups;
+    m_tile = slot % m_tiles;
+  } else {
+    const int unit = slot - in_group + it * spare;
+    if (unit >= spare_tiles * m_tiles) break;
+    nth = unit / m_tiles;
+    m_tile = unit - nth * m_tiles;
+  }
+  const int v_tile = nth * kXcds + xcd;
+  if (v_tile >= v_tiles) break;
+  const int m0 = m_tile * TM;
   const int v0 = v_tile * TV;
 
   // Global -> LDS without passing through registers (global_load_lds_dwordx4): one instruction
@@ -281,12 +299,32 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, u
   int need = (v_tiles + kXcds - 1) / kXcds;
   int rounds = (need + max_groups - 1) / max_groups;
   int groups = (need + rounds - 1) / rounds;
+  // CUs of an XCD that no group occupies: if handing them a few vocabulary tiles (every XCD has
+  // at least v_tiles / 8) saves the groups a round, do so (960 rows = 5 hidden tiles: 6 groups
+  // on 30 CUs would need 13 rounds for 75 tiles; with 3 tiles on the 2 other CUs, 15 units in 8
+  // rounds, they need 12).  The fewest tiles that reach the best round count are handed over.
+  int spare = 0, spare_tiles = 0;
+  if (m_tiles <= 32) {
+    const int left = 32 - max_groups * m_tiles;
+    int best = rounds;
+    for (int y = 1; left > 0 && y <= v_tiles / kXcds; ++y) {
+      const int full = (need - y + max_groups - 1) / max_groups;
+      const int mine = (y * m_tiles + left - 1) / left;
+      const int cost = full > mine ? full : mine;
+      if (cost < best) {
+        best = cost;
+        spare = left;
+        spare_tiles = y;
+      }
+    }
+    if (spare) groups = max_groups;
+  }
   size_t lds_bytes = (size_t)(3 * TV + 2 * TM) * CH * sizeof(u32x4);
   auto kern = lmhead_mfma_kernel<MT, WV, WNT>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
-  dim3 grid((unsigned)(groups * m_tiles * kXcds));
-  kern<<<grid, 128 * WV, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, groups, (const u32x4 *)hidden, (const u32x4 *)weight, keys);
+  dim3 grid((unsigned)((groups * m_tiles + spare) * kXcds));
+  kern<<<grid, 128 * WV, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, groups, spare, spare_tiles, (const u32x4 *)hidden, (const u32x4 *)weight, keys);
   return hipGetLastError();
 }
 
