@@ -55,6 +55,28 @@ def test_small_shapes(step, dtype, M, K, V):
     _check(hidden, weight, ids, mx)
 
 
+def test_work_units_of_the_left_over_cus(step):
+    """960 rows are five 192-row hidden tiles: six lockstep groups occupy 30 of an XCD's 32 CUs.
+    With 152 vocabulary tiles (19 per XCD) the other two CUs take the XCD's first tile as five
+    (vocabulary tile, hidden tile) units, which saves the groups their fourth round.  Every row
+    is checked against the oracle over the whole vocabulary, and winners are planted in the tiles
+    that travel that way (vocabulary ids below 8 * 256) and in the ragged last tile."""
+    M, K, V = 960, 192, 152 * 256 - 100
+    hidden, weight = W.make_lmhead_inputs(4242, M, K, V, dtype="bf16", w_std=0.05)
+    rng = np.random.default_rng(7)
+    planted = {}
+    for m in rng.choice(M, size=120, replace=False):
+        v = int(rng.integers(0, 2048)) if m % 3 else int(rng.integers(V - 156, V))
+        weight[v] = (hidden[m].float() * 0.5).to(weight.dtype)
+        planted[int(m)] = v
+    ids, mx = step.lmhead_argmax(hidden.cuda(), weight.cuda())
+    torch.cuda.synchronize()
+    _check(hidden, weight, ids, mx)
+    got = ids.cpu().numpy()
+    hit = sum(int(got[m]) == v for m, v in planted.items())
+    assert hit >= 100  # a later planted row can only lose to another planted row of the same kind
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_planted_winner_ties_and_nan(step, dtype):
     M, K, V = 70, 256, 3000
