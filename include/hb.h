@@ -24,8 +24,8 @@
  *     pending committed token), 0 <= parent[i] < i otherwise.  Trees of a batch are
  *     concatenated; node_offset[b] .. node_offset[b+1] are the nodes of sequence b.
  *   - Tensors are dense, row-major, in the layouts stated per function, and start at a 16-byte
- *     aligned address (kernels move 16-byte pieces).  bf16 is the upper half of an IEEE float32
- *     (round to nearest even on output).
+ *     aligned address (kernels move 16-byte pieces; another address is HB_ERR_INVALID_ARG).
+ *     bf16 is the upper half of an IEEE float32 (round to nearest even on output).
  */
 #ifndef HB_H
 #define HB_H

@@ -21,6 +21,8 @@ int32_t fail_hip(hipError_t e, const char *what) {
 }
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+// tensors start at a 16-byte aligned address (the kernels move 16-byte pieces)
+static bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }
 static int32_t gcd32(int32_t a, int32_t b) { while (b) { int32_t t = a % b; a = b; b = t; } return a; }
 
 static int32_t check_shape(const hb_attn_desc *d) {
@@ -170,6 +172,9 @@ int32_t hb_tree_verify_attn(const hb_attn_desc *desc, const void *q, const void 
   if (!q || !k_tree || !v_tree || !k_pool || !v_pool || !block_table || !prefix_len || !node_offset ||
       !parent || !out)
     return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(q) || misaligned(k_tree) || misaligned(v_tree) || misaligned(k_pool) || misaligned(v_pool) ||
+      misaligned(out))
+    return fail(HB_ERR_INVALID_ARG, "q, k_tree, v_tree, k_pool, v_pool and out must be 16-byte aligned");
   float *part_o = nullptr, *part_ml = nullptr;
   if (plan.splits > 1) {
     if (!workspace || workspace_bytes < plan.bytes)
@@ -200,6 +205,8 @@ int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const v
   if (M < 0 || K <= 0 || V <= 0) return fail(HB_ERR_INVALID_ARG, "need M >= 0, K > 0, V > 0 (got %d, %d, %d)", M, K, V);
   if (M == 0) return HB_OK;
   if (!hidden || !weight || !out_ids) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(hidden) || misaligned(weight))
+    return fail(HB_ERR_INVALID_ARG, "hidden and weight must be 16-byte aligned");
   size_t need = hb_lmhead_argmax_workspace_bytes(M);
   if (!workspace || workspace_bytes < need)
     return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
@@ -246,6 +253,8 @@ int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *
   if (!k_tree || !v_tree || !k_pool || !v_pool || !block_table || !prefix_len || !node_offset ||
       !accept_len || !accept_path)
     return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(k_tree) || misaligned(v_tree) || misaligned(k_pool) || misaligned(v_pool))
+    return fail(HB_ERR_INVALID_ARG, "k_tree, v_tree, k_pool and v_pool must be 16-byte aligned");
   HB_HIP_TRY(launch_kv_compact(*desc, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset,
                                accept_len, accept_path, max_path, out_slots, new_len, (hipStream_t)stream));
   return HB_OK;

@@ -71,6 +71,9 @@ def test_attention_argument_errors():
     assert _attn_rc(_desc(dtype="f32", D=64, algo=hb.HB_ATTN_MFMA)) == 2
     # empty batches are a no-op that needs no pointers
     assert _attn_rc(_desc(B=0, total_nodes=0), ptr=0) == 0
+    # tensors must start at a 16-byte aligned address
+    assert _attn_rc(_desc(), ptr=0x1008) == 1
+    assert "aligned" in hb.hb_last_error()
 
 
 def test_split_plan_is_consistent():
@@ -94,6 +97,8 @@ def test_lmhead_accept_compact_argument_errors():
     assert L.hb_lmhead_argmax(1, 4, 8, 16, p, p, p, None, p, 8, None) == 3
     assert L.hb_lmhead_argmax(1, 4, 8, 16, None, p, p, None, p, 64, None) == 1
     assert L.hb_lmhead_argmax(1, 0, 8, 16, None, None, None, None, None, 0, None) == 0
+    assert L.hb_lmhead_argmax(1, 4, 8, 16, C.c_void_p(0x1004), p, p, None, p, 64, None) == 1
+    assert "aligned" in hb.hb_last_error()
     assert hb.hb_lmhead_argmax_workspace_bytes(960) == 960 * 8
     assert L.hb_tree_accept(2, 65, p, p, p, p, 6, p, p, p, p, None) == 2
     assert L.hb_tree_accept(2, 60, p, p, p, p, 0, p, p, p, p, None) == 1
@@ -103,3 +108,5 @@ def test_lmhead_accept_compact_argument_errors():
     assert L.hb_kv_compact(C.byref(d), p, p, p, p, p, p, p, p, p, 0, None, None, None) == 1
     assert L.hb_kv_compact(C.byref(d), None, p, p, p, p, p, p, p, p, 6, None, None, None) == 1
     assert L.hb_kv_compact(None, p, p, p, p, p, p, p, p, p, 6, None, None, None) == 1
+    assert L.hb_kv_compact(C.byref(d), C.c_void_p(0x1002), p, p, p, p, p, p, p, p, 6, None, None, None) == 1
+    assert "aligned" in hb.hb_last_error()
