@@ -163,6 +163,7 @@ def main():
     ap.add_argument("--no-attn-extra", action="store_true", help="skip the attention-only runs of the "
                     "ragged-batch and long-context workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stack", action="store_true", help="skip the 28-layer variant of the step")
     ap.add_argument("--copy-probe", action="store_true", help="also run three 1 GiB device-to-device "
                     "copies before the timed region: the known-size reference for scaling the "
                     "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -299,6 +300,47 @@ def main():
             "attn_splits": hb.hb_tree_verify_attn_num_splits(desc),
         },
     }
+    if not args.no_stack:
+        # The same step with a realistic depth: 28 attention layers over 28 distinct KV pools (2.3 GB,
+        # so every layer streams its KV from HBM), one LM head, one acceptance, 28 compactions.
+        # Reported next to the headline figure, which is the one-layer step.
+        n_layers, n_stack = 28, max(5, args.steps // 5)
+        pools = [(dv.k_pool, dv.v_pool)] + [(dv.k_pool.clone(), dv.v_pool.clone()) for _ in range(n_layers - 1)]
+
+        def stack_step(ev=None):
+            if ev: ev[0].record()
+            for kp, vp in pools:
+                hb.hb_tree_verify_attn(desc, dv.q, dv.k_tree, dv.v_tree, kp, vp, dv.block_table, dv.prefix_len,
+                                       dv.node_offset, dv.parent, step.out, None, step.ws_attn)
+            if ev: ev[1].record()
+            hb.hb_lmhead_argmax(step.out.view(inp.total_nodes, -1), wdev, step.target_ids, None, step.ws_lm)
+            hb.hb_tree_accept(desc.batch, desc.max_nodes_per_tree, dv.node_offset, dv.parent, step.draft_ids,
+                              step.target_ids, step.max_path, step.accept_len, step.accept_path,
+                              step.out_tokens, step.bonus)
+            for kp, vp in pools:
+                hb.hb_kv_compact(desc, dv.k_tree, dv.v_tree, kp, vp, dv.block_table, dv.prefix_len,
+                                 dv.node_offset, step.accept_len, step.accept_path, step.max_path,
+                                 step.out_slots, step.new_len)
+
+        for _ in range(2):
+            stack_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_stack):
+            stack_step()
+        torch.cuda.synchronize()
+        ms_stack = (time.perf_counter() - t0) * 1e3 / n_stack
+        ev = _events(n_stack)
+        for i in range(n_stack):
+            stack_step(ev[i])
+        torch.cuda.synchronize()
+        ms_attn_layer = _mean_ms(ev) / n_layers
+        result["stack28"] = {
+            "layers": n_layers, "steps": n_stack, "ms_per_step": ms_stack,
+            "tree_tokens_per_s": M / (ms_stack * 1e-3), "attn_ms_per_layer": ms_attn_layer,
+            "kv_GBps": kv_bytes / (ms_attn_layer * 1e-3) / 1e9,
+        }
+        del pools
     if not args.no_attn_extra and args.tree == "tree":
         del step, wdev
         torch.cuda.empty_cache()
