@@ -162,16 +162,28 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(int rows, int D, int sp
   const int piece = (int)(gid - (long)row * tpr);
   if (row >= rows) return;
   const merge_f32x2 *ml = reinterpret_cast<const merge_f32x2 *>(part_ml) + (size_t)row * splits;
-  if (ml[0].y < 0.f) return;  // the attention kernel wrote this row out itself (row sums are never negative)
   // Chunks are filled from slot 0 on and empty ones only follow non-empty ones (a chunk that
   // holds any key has l > 0), so the first empty slot ends the list; producers need to mark
   // only that one.
+  // Slots are read kMergeBatch at a time (independent loads: one round trip per batch instead
+  // of one per slot).
   float m = -__builtin_huge_valf();
   int live = 0;
-  for (; live < splits; ++live) {
-    merge_f32x2 x = ml[live];
-    if (!(x.y > 0.f)) break;
-    m = fmaxf(m, x.x);
+  bool open = true;
+  for (int c0 = 0; c0 < splits && open; c0 += kMergeBatch) {
+    merge_f32x2 x[kMergeBatch];
+#pragma unroll
+    for (int i = 0; i < kMergeBatch; ++i) {
+      x[i] = (merge_f32x2){0.f, 0.f};
+      if (c0 + i < splits) x[i] = ml[c0 + i];
+    }
+    if (c0 == 0 && x[0].y < 0.f) return;  // the attention kernel wrote this row out itself (row sums are never negative)
+#pragma unroll
+    for (int i = 0; i < kMergeBatch; ++i) {
+      open = open && x[i].y > 0.f;
+      m = open ? fmaxf(m, x[i].x) : m;
+      live += open ? 1 : 0;
+    }
   }
   const merge_f32x4 *po = reinterpret_cast<const merge_f32x4 *>(part_o) + (size_t)row * splits * tpr + piece;
   float l = 0.f;
