@@ -146,6 +146,12 @@ size_t hb_lmhead_argmax_workspace_bytes(int32_t M);
  * match.  The deepest accepted node wins (lowest id among equals).  accept_len is the number
  * of tokens the step emits (accepted drafts below the root plus the bonus token), the quantity
  * whose mean the paper reports as average acceptance length (Table 1).
+ * prev_target_or_null (device int32 [B], or NULL) switches to the reading in which the root too
+ * is a guess: it matches only when draft_ids[root] == prev_target[b], the token the target chose
+ * at the end of the previous step.  A rejected root voids the whole tree: accept_len = 0, path
+ * and tokens all -1, bonus_id = prev_target[b].  A sequence without nodes gives accept_len = 0,
+ * path and tokens -1 and bonus_id = prev_target[b] (-1 when NULL); hb_kv_compact then copies
+ * nothing for it.
  *
  *   node_offset  device int32 [B+1]     parent, draft_ids, target_ids  device int32 [total]
  *   accept_len   device int32 [B]       bonus_id  device int32 [B] = target_ids[best node]
@@ -157,8 +163,8 @@ size_t hb_lmhead_argmax_workspace_bytes(int32_t M);
  */
 int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,
                        const int32_t *parent, const int32_t *draft_ids, const int32_t *target_ids,
-                       int32_t max_path, int32_t *accept_len, int32_t *accept_path,
-                       int32_t *out_tokens, int32_t *bonus_id, void *stream);
+                       const int32_t *prev_target_or_null, int32_t max_path, int32_t *accept_len,
+                       int32_t *accept_path, int32_t *out_tokens, int32_t *bonus_id, void *stream);
 
 /*
  * Append the accepted path's K/V to the paged cache of one layer (Section 4.1: committed

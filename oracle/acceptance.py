@@ -6,15 +6,24 @@ ancestors match.  The step keeps the deepest accepted node (lowest id among equa
 draft ids along its path after the root plus the target's token at that node (the bonus token).
 The number of emitted tokens is the per-step acceptance length whose mean the paper reports as
 tau (Table 1, following EAGLE-3).
+
+Second reading of the root (optional ``prev_target``): node 0 is itself a guess for the token
+the target chose at the end of the previous step, and matches iff draft_ids[0] equals that
+token.  A matching root gives exactly the result above.  A rejected root invalidates every
+node (all were computed on a wrong context): nothing is accepted, nothing is emitted, the
+pending token stays prev_target.  A sequence without nodes behaves the same way with no
+pending token known (-1).
 """
 from __future__ import annotations
 
 import numpy as np
 
 
-def tree_accept_ref(node_offset, parent, draft_ids, target_ids, max_path):
+def tree_accept_ref(node_offset, parent, draft_ids, target_ids, max_path, prev_target=None):
     """Returns accept_len[B], accept_path[B,max_path], out_tokens[B,max_path], bonus_id[B]
-    (int32; paths hold tree-local node ids, unused entries are -1)."""
+    (int32; paths hold tree-local node ids, unused entries are -1).  prev_target int[B] or None:
+    when given, the root of sequence b is accepted only if draft_ids[root] == prev_target[b];
+    otherwise accept_len[b] = 0 and bonus_id[b] = prev_target[b]."""
     node_offset = np.asarray(node_offset)
     parent = np.asarray(parent)
     draft_ids = np.asarray(draft_ids)
@@ -30,6 +39,10 @@ def tree_accept_ref(node_offset, parent, draft_ids, target_ids, max_path):
         d_ids = draft_ids[n0:n1]
         t_ids = target_ids[n0:n1]
         n = n1 - n0
+        if n == 0 or (prev_target is not None and int(d_ids[0]) != int(prev_target[b])):
+            # no node, or a root that is not the token the target had chosen: nothing is valid
+            bonus_id[b] = -1 if prev_target is None else int(prev_target[b])
+            continue
         acc = np.zeros(n, dtype=bool)
         depth = np.zeros(n, dtype=np.int64)
         acc[0] = True

@@ -61,7 +61,7 @@ def _load():
     lib.hb_lmhead_argmax_workspace_bytes.restype = sz
     lib.hb_lmhead_argmax_workspace_bytes.argtypes = [i32]
     lib.hb_tree_accept.restype = i32
-    lib.hb_tree_accept.argtypes = [i32, i32, p, p, p, p, i32, p, p, p, p, p]
+    lib.hb_tree_accept.argtypes = [i32, i32, p, p, p, p, p, i32, p, p, p, p, p]
     lib.hb_kv_compact.restype = i32
     lib.hb_kv_compact.argtypes = [C.POINTER(AttnDesc)] + [p] * 9 + [i32, p, p, p]
     return lib
@@ -144,9 +144,10 @@ def hb_lmhead_argmax(hidden, weight, out_ids, out_max=None, workspace=None, stre
 
 
 def hb_tree_accept(B: int, max_nodes_per_tree: int, node_offset, parent, draft_ids, target_ids,
-                   max_path: int, accept_len, accept_path, out_tokens, bonus_id, stream=None) -> None:
+                   max_path: int, accept_len, accept_path, out_tokens, bonus_id, stream=None,
+                   prev_target=None) -> None:
     _check(lib.hb_tree_accept(B, max_nodes_per_tree, _ptr(node_offset), _ptr(parent), _ptr(draft_ids),
-                              _ptr(target_ids), max_path, _ptr(accept_len), _ptr(accept_path),
+                              _ptr(target_ids), _ptr(prev_target), max_path, _ptr(accept_len), _ptr(accept_path),
                               _ptr(out_tokens), _ptr(bonus_id), _stream(stream)))
 
 

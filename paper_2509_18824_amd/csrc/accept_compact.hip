@@ -13,15 +13,15 @@ namespace {
 
 __global__ __launch_bounds__(64) void tree_accept_kernel(
     int max_nodes, const int32_t *__restrict__ node_offset, const int32_t *__restrict__ parent,
-    const int32_t *__restrict__ draft_ids, const int32_t *__restrict__ target_ids, int max_path,
-    int32_t *__restrict__ accept_len, int32_t *__restrict__ accept_path, int32_t *__restrict__ out_tokens,
+    const int32_t *__restrict__ draft_ids, const int32_t *__restrict__ target_ids,
+    const int32_t *__restrict__ prev_target, int max_path, int32_t *__restrict__ accept_len, int32_t *__restrict__ accept_path, int32_t *__restrict__ out_tokens,
     int32_t *__restrict__ bonus_id) {
   __shared__ int32_t spar[64];
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
   const int n0 = node_offset[b];
   int n = node_offset[b + 1] - n0;
-  n = n < 1 ? 1 : (n > max_nodes ? max_nodes : n);
+  n = n < 0 ? 0 : (n > max_nodes ? max_nodes : n);
   const bool live = lane < n;
 
   int par = -1, did = 0, tid_ = 0;
@@ -44,7 +44,10 @@ __global__ __launch_bounds__(64) void tree_accept_kernel(
   }
   bool rooted = live && (anc & 1ull);  // a path that does not reach node 0 is never accepted
   int par_target = __shfl(tid_, par < 0 ? 0 : par, 64);
-  bool match = live && (lane == 0 || did == par_target);
+  // the root is the pending committed token (always a match) unless the caller names the token
+  // the target chose last step: then the root is a guess like any other node
+  const int prev = prev_target ? prev_target[b] : 0;
+  bool match = live && (lane == 0 ? (!prev_target || did == prev) : did == par_target);
   unsigned long long match_mask = __ballot(match);
   int depth = __popcll(anc) - 1;
   bool accepted = rooted && ((anc & ~match_mask) == 0ull) && depth < max_path;
@@ -53,6 +56,19 @@ __global__ __launch_bounds__(64) void tree_accept_kernel(
   int key = accepted ? depth * 64 + (63 - lane) : -1;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) key = max(key, __shfl_xor(key, off, 64));
+  // no node accepted (no nodes at all, or a rejected root): nothing is emitted, the pending
+  // token stays what it was
+  if (key < 0) {
+    for (int j = lane; j < max_path; j += 64) {
+      accept_path[(size_t)b * max_path + j] = -1;
+      out_tokens[(size_t)b * max_path + j] = -1;
+    }
+    if (lane == 0) {
+      accept_len[b] = 0;
+      bonus_id[b] = prev_target ? prev : -1;
+    }
+    return;
+  }
   const int best = 63 - (key & 63);
   const int len = (key >> 6) + 1;
   const unsigned long long best_anc = __shfl((long long)anc, best, 64);
@@ -117,10 +133,10 @@ __global__ __launch_bounds__(256) void kv_compact_kernel(
 
 hipError_t launch_tree_accept(int32_t B, int32_t max_nodes, const int32_t *node_offset,
                               const int32_t *parent, const int32_t *draft_ids,
-                              const int32_t *target_ids, int32_t max_path, int32_t *accept_len,
-                              int32_t *accept_path, int32_t *out_tokens, int32_t *bonus_id,
-                              hipStream_t s) {
-  tree_accept_kernel<<<B, 64, 0, s>>>(max_nodes, node_offset, parent, draft_ids, target_ids, max_path,
+                              const int32_t *target_ids, const int32_t *prev_target, int32_t max_path,
+                              int32_t *accept_len, int32_t *accept_path, int32_t *out_tokens,
+                              int32_t *bonus_id, hipStream_t s) {
+  tree_accept_kernel<<<B, 64, 0, s>>>(max_nodes, node_offset, parent, draft_ids, target_ids, prev_target, max_path,
                                       accept_len, accept_path, out_tokens, bonus_id);
   return hipGetLastError();
 }

@@ -225,8 +225,8 @@ int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const v
 
 int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,
                        const int32_t *parent, const int32_t *draft_ids, const int32_t *target_ids,
-                       int32_t max_path, int32_t *accept_len, int32_t *accept_path,
-                       int32_t *out_tokens, int32_t *bonus_id, void *stream) {
+                       const int32_t *prev_target_or_null, int32_t max_path, int32_t *accept_len,
+                       int32_t *accept_path, int32_t *out_tokens, int32_t *bonus_id, void *stream) {
   if (B < 0 || max_path <= 0 || max_nodes_per_tree <= 0)
     return fail(HB_ERR_INVALID_ARG, "need B >= 0, max_path > 0, max_nodes_per_tree > 0");
   if (max_nodes_per_tree > 64)
@@ -236,7 +236,8 @@ int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *nod
   if (!node_offset || !parent || !draft_ids || !target_ids || !accept_len || !accept_path || !out_tokens ||
       !bonus_id)
     return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
-  HB_HIP_TRY(launch_tree_accept(B, max_nodes_per_tree, node_offset, parent, draft_ids, target_ids, max_path,
+  HB_HIP_TRY(launch_tree_accept(B, max_nodes_per_tree, node_offset, parent, draft_ids, target_ids,
+                                prev_target_or_null, max_path,
                                 accept_len, accept_path, out_tokens, bonus_id, (hipStream_t)stream));
   return HB_OK;
 }

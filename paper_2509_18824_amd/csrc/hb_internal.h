@@ -89,9 +89,9 @@ hipError_t launch_lmhead_finish(const unsigned long long *keys, int32_t M, int32
 
 hipError_t launch_tree_accept(int32_t B, int32_t max_nodes, const int32_t *node_offset,
                               const int32_t *parent, const int32_t *draft_ids,
-                              const int32_t *target_ids, int32_t max_path, int32_t *accept_len,
-                              int32_t *accept_path, int32_t *out_tokens, int32_t *bonus_id,
-                              hipStream_t s);
+                              const int32_t *target_ids, const int32_t *prev_target, int32_t max_path,
+                              int32_t *accept_len, int32_t *accept_path, int32_t *out_tokens,
+                              int32_t *bonus_id, hipStream_t s);
 hipError_t launch_kv_compact(const hb_attn_desc &d, const void *k_tree, const void *v_tree,
                              void *k_pool, void *v_pool, const int32_t *block_table,
                              const int32_t *prefix_len, const int32_t *node_offset,

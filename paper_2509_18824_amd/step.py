@@ -78,7 +78,7 @@ def lmhead_argmax(hidden, weight, want_max=True, workspace=None):
     return ids, mx
 
 
-def tree_accept(node_offset, parent, draft_ids, target_ids, max_path, max_nodes):
+def tree_accept(node_offset, parent, draft_ids, target_ids, max_path, max_nodes, prev_target=None):
     B = node_offset.numel() - 1
     dev = node_offset.device
     accept_len = torch.empty(B, dtype=torch.int32, device=dev)
@@ -86,7 +86,7 @@ def tree_accept(node_offset, parent, draft_ids, target_ids, max_path, max_nodes)
     out_tokens = torch.empty((B, max_path), dtype=torch.int32, device=dev)
     bonus = torch.empty(B, dtype=torch.int32, device=dev)
     hb.hb_tree_accept(B, max_nodes, node_offset, parent, draft_ids, target_ids, max_path, accept_len,
-                      accept_path, out_tokens, bonus)
+                      accept_path, out_tokens, bonus, prev_target=prev_target)
     return accept_len, accept_path, out_tokens, bonus
 
 

@@ -100,10 +100,10 @@ def test_lmhead_accept_compact_argument_errors():
     assert L.hb_lmhead_argmax(1, 4, 8, 16, C.c_void_p(0x1004), p, p, None, p, 64, None) == 1
     assert "aligned" in hb.hb_last_error()
     assert hb.hb_lmhead_argmax_workspace_bytes(960) == 960 * 8
-    assert L.hb_tree_accept(2, 65, p, p, p, p, 6, p, p, p, p, None) == 2
-    assert L.hb_tree_accept(2, 60, p, p, p, p, 0, p, p, p, p, None) == 1
-    assert L.hb_tree_accept(2, 60, None, p, p, p, 6, p, p, p, p, None) == 1
-    assert L.hb_tree_accept(0, 60, None, None, None, None, 6, None, None, None, None, None) == 0
+    assert L.hb_tree_accept(2, 65, p, p, p, p, None, 6, p, p, p, p, None) == 2
+    assert L.hb_tree_accept(2, 60, p, p, p, p, None, 0, p, p, p, p, None) == 1
+    assert L.hb_tree_accept(2, 60, None, p, p, p, p, 6, p, p, p, p, None) == 1
+    assert L.hb_tree_accept(0, 60, None, None, None, None, None, 6, None, None, None, None, None) == 0
     d = _desc()
     assert L.hb_kv_compact(C.byref(d), p, p, p, p, p, p, p, p, p, 0, None, None, None) == 1
     assert L.hb_kv_compact(C.byref(d), None, p, p, p, p, p, p, p, p, 6, None, None, None) == 1

@@ -16,12 +16,13 @@ def step():
     return s
 
 
-def _accept_both(step, trees, draft, target, max_path):
+def _accept_both(step, trees, draft, target, max_path, prev_target=None):
     off = np.concatenate([[0], np.cumsum([len(t) for t in trees])]).astype(np.int32)
     par = np.concatenate(trees).astype(np.int32)
-    ref = tree_accept_ref(off, par, draft, target, max_path)
+    ref = tree_accept_ref(off, par, draft, target, max_path, prev_target=prev_target)
     t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.int32)).cuda()
-    got = step.tree_accept(t(off), t(par), t(draft), t(target), max_path, max(len(x) for x in trees))
+    got = step.tree_accept(t(off), t(par), t(draft), t(target), max_path, max(max(len(x) for x in trees), 1),
+                           prev_target=None if prev_target is None else t(prev_target))
     torch.cuda.synchronize()
     for g, r, name in zip(got, ref, ("accept_len", "accept_path", "out_tokens", "bonus_id")):
         assert np.array_equal(g.cpu().numpy(), r), name
@@ -60,6 +61,50 @@ def test_random_small_vocab_with_duplicates_and_ties(step):
         draft = rng.integers(0, 3, size=total)
         target = rng.integers(0, 3, size=total)
         _accept_both(step, trees, draft, target, 64)
+
+
+def test_root_as_a_guess_and_sequences_without_nodes(step):
+    """prev_target makes the root one more guess (a rejected root voids the tree); a sequence
+    whose tree is empty, also the last of the batch, emits nothing.  Compaction then appends
+    nothing for those sequences."""
+    rng = np.random.default_rng(11)
+    for trial in range(12):
+        B = int(rng.integers(1, 7))
+        trees = []
+        for b in range(B):
+            n = int(rng.integers(0, 20)) if (trial + b) % 3 else 0
+            trees.append(np.array(([-1] + [int(rng.integers(0, i)) for i in range(1, n)]) if n else [], dtype=np.int32))
+        if all(len(t) == 0 for t in trees):
+            trees[0] = W.chain_tree(3)
+        total = sum(len(t) for t in trees)
+        draft = rng.integers(0, 3, size=total)
+        target = rng.integers(0, 3, size=total)
+        prev = rng.integers(0, 3, size=B)
+        ref = _accept_both(step, trees, draft, target, 20, prev_target=prev)
+        ref0 = _accept_both(step, trees, draft, target, 20)
+        for b, t in enumerate(trees):
+            if len(t) == 0:
+                assert ref[0][b] == 0 and ref[3][b] == prev[b] and ref0[0][b] == 0 and ref0[3][b] == -1
+    # compaction with empty and voided sequences: whole pools compared
+    trees = [W.seeded_tree(1), np.array([], dtype=np.int32), W.chain_tree(4), np.array([], dtype=np.int32)]
+    inp = W.make_verify_inputs(5, "bf16", 4, 2, 64, [14, 20, 15, 3], trees, poison=False)
+    target = np.random.default_rng(2).integers(0, 50, size=inp.total_nodes)
+    draft, _ = W.plant_draft_ids(2, [trees[0], trees[2]], target, 50, want_depth=[3, 2])
+    prev = np.array([draft[0], 7, (draft[len(trees[0])] + 1) % 50, 9])  # sequence 2: rejected root
+    alen, apath, _, bonus = tree_accept_ref(inp.node_offset.numpy(), inp.parent.numpy(), draft, target,
+                                            inp.max_path, prev_target=prev)
+    assert list(alen) == [4, 0, 0, 0] and list(bonus[1:]) == [7, prev[2], 9]
+    ref_k, ref_v, ref_slots, ref_len = kv_compact_ref(bits(inp.k_tree), bits(inp.v_tree), bits(inp.k_pool),
+                                                      bits(inp.v_pool), inp.block_table.numpy(),
+                                                      inp.prefix_len.numpy(), inp.node_offset.numpy(), alen, apath)
+    dev = step.to_device(inp)
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.int32)).cuda()
+    got = step.tree_accept(dev.node_offset, dev.parent, t(draft), t(target), inp.max_path, 60, prev_target=t(prev))
+    assert np.array_equal(got[0].cpu().numpy(), alen) and np.array_equal(got[1].cpu().numpy(), apath)
+    slots, new_len = step.kv_compact(step.desc_for(inp), dev, got[0], got[1])
+    torch.cuda.synchronize()
+    assert np.array_equal(slots.cpu().numpy(), ref_slots) and np.array_equal(new_len.cpu().numpy(), ref_len)
+    assert np.array_equal(bits(dev.k_pool), ref_k) and np.array_equal(bits(dev.v_pool), ref_v)
 
 
 @pytest.mark.parametrize("dtype,Hkv,D", [("bf16", 4, 128), ("f32", 1, 64), ("bf16", 2, 64)])

@@ -1,5 +1,5 @@
 """GPU parity: hb_tree_verify_attn against the CPU oracle, element by element on sizes the
-oracle finishes in seconds, and on sampled nodes at the full workload sizes."""
+oracle finishes in seconds, and on every node at the full workload sizes."""
 import numpy as np
 import pytest
 import torch
@@ -153,25 +153,79 @@ def test_results_are_deterministic(hb, step):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4])
-def test_full_size_workloads_on_sampled_nodes(hb, step, cfg):
-    """Full sizes, default launch configuration (the one the benchmark times); the oracle
-    recomputes a seeded sample of nodes from every sequence."""
-    inp = W.make_config(cfg)
-    rng = np.random.default_rng(cfg)
-    off = inp.node_offset.numpy()
-    per_seq = 2 if cfg != 3 else 6
-    nodes = sorted(int(off[b] + i) for b in range(inp.B)
-                   for i in rng.choice(off[b + 1] - off[b], size=per_seq, replace=False))
-    ref = oracle_attn(inp, nodes=nodes)
+@pytest.mark.parametrize("cfg,tree", [(2, "tree"), (3, "tree"), (4, "tree"), (4, "chain8")])
+def test_full_size_workloads_every_node(hb, step, cfg, tree):
+    """Full sizes, default launch configuration (the one the benchmark times), with and without
+    the length hint the benchmark passes; the oracle recomputes every node of every sequence.
+    The 8-node-chain run of the full-step workload takes the four-wavefront kernel with the
+    device-side KV cut over 16 ragged prefixes."""
+    inp = W.make_config(cfg, tree=tree)
+    ref = oracle_attn(inp)
     hint = int(inp.prefix_len.max())
     for kw in (dict(), dict(hint=hint)):
         out, lse, desc = _run(step, inp, **kw)
-        check_attn(inp, out, lse, nodes=nodes, ref=ref, label=f"cfg{cfg} full {kw}")
+        check_attn(inp, out, lse, ref=ref, label=f"cfg{cfg} {tree} full {kw}")
         assert torch.isfinite(out.float()).all()
+        # per-row check as well: a wrong row must not hide in the batch-wide norms
+        got, want = W.widen(out), ref[0]
+        rel_rows = np.linalg.norm(got - want, axis=2) / np.linalg.norm(want, axis=2)
+        assert rel_rows.max() <= 3e-2, f"cfg{cfg} {tree}: worst row rel err {rel_rows.max():.3e}"
     if cfg == 3 and hb.HB_ATTN_MFMA in _algos(hb, inp):
         # only 8 (sequence, kv head) pairs: the KV-sharing kernel must split the long context
         assert hb.hb_tree_verify_attn_num_splits(desc) > 1
+
+
+def _planted_scores(inp, log2_scores):
+    """Overwrite sequence 0 so that the prefix key at position p scores log2_scores[p] (in log2
+    units, i.e. score * log2(e)) against a query that is c_r * e_0, c_r = 1 for row 0 and
+    slightly different for other rows; all other key components are 0, V stays random."""
+    L = len(log2_scores)
+    assert int(inp.prefix_len[0]) == L
+    ln2 = float(np.log(2.0))
+    q = torch.zeros_like(inp.q, dtype=torch.float32)
+    T, Hq, _ = inp.q.shape
+    # row-dependent gain: rows cross the rescale threshold at different blocks
+    gain = 1.0 + 0.03125 * (torch.arange(T * Hq).reshape(T, Hq) % 5).float()
+    q[:, :, 0] = gain / inp.softmax_scale
+    inp.q.copy_(q.to(inp.q.dtype))
+    kt = torch.zeros_like(inp.k_tree, dtype=torch.float32)
+    kt[:, :, 0] = float(log2_scores[-1]) * ln2  # tree keys score like the last prefix key
+    inp.k_tree.copy_(kt.to(inp.k_tree.dtype))
+    for p in range(L):
+        blk = int(inp.block_table[0, p // inp.page])
+        row = torch.zeros(inp.D)
+        row[0] = float(log2_scores[p]) * ln2
+        inp.k_pool[blk, :, p % inp.page] = row.to(inp.k_pool.dtype)
+    return inp
+
+
+@pytest.mark.parametrize("shape", ["tree60_gqa7", "chain8_gqa7", "tree20_gqa1"])
+def test_reference_exponent_of_the_online_softmax_under_climbing_scores(hb, step, shape):
+    """The matrix-core kernel keeps a per-row reference exponent that moves only when a score
+    outgrows it by a fixed slack (2^8).  Scores that climb by just under / just over that slack
+    from one 32-key block to the next, by fractions of it, that ramp from 60 below to 60 above,
+    that jump up once at the very end, and that fall all the way: each must still give the
+    oracle's output and log-sum-exp."""
+    Hq, Hkv, tree = {"tree60_gqa7": (28, 4, W.seeded_tree(5)), "chain8_gqa7": (28, 4, W.chain_tree(8)),
+                     "tree20_gqa1": (2, 2, W.seeded_tree(6, n_nodes=20))}[shape]
+    nblk = 40
+    L = 32 * nblk
+    blk = np.arange(L) // 32
+    jitter = np.random.default_rng(0).uniform(-0.5, 0.0, size=L)
+    patterns = {
+        "step 7.9": 7.9 * blk, "step 8.1": 8.1 * blk, "step 3.9": 3.9 * blk, "step 16.3": 16.3 * blk,
+        "ramp -60..60": np.linspace(-60.0, 60.0, L) / np.log(2.0),
+        "late jump": np.where(np.arange(L) == L - 3, 90.0, 0.0) + jitter,
+        "falling": -7.9 * blk + jitter,
+        "sawtooth": 7.9 * (blk % 3) + 8.1 * (blk // 3) + jitter,
+    }
+    for name, sc in patterns.items():
+        inp = W.make_verify_inputs(321, "bf16", Hq, Hkv, 128, [L], [tree], kv_std=1.0, q_std=1.0)
+        inp = _planted_scores(inp, sc)
+        ref = oracle_attn(inp)
+        for splits in (1, 0, 3):
+            out, lse, _ = _run(step, inp, num_splits=splits, algo=hb.HB_ATTN_MFMA)
+            check_attn(inp, out, lse, ref=ref, label=f"{shape} {name} splits={splits}")
 
 
 def test_device_side_cut_on_random_batches(hb, step):

@@ -20,25 +20,36 @@ def step():
     return s
 
 
-def _check(hidden, weight, ids, mx, rows=None):
+def _check(hidden, weight, ids, mx, rows=None, block=192):
     rows = np.arange(hidden.shape[0]) if rows is None else np.asarray(rows)
-    h = W.widen(hidden)[rows]
     w = W.widen(weight)
-    logits = lmhead_logits_ref(h, w)
-    order = np.argsort(-logits, axis=1, kind="stable")[:, :2]
-    top1 = order[:, 0]
-    top2 = order[:, 1] if logits.shape[1] > 1 else order[:, 0]
-    r = np.arange(len(rows))
-    margin = logits[r, top1] - logits[r, top2]
-    eps = 1e-4 * np.linalg.norm(h, axis=1) * np.sqrt((w * w).sum(1).mean())
-    got = ids.cpu().numpy()[rows]
-    clear = margin > eps
-    assert (got[clear] == top1[clear]).all(), "argmax differs where the margin is clear"
-    assert np.logical_or(got == top1, got == top2)[~clear].all()
-    if mx is not None:
-        got_mx = mx.cpu().numpy()[rows]
-        assert np.abs(got_mx - logits[r, got]).max() <= 1e-2
-    return int(clear.sum())
+    w_rms = np.sqrt((w * w).sum(1).mean())
+    got_all = ids.cpu().numpy()
+    mx_all = mx.cpu().numpy() if mx is not None else None
+    n_clear = 0
+    for i0 in range(0, len(rows), block):  # blocks of rows bound the float64 logits in memory
+        rb = rows[i0:i0 + block]
+        h = W.widen(hidden)[rb]
+        logits = lmhead_logits_ref(h, w)
+        r = np.arange(len(rb))
+        top1 = np.argmax(logits, axis=1)  # first maximum = lowest id
+        best = logits[r, top1]
+        if logits.shape[1] > 1:
+            rest = logits.copy()
+            rest[r, top1] = -np.inf
+            top2 = np.argmax(rest, axis=1)
+        else:
+            top2 = top1
+        margin = best - logits[r, top2]
+        eps = 1e-4 * np.linalg.norm(h, axis=1) * w_rms
+        got = got_all[rb]
+        clear = margin > eps
+        assert (got[clear] == top1[clear]).all(), "argmax differs where the margin is clear"
+        assert np.logical_or(got == top1, got == top2)[~clear].all()
+        if mx_all is not None:
+            assert np.abs(mx_all[rb] - logits[r, got]).max() <= 1e-2
+        n_clear += int(clear.sum())
+    return n_clear
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -116,14 +127,13 @@ def full_weight():
 
 
 @pytest.mark.parametrize("M", [960, 128])
-def test_full_vocabulary_on_sampled_rows(step, full_weight, M):
+def test_full_vocabulary_every_row(step, full_weight, M):
     """hidden 3584 x vocab 152064 (the full-step workload; M = 960 tree nodes, or 128 for the
-    8-node-chain run); the oracle recomputes a seeded sample of rows."""
+    8-node-chain run); the oracle recomputes every row over the whole vocabulary."""
     hidden, weight = full_weight
     hidden = hidden[:M].contiguous()
     ids, mx = step.lmhead_argmax(hidden.cuda(), weight.cuda())
     torch.cuda.synchronize()
-    rows = np.sort(np.random.default_rng(M).choice(M, size=12, replace=False))
-    n_clear = _check(hidden, weight, ids, mx, rows=rows)
-    assert n_clear >= 10
+    n_clear = _check(hidden, weight, ids, mx)
+    assert n_clear >= 0.9 * M
     assert (ids >= 0).all() and (ids < 152064).all()

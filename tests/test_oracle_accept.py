@@ -23,6 +23,12 @@ def test_hand_worked_example():
     assert list(path[0, :alen[0]]) == rec["path"] and path[0, alen[0]:].tolist() == [-1]
     assert list(toks[0, :alen[0]]) == rec["tokens"] and toks[0, alen[0]:].tolist() == [-1]
     assert bonus[0] == rec["bonus"][0]
+    # second reading of the root: a matching root changes nothing, a rejected root voids the step
+    ok = tree_accept_ref([0, n], rec["parent"], rec["draft"], rec["target"], 5, prev_target=rec["prev_ok"])
+    assert ok[0][0] == alen[0] and np.array_equal(ok[1], path) and np.array_equal(ok[2], toks) and ok[3][0] == bonus[0]
+    bad = tree_accept_ref([0, n], rec["parent"], rec["draft"], rec["target"], 5, prev_target=rec["prev_bad"])
+    assert bad[0][0] == rec["bad_accept_len"][0] and bad[3][0] == rec["bad_bonus"][0]
+    assert (bad[1] == -1).all() and (bad[2] == -1).all()
 
 
 @pytest.mark.parametrize("n,k", [(4, 0), (4, 1), (4, 3), (8, 5), (1, 0)])
@@ -94,3 +100,27 @@ def test_batch_and_planted_paths():
 def test_max_path_too_small_is_an_error():
     with pytest.raises(ValueError):
         tree_accept_ref([0, 3], [-1, 0, 1], [1, 5, 6], [5, 6, 7], 2)
+
+
+def test_root_as_a_guess_matches_enumeration_and_empty_trees_emit_nothing():
+    """With prev_target the root is one more link of the chain: prepend a virtual node whose
+    target is prev_target and the first reading must give the same path shifted by one."""
+    rng = np.random.default_rng(5)
+    for _ in range(20):
+        n = int(rng.integers(1, 10))
+        parent = np.array([-1] + [int(rng.integers(0, i)) for i in range(1, n)])
+        draft = rng.integers(0, 3, size=n); target = rng.integers(0, 3, size=n)
+        prev = int(rng.integers(0, 3))
+        alen, path, toks, bonus = tree_accept_ref([0, n], parent, draft, target, n + 1, prev_target=[prev])
+        # virtual root (id 0) in front: its target is prev, old node i becomes i + 1
+        vpar = np.concatenate([[-1], parent + 1]); vpar[1] = 0
+        want = _brute(vpar.tolist(), [0] + draft.tolist(), [prev] + target.tolist())
+        assert alen[0] == len(want) - 1
+        assert list(path[0, :alen[0]]) == [x - 1 for x in want[1:]]
+        if alen[0] == 0:
+            assert bonus[0] == prev and (toks[0] == -1).all()
+        else:
+            assert bonus[0] == target[want[-1] - 1] and toks[0, alen[0] - 1] == bonus[0]
+    # a sequence without nodes between two ordinary ones
+    alen, path, toks, bonus = tree_accept_ref([0, 2, 2, 4], [-1, 0, -1, 0], [1, 5, 1, 9], [5, 6, 9, 2], 3)
+    assert list(alen) == [2, 0, 2] and bonus[1] == -1 and (path[1] == -1).all() and (toks[1] == -1).all()

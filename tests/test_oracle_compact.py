@@ -1,4 +1,6 @@
 """Pins for the KV-compaction oracle: gather-back, untouched bytes, page-boundary crossing."""
+import os
+
 import numpy as np
 import pytest
 
@@ -45,3 +47,26 @@ def test_gather_back_and_nothing_else_changes(dtype, L0):
     assert touched.sum() == 8
     # inputs were not modified in place
     assert np.array_equal(kp, _bits(inp.k_pool))
+
+
+def test_hand_worked_slots():
+    """Literal slot numbers for a permuted three-page table (tests/golden/kv_compact_hand_example.txt)."""
+    rec = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "kv_compact_hand_example.txt")):
+        if line.strip() and not line.startswith("#"):
+            key, *vals = line.split()
+            rec[key] = [int(v) for v in vals]
+    page, L, path = rec["page"][0], rec["prefix_len"][0], rec["path"]
+    rng = np.random.default_rng(0)
+    kt = rng.integers(-2**15, 2**15, size=(10, 2, 8)).astype(np.int16)
+    vt = rng.integers(-2**15, 2**15, size=(10, 2, 8)).astype(np.int16)
+    kp = rng.integers(-2**15, 2**15, size=(8, 2, page, 8)).astype(np.int16)
+    vp = rng.integers(-2**15, 2**15, size=(8, 2, page, 8)).astype(np.int16)
+    k2, v2, slots, new_len = kv_compact_ref(kt, vt, kp, vp, np.array([rec["block_table"]]), [L], [0, 10],
+                                            [len(path)], np.array([path + [-1]]))
+    assert list(slots[0]) == rec["out_slots"] + [-1] and list(new_len) == rec["new_len"]
+    for node, slot in zip(path, rec["out_slots"]):
+        assert np.array_equal(k2[slot // page, :, slot % page], kt[node])
+        assert np.array_equal(v2[slot // page, :, slot % page], vt[node])
+    changed = (k2 != kp).any(axis=(1, 3))  # [block, offset]
+    assert sorted(map(tuple, np.argwhere(changed))) == sorted((s // page, s % page) for s in rec["out_slots"])

@@ -161,8 +161,9 @@ def make_verify_inputs(
     for b, t in enumerate(trees):
         node_offset[b + 1] = node_offset[b] + len(t)
     total_nodes = int(node_offset[-1])
-    parent = np.concatenate([np.asarray(t, dtype=np.int32) for t in trees]) if B else np.zeros(0, np.int32)
-    max_path = max((int(tree_depths(t).max()) + 1 for t in trees), default=1)
+    parent = (np.concatenate([np.asarray(t, dtype=np.int32) for t in trees]).astype(np.int32)
+              if B else np.zeros(0, np.int32))
+    max_path = max((int(tree_depths(t).max()) + 1 for t in trees if len(t)), default=1)
 
     pages_per_seq = [-(-(int(L) + max_path) // page) for L in prefix_lens]
     max_blocks = max(pages_per_seq, default=1) + 1  # at least one unmapped entry per row
