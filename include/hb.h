@@ -141,6 +141,23 @@ int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const v
 size_t hb_lmhead_argmax_workspace_bytes(int32_t M);
 
 /*
+ * hb_lmhead_argmax for callers that cannot allocate device memory or carry a workspace around
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments without the workspace, same kernels, same results.  The per-row keys live in a
+ * device array that belongs to the library (8 bytes per row, 128 KiB on every GPU the library
+ * runs on, held until the process ends); the call allocates and frees nothing.
+ *   M <= hb_lmhead_argmax_noalloc_max_rows() (16384), else HB_ERR_UNSUPPORTED.
+ * Every call on a GPU uses that GPU's one array (cleared by a kernel at the start of the
+ * call): calls that overlap on one GPU (different streams, or graphs replayed concurrently)
+ * race and give unspecified ids; calls ordered on one stream, or otherwise serialised, are fine.
+ * Errors otherwise as hb_lmhead_argmax (DEVICE also when the array's address cannot be found).
+ */
+int32_t hb_lmhead_argmax_noalloc(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
+                                 const void *weight, int32_t *out_ids, float *out_max, void *stream);
+
+int32_t hb_lmhead_argmax_noalloc_max_rows(void);
+
+/*
  * Greedy longest accepted path per sequence.  Node 0 is always accepted; node i > 0 matches
  * when draft_ids[i] == target_ids[parent[i]] and is accepted when it and all its ancestors
  * match.  The deepest accepted node wins (lowest id among equals).  accept_len is the number

@@ -16,6 +16,8 @@ from .binding import (
     hb_tree_verify_attn_num_splits,
     hb_lmhead_argmax,
     hb_lmhead_argmax_workspace_bytes,
+    hb_lmhead_argmax_noalloc,
+    hb_lmhead_argmax_noalloc_max_rows,
     hb_tree_accept,
     hb_kv_compact,
     HB_F32,

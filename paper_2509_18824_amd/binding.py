@@ -60,6 +60,10 @@ def _load():
     lib.hb_lmhead_argmax.argtypes = [i32, i32, i32, i32, p, p, p, p, p, sz, p]
     lib.hb_lmhead_argmax_workspace_bytes.restype = sz
     lib.hb_lmhead_argmax_workspace_bytes.argtypes = [i32]
+    lib.hb_lmhead_argmax_noalloc.restype = i32
+    lib.hb_lmhead_argmax_noalloc.argtypes = [i32, i32, i32, i32, p, p, p, p, p]
+    lib.hb_lmhead_argmax_noalloc_max_rows.restype = i32
+    lib.hb_lmhead_argmax_noalloc_max_rows.argtypes = []
     lib.hb_tree_accept.restype = i32
     lib.hb_tree_accept.argtypes = [i32, i32, p, p, p, p, p, i32, p, p, p, p, p]
     lib.hb_kv_compact.restype = i32
@@ -141,6 +145,19 @@ def hb_lmhead_argmax(hidden, weight, out_ids, out_max=None, workspace=None, stre
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.hb_lmhead_argmax(_dtype_code(hidden), M, K, V, _ptr(hidden), _ptr(weight), _ptr(out_ids),
                                 _ptr(out_max), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def hb_lmhead_argmax_noalloc_max_rows() -> int:
+    return int(lib.hb_lmhead_argmax_noalloc_max_rows())
+
+
+def hb_lmhead_argmax_noalloc(hidden, weight, out_ids, out_max=None, stream=None) -> None:
+    M, K = hidden.shape
+    V = weight.shape[0]
+    if weight.shape[1] != K or weight.dtype != hidden.dtype:
+        raise ValueError("weight must be [V, K] in the dtype of hidden")
+    _check(lib.hb_lmhead_argmax_noalloc(_dtype_code(hidden), M, K, V, _ptr(hidden), _ptr(weight), _ptr(out_ids),
+                                        _ptr(out_max), _stream(stream)))
 
 
 def hb_tree_accept(B: int, max_nodes_per_tree: int, node_offset, parent, draft_ids, target_ids,

@@ -2,7 +2,14 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 #include "hb_internal.h"
+
+// Row keys of hb_lmhead_argmax_noalloc: device memory that belongs to the library, one copy per
+// GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address kernels get is looked up once per device (scratch_on_device).
+#define HB_NOALLOC_MAX_ROWS 16384
+static __device__ __align__(256) unsigned long long scratch[HB_NOALLOC_MAX_ROWS];
 
 namespace hb {
 
@@ -18,6 +25,27 @@ int32_t fail(int32_t code, const char *fmt, ...) {
 
 int32_t fail_hip(hipError_t e, const char *what) {
   return fail(HB_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Device address of `scratch` on the current device; looked up at the first call per device.
+static hipError_t scratch_on_device(unsigned long long **out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static unsigned long long *ptrs[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    unsigned long long *p = nullptr;
+    e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return hipSuccess;
 }
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -197,9 +225,8 @@ int32_t hb_tree_verify_attn(const hb_attn_desc *desc, const void *q, const void 
 
 size_t hb_lmhead_argmax_workspace_bytes(int32_t M) { return M > 0 ? (size_t)M * 8 : 0; }
 
-int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
-                         const void *weight, int32_t *out_ids, float *out_max, void *workspace,
-                         size_t workspace_bytes, void *stream) {
+static int32_t check_lmhead_args(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
+                                 const void *weight, const int32_t *out_ids) {
   if (dtype != HB_F32 && dtype != HB_BF16)
     return fail(HB_ERR_UNSUPPORTED, "dtype %d: only HB_F32 and HB_BF16 are supported", dtype);
   if (M < 0 || K <= 0 || V <= 0) return fail(HB_ERR_INVALID_ARG, "need M >= 0, K > 0, V > 0 (got %d, %d, %d)", M, K, V);
@@ -207,13 +234,13 @@ int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const v
   if (!hidden || !weight || !out_ids) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
   if (misaligned(hidden) || misaligned(weight))
     return fail(HB_ERR_INVALID_ARG, "hidden and weight must be 16-byte aligned");
-  size_t need = hb_lmhead_argmax_workspace_bytes(M);
-  if (!workspace || workspace_bytes < need)
-    return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
-                workspace ? workspace_bytes : (size_t)0);
-  if ((uintptr_t)workspace % 8) return fail(HB_ERR_WORKSPACE, "workspace must be 8-byte aligned");
-  hipStream_t s = (hipStream_t)stream;
-  unsigned long long *keys = (unsigned long long *)workspace;
+  return HB_OK;
+}
+
+// init (every key starts at zero, by a fill kernel), GEMM + argmax into the keys, keys -> ids
+static int32_t lmhead_enqueue(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
+                              const void *weight, int32_t *out_ids, float *out_max,
+                              unsigned long long *keys, hipStream_t s) {
   HB_HIP_TRY(launch_lmhead_init(keys, M, s));
   if (lmhead_mfma_supports(dtype, M, K, V))
     HB_HIP_TRY(launch_lmhead_mfma(M, K, V, hidden, weight, keys, s));
@@ -221,6 +248,35 @@ int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const v
     HB_HIP_TRY(launch_lmhead_scalar(dtype, M, K, V, hidden, weight, keys, s));
   HB_HIP_TRY(launch_lmhead_finish(keys, M, V, out_ids, out_max, s));
   return HB_OK;
+}
+
+int32_t hb_lmhead_argmax_noalloc_max_rows(void) { return HB_NOALLOC_MAX_ROWS; }
+
+int32_t hb_lmhead_argmax_noalloc(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
+                                 const void *weight, int32_t *out_ids, float *out_max, void *stream) {
+  int32_t rc = check_lmhead_args(dtype, M, K, V, hidden, weight, out_ids);
+  if (rc || M == 0) return rc;
+  if (M > HB_NOALLOC_MAX_ROWS)
+    return fail(HB_ERR_UNSUPPORTED, "hb_lmhead_argmax_noalloc takes at most %d rows, got %d; use hb_lmhead_argmax "
+                "with a caller-provided workspace", HB_NOALLOC_MAX_ROWS, M);
+  unsigned long long *keys = nullptr;
+  HB_HIP_TRY(scratch_on_device(&keys));
+  return lmhead_enqueue(dtype, M, K, V, hidden, weight, out_ids, out_max, keys, (hipStream_t)stream);
+}
+
+int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const void *hidden,
+                         const void *weight, int32_t *out_ids, float *out_max, void *workspace,
+                         size_t workspace_bytes, void *stream) {
+  int32_t rc = check_lmhead_args(dtype, M, K, V, hidden, weight, out_ids);
+  if (rc || M == 0) return rc;
+  size_t need = hb_lmhead_argmax_workspace_bytes(M);
+  if (!workspace || workspace_bytes < need)
+    return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  if ((uintptr_t)workspace % 8) return fail(HB_ERR_WORKSPACE, "workspace must be 8-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  unsigned long long *keys = (unsigned long long *)workspace;
+  return lmhead_enqueue(dtype, M, K, V, hidden, weight, out_ids, out_max, keys, s);
 }
 
 int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,
