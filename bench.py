@@ -154,39 +154,18 @@ def bench_attention_only(cfg, steps, warmup, n_pools=4):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--tree", choices=["tree", "chain8"], default="tree")
-    ap.add_argument("--no-attn-extra", action="store_true", help="skip the attention-only runs of the "
-                    "ragged-batch and long-context workloads")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-stack", action="store_true", help="skip the 28-layer variant of the step")
-    ap.add_argument("--copy-probe", action="store_true", help="also run three 1 GiB device-to-device "
-                    "copies before the timed region: the known-size reference for scaling the "
-                    "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
-              file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
+def run_full_step(tree, steps, warmup, weight, V, K):
+    """Times `steps` full verification steps (attention of one layer, LM head with fused argmax,
+    acceptance, compaction) on the full-step workload with `tree` = "tree" (60-node trees) or
+    "chain8" (8-node chains).  Returns the measurements and what the parity check needs."""
     import torch
     import workloads as W
     import paper_2509_18824_amd as hb
     import paper_2509_18824_amd.step as S
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-
-    inp = W.make_config(4, tree=args.tree)
-    V, K = 152064, inp.Hq * inp.D
-    _, weight = W.make_lmhead_inputs(4000, 1, K, V, dtype="bf16")
+    inp = W.make_config(4, tree=tree)
     dev = S.to_device(inp)
-    wdev = weight.cuda()
+    wdev = weight if weight.is_cuda else weight.cuda()
     hint = int(inp.prefix_len.max())
     desc = S.desc_for(inp, hint=hint)
     draft = torch.zeros(inp.total_nodes, dtype=torch.int32, device="cuda")
@@ -198,19 +177,11 @@ def main():
     target = step.target_ids.cpu().numpy()
     draft_np, planted = W.plant_draft_ids(4, inp.trees(), target, V)
     step.draft_ids.copy_(torch.from_numpy(draft_np))
+    k_pool0, v_pool0 = dev.k_pool.clone(), dev.v_pool.clone()  # the cache before any compaction
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step.run()
     torch.cuda.synchronize()
-
-    if args.copy_probe:
-        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     dv = step.dev
 
     def one_step(i, ev_attn=None, ev_lm=None, ev_acc=None, ev_cmp=None):
@@ -236,27 +207,177 @@ def main():
     # bracket the LM-head call only, the dominant kernel whose duration the roofline needs: an
     # event pair costs the stream about 5 us, and eight of them per step would take 4 % off the
     # figure they are there to explain.
-    ev_lm = _events(args.steps)
+    ev_lm = _events(steps)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         one_step(i, ev_lm=ev_lm)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_step = (t1 - t0) * 1e3 / args.steps
+    ms_step = (t1 - t0) * 1e3 / steps
     ms_lm = _mean_ms(ev_lm)
     # The other calls' durations come from a second pass of the same steps, outside the timed
     # region, with events around every call.
-    ev_attn, ev_lm2, ev_acc, ev_cmp = (_events(args.steps) for _ in range(4))
-    for i in range(args.steps):
+    ev_attn, ev_lm2, ev_acc, ev_cmp = (_events(steps) for _ in range(4))
+    for i in range(steps):
         one_step(i, ev_attn, ev_lm2, ev_acc, ev_cmp)
     torch.cuda.synchronize()
     ms_attn, ms_acc, ms_cmp = map(_mean_ms, (ev_attn, ev_acc, ev_cmp))
     accept_len = step.accept_len.cpu().numpy()
     assert list(accept_len) == [d + 1 for d in planted], "accepted lengths differ from the planted paths"
+    return dict(inp=inp, desc=desc, step=step, dev=dv, wdev=wdev, draft_np=draft_np, planted=planted,
+                ms_step=ms_step, ms_lm=ms_lm, ms_attn=ms_attn, ms_acc=ms_acc, ms_cmp=ms_cmp,
+                accept_len=accept_len, k_pool0=k_pool0, v_pool0=v_pool0)
+
+
+def parity_check(run, weight):
+    """GPU outputs of the last timed step against the CPU oracle on the same inputs, every node
+    (outside the timed region): attention output of all tree nodes; LM-head ids of all rows by
+    the margin rule (the oracle's logits are computed from the GPU's own bf16 hidden states, so
+    that the comparison isolates the LM head); acceptance and compaction bit for bit."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from oracle import tree_attn_ref, lmhead_logits_ref, tree_accept_ref, kv_compact_ref
+
+    inp, step = run["inp"], run["step"]
+    ref, _ = tree_attn_ref(W.widen(inp.q), W.widen(inp.k_tree), W.widen(inp.v_tree), W.widen(run["k_pool0"]),
+                           W.widen(run["v_pool0"]), inp.block_table.numpy(), inp.prefix_len.numpy(),
+                           inp.node_offset.numpy(), inp.parent.numpy(), inp.softmax_scale)
+    got = W.widen(step.out)
+    attn_abs = float(np.abs(got - ref).max())
+    attn_rel = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+    hidden = got.reshape(inp.total_nodes, -1)
+    w = W.widen(weight)
+    w_rms = float(np.sqrt((w * w).sum(1).mean()))
+    ids = step.target_ids.cpu().numpy()
+    mism_clear = n_clear = mism_any = 0
+    for r0 in range(0, hidden.shape[0], 192):
+        h = hidden[r0:r0 + 192]
+        logits = lmhead_logits_ref(h, w)
+        r = np.arange(h.shape[0])
+        top1 = np.argmax(logits, axis=1)
+        best = logits[r, top1]
+        logits[r, top1] = -np.inf
+        top2 = np.argmax(logits, axis=1)
+        margin = best - logits[r, top2]
+        clear = margin > 1e-4 * np.linalg.norm(h, axis=1) * w_rms
+        g = ids[r0:r0 + 192]
+        mism_clear += int((g[clear] != top1[clear]).sum())
+        mism_any += int(((g != top1) & (g != top2)).sum())
+        n_clear += int(clear.sum())
+    off = inp.node_offset.numpy()
+    alen, apath, otoks, bonus = tree_accept_ref(off, inp.parent.numpy(), run["draft_np"], ids, inp.max_path)
+    accept_exact = bool(np.array_equal(step.accept_len.cpu().numpy(), alen)
+                        and np.array_equal(step.accept_path.cpu().numpy(), apath)
+                        and np.array_equal(step.out_tokens.cpu().numpy(), otoks)
+                        and np.array_equal(step.bonus.cpu().numpy(), bonus))
+    bits = lambda t: t.detach().cpu().view(torch.int16).numpy()
+    rk, rv, rslots, rlen = kv_compact_ref(bits(inp.k_tree), bits(inp.v_tree), bits(run["k_pool0"]), bits(run["v_pool0"]),
+                                          inp.block_table.numpy(), inp.prefix_len.numpy(), off, alen, apath)
+    compact_exact = bool(np.array_equal(bits(run["dev"].k_pool), rk) and np.array_equal(bits(run["dev"].v_pool), rv)
+                         and np.array_equal(step.out_slots.cpu().numpy(), rslots)
+                         and np.array_equal(step.new_len.cpu().numpy(), rlen))
+    return {"nodes": int(inp.total_nodes), "attn_max_abs": attn_abs, "attn_rel_l2": attn_rel,
+            "attn_tolerance": {"max_abs": 2e-2, "rel_l2": 1e-2},
+            "argmax_rows_clear": n_clear, "argmax_mismatch_clear": mism_clear,
+            "argmax_outside_top2": mism_any, "accept_exact": accept_exact, "compact_exact": compact_exact,
+            "ok": bool(attn_abs <= 2e-2 and attn_rel <= 1e-2 and mism_clear == 0 and mism_any == 0
+                       and accept_exact and compact_exact)}
+
+
+def achievable_peaks():
+    """What this machine delivers on plain library kernels, measured in this run: a 1 GiB device copy
+    and a 1 GiB read (HBM), and bf16 GEMMs by the vendor library through torch.matmul (a square
+    one and one of the LM head's shape, logits written out)."""
+    import torch
+    out = {}
+    src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")  # 1 GiB
+    dst = torch.empty_like(src)
+
+    def timed(fn, n=5):
+        fn(); torch.cuda.synchronize()
+        ev = _events(n)
+        for a, b in ev:
+            a.record(); fn(); b.record()
+        torch.cuda.synchronize()
+        return min(a.elapsed_time(b) for a, b in ev)
+    ms = timed(lambda: dst.copy_(src))
+    out["hbm_copy_GBps"] = 2 * src.numel() * 2 / (ms * 1e-3) / 1e9  # bytes read + bytes written
+    ms = timed(lambda: torch.max(src.view(torch.int16)))
+    out["hbm_read_GBps"] = src.numel() * 2 / (ms * 1e-3) / 1e9
+    del src, dst
+    a = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    ms = timed(lambda: torch.matmul(a, b))
+    out["bf16_gemm_8192_TFLOPs"] = 2 * 8192.0 ** 3 / (ms * 1e-3) / 1e12
+    del a, b
+    h = torch.randn(960, 3584, device="cuda", dtype=torch.bfloat16)
+    w = (torch.randn(152064, 3584, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    ms = timed(lambda: torch.matmul(h, w.t()))
+    out["bf16_gemm_lmhead_shape_TFLOPs"] = 2.0 * 960 * 3584 * 152064 / (ms * 1e-3) / 1e12
+    out["bf16_gemm_lmhead_shape_ms"] = ms
+    del h, w
+    torch.cuda.empty_cache()
+    out["note"] = "library kernels through torch on this box in this run; fractions of the published peaks: " \
+                  f"copy {out['hbm_copy_GBps'] / PEAK_HBM_GBS:.2f}, read {out['hbm_read_GBps'] / PEAK_HBM_GBS:.2f}, " \
+                  f"GEMM {out['bf16_gemm_8192_TFLOPs'] / PEAK_BF16_TFLOPS:.2f}"
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--tree", choices=["tree", "chain8"], default="tree",
+                    help="the draft of the headline run (the default run reports the other one as a block)")
+    ap.add_argument("--no-attn-extra", action="store_true", help="skip the attention-only runs of the "
+                    "ragged-batch and long-context workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stack", action="store_true", help="skip the 28-layer variant of the step")
+    ap.add_argument("--no-chain", action="store_true", help="skip the 8-node-chain run of the step")
+    ap.add_argument("--no-achievable", action="store_true", help="skip the library-kernel yardsticks")
+    ap.add_argument("--no-parity", action="store_true", help="skip the comparison with the CPU oracle")
+    ap.add_argument("--copy-probe", action="store_true", help="also run three 1 GiB device-to-device "
+                    "copies before the timed region: the known-size reference for scaling the "
+                    "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2509_18824_amd as hb
+    import paper_2509_18824_amd.step as S
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    V, K = 152064, 28 * 128
+    _, weight = W.make_lmhead_inputs(4000, 1, K, V, dtype="bf16")
+    wdev = weight.cuda()
+
+    if args.copy_probe:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    run = run_full_step(args.tree, args.steps, args.warmup, wdev, V, K)
+    inp, desc, step, dv = run["inp"], run["desc"], run["step"], run["dev"]
+    ms_step, ms_lm, ms_attn, ms_acc, ms_cmp = (run[k] for k in ("ms_step", "ms_lm", "ms_attn", "ms_acc", "ms_cmp"))
+    accept_len = run["accept_len"]
 
     M = inp.total_nodes
     lm_flops = 2.0 * M * K * V
     lm_tflops = lm_flops / (ms_lm * 1e-3) / 1e12
+    lm_bytes = V * K * 2 + M * K * 2
     kv_bytes = inp.kv_bytes()
     result = {
         "metric": "verified tree-tokens/sec per verify step",
@@ -283,11 +404,10 @@ def main():
         "roofline": {
             "kernel": "lmhead_argmax",
             "bound": "mfma" if M >= 512 else "hbm",
-            "achieved": lm_tflops if M >= 512 else (V * K * 2 + M * K * 2) / (ms_lm * 1e-3) / 1e9,
+            "achieved": lm_tflops if M >= 512 else lm_bytes / (ms_lm * 1e-3) / 1e9,
             "peak": PEAK_BF16_TFLOPS if M >= 512 else PEAK_HBM_GBS,
             "unit": "TFLOP/s" if M >= 512 else "GB/s",
-            "frac": (lm_tflops / PEAK_BF16_TFLOPS) if M >= 512
-            else (V * K * 2 + M * K * 2) / (ms_lm * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "frac": (lm_tflops / PEAK_BF16_TFLOPS) if M >= 512 else lm_bytes / (ms_lm * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "traffic": (_lmhead_traffic() or {}).get("bytes") if args.tree == "tree" else None,
             "traffic_detail": _lmhead_traffic() if args.tree == "tree" else None,
             "ms": ms_lm,
@@ -300,6 +420,9 @@ def main():
             "attn_splits": hb.hb_tree_verify_attn_num_splits(desc),
         },
     }
+    if not args.no_parity:
+        result["parity"] = parity_check(run, weight)
+    draft_np = run["draft_np"]
     if not args.no_stack:
         # The same step with a realistic depth: 28 attention layers over 28 distinct KV pools (2.3 GB,
         # so every layer streams its KV from HBM), one LM head, one acceptance, 28 compactions.
@@ -341,13 +464,46 @@ def main():
             "kv_GBps": kv_bytes / (ms_attn_layer * 1e-3) / 1e9,
         }
         del pools
+    other = "chain8" if args.tree == "tree" else "tree"
+    if not args.no_chain:
+        # The same step with the other draft shape (the paper measures chain drafts: Section 1,
+        # Section 4.2): 8-node chains make 128 rows, where both the attention and the LM head are
+        # bound by HBM, not by the matrix cores.
+        del step, run
+        torch.cuda.empty_cache()
+        r2 = run_full_step(other, args.steps, args.warmup, wdev, V, K)
+        M2 = r2["inp"].total_nodes
+        kv2 = r2["inp"].kv_bytes()
+        lm_gbps = lm_bytes_for(M2, K, V) / (r2["ms_lm"] * 1e-3) / 1e9
+        result[other] = {
+            "tree_nodes": M2, "ms_per_step": r2["ms_step"], "tree_tokens_per_s": M2 / (r2["ms_step"] * 1e-3),
+            "mean_accept_len": float(r2["accept_len"].mean()),
+            "kernels_ms": {"tree_verify_attn": r2["ms_attn"], "lmhead_argmax": r2["ms_lm"],
+                           "tree_accept": r2["ms_acc"], "kv_compact": r2["ms_cmp"]},
+            "lmhead_bound": "hbm" if M2 < 512 else "mfma",
+            "lmhead_GBps": lm_gbps, "lmhead_frac_of_hbm_peak": lm_gbps / PEAK_HBM_GBS,
+            "lmhead_TFLOPs": 2.0 * M2 * K * V / (r2["ms_lm"] * 1e-3) / 1e12,
+            "kv_bytes": kv2, "kv_GBps": kv2 / (r2["ms_attn"] * 1e-3) / 1e9,
+            "kv_frac_of_hbm_peak": kv2 / (r2["ms_attn"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        }
+        if not args.no_parity:
+            result[other]["parity"] = parity_check(r2, weight)
+        del r2
     if not args.no_attn_extra and args.tree == "tree":
-        del step, wdev
+        step = run = None
+        del wdev
         torch.cuda.empty_cache()
         result["attention_only"] = [bench_attention_only(c, max(args.steps, 20), args.warmup) for c in (2, 3)]
+    if not args.no_achievable:
+        torch.cuda.empty_cache()
+        result["achievable"] = achievable_peaks()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, weight, draft_np)
     print(json.dumps(result))
+
+
+def lm_bytes_for(M, K, V):
+    return V * K * 2 + M * K * 2
 
 
 if __name__ == "__main__":

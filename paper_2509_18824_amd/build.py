@@ -64,5 +64,34 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     return LIB
 
 
+def build_host_sanitizer_check(driver_c: str) -> str:
+    """Builds a host program from `driver_c` and the library's objects, with the host code of
+    csrc/hb_api.hip (validation, planning, error text) compiled under AddressSanitizer and
+    UndefinedBehaviorSanitizer (device code is not instrumented).  Returns the executable."""
+    out_dir = os.path.join(BUILD, "san")
+    os.makedirs(out_dir, exist_ok=True)
+    others = [os.path.join(BUILD, s.replace(".hip", ".o")) for s in sources() if s != "hb_api.hip"]
+    if not all(os.path.exists(o) for o in others):
+        build()
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-omit-frame-pointer"]
+    api_o = os.path.join(out_dir, "hb_api.o")
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g"]
+    host_san = [x for f in san for x in ("-Xarch_host", f)]
+    drv_o = os.path.join(out_dir, "driver.o")
+    exe = os.path.join(out_dir, "host_sanitize_check")
+    clang = os.path.join(os.path.dirname(os.path.realpath(HIPCC)), "..", "lib", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/lib/llvm/bin/clang"
+    for cmd in (
+        [HIPCC, *flags, *host_san, "-c", os.path.join(CSRC, "hb_api.hip"), "-o", api_o],
+        [clang, *san, "-g", "-I", os.path.join(ROOT, "include"), "-c", driver_c, "-o", drv_o],
+        [HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", *san, "-fno-gpu-sanitize", drv_o, api_o, *others, "-o", exe],
+    ):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"sanitizer build failed: {' '.join(cmd)}\n{r.stderr}")
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))

@@ -1,0 +1,105 @@
+/* Host-side checks of the C ABI's argument validation, planning and error text, built with
+ * AddressSanitizer and UndefinedBehaviorSanitizer on the host code of the library (see
+ * tests/test_host_sanitizers.py).  No call here reaches a kernel launch: every one fails, or
+ * succeeds as a no-op, on host-visible arguments alone, so it runs without a GPU. */
+#include <stdio.h>
+#include <string.h>
+#include "hb.h"
+
+#define CHECK(cond)                                                        \
+  do {                                                                     \
+    if (!(cond)) {                                                         \
+      printf("FAILED line %d: %s (last error: %s)\n", __LINE__, #cond, hb_last_error()); \
+      return 1;                                                            \
+    }                                                                      \
+  } while (0)
+
+static hb_attn_desc base_desc(void) {
+  hb_attn_desc d;
+  memset(&d, 0, sizeof d);
+  d.dtype = HB_BF16; d.batch = 2; d.num_q_heads = 28; d.num_kv_heads = 4; d.head_dim = 128;
+  d.page_size = 16; d.max_blocks_per_seq = 64; d.num_blocks = 200; d.total_nodes = 120;
+  d.max_nodes_per_tree = 60; d.softmax_scale = 0.1f;
+  return d;
+}
+
+int main(void) {
+  static int32_t buf[4096] __attribute__((aligned(256)));
+  void *p = buf;
+  CHECK(hb_version() >= 1);
+
+  int32_t par[65];
+  par[0] = -1;
+  for (int i = 1; i < 65; ++i) par[i] = i - 1;
+  CHECK(hb_tree_validate_host(par, 64) == HB_OK);
+  CHECK(hb_tree_validate_host(par, 65) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_tree_validate_host(par, 0) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_tree_validate_host(NULL, 4) == HB_ERR_INVALID_ARG);
+  par[3] = 3;
+  CHECK(hb_tree_validate_host(par, 8) == HB_ERR_INVALID_ARG);
+  CHECK(strstr(hb_last_error(), "parent[3]") != NULL);
+
+  /* planning over a range of shapes: sizes must be consistent and never overflow */
+  for (int batch = 1; batch <= 130; batch += 43)
+    for (int nodes = 1; nodes <= 64; nodes += 21)
+      for (int blocks = 1; blocks <= 4096; blocks *= 8)
+        for (int dtype = 0; dtype < 2; ++dtype)
+          for (int splits = 0; splits <= 7; splits += 7)
+            for (int algo = 0; algo <= 2; ++algo) {
+              hb_attn_desc d = base_desc();
+              d.batch = batch; d.max_nodes_per_tree = nodes; d.total_nodes = batch * nodes;
+              d.max_blocks_per_seq = blocks; d.num_blocks = blocks * batch + 4; d.dtype = dtype;
+              d.num_splits = splits; d.algo = algo; d.max_prefix_len_hint = blocks > 8 ? blocks * 8 : 0;
+              size_t ws = hb_tree_verify_attn_workspace_bytes(&d);
+              int32_t ns = hb_tree_verify_attn_num_splits(&d);
+              if (algo == HB_ATTN_MFMA && dtype == HB_F32) { CHECK(ns == 0 && ws == 0); continue; }
+              CHECK(ns >= 1 && ns <= 4096);
+              CHECK((ns == 1) == (ws == 0));
+              if (ns > 1) CHECK(ws >= (size_t)d.total_nodes * d.num_q_heads * ns * (d.head_dim + 2) * 4);
+            }
+
+  hb_attn_desc d = base_desc();
+  d.num_q_heads = 30;
+  CHECK(hb_tree_verify_attn(&d, p, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_INVALID_ARG);
+  d = base_desc(); d.head_dim = 100;
+  CHECK(hb_tree_verify_attn(&d, p, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_UNSUPPORTED);
+  d = base_desc(); d.max_nodes_per_tree = 65;
+  CHECK(hb_tree_verify_attn(&d, p, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_UNSUPPORTED);
+  d = base_desc(); d.dtype = 7;
+  CHECK(hb_tree_verify_attn(&d, p, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_UNSUPPORTED);
+  d = base_desc(); d.algo = 9;
+  CHECK(hb_tree_verify_attn(&d, p, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_INVALID_ARG);
+  d = base_desc();
+  CHECK(hb_tree_verify_attn(&d, NULL, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_tree_verify_attn(&d, (char *)p + 4, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_tree_verify_attn(&d, p, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_WORKSPACE);
+  CHECK(hb_tree_verify_attn(&d, p, p, p, p, p, p, p, p, p, p, NULL, (char *)p + 8, (size_t)1 << 40, NULL) == HB_ERR_WORKSPACE);
+  CHECK(hb_tree_verify_attn(NULL, p, p, p, p, p, p, p, p, p, p, NULL, NULL, 0, NULL) == HB_ERR_INVALID_ARG);
+  d = base_desc(); d.batch = 0; d.total_nodes = 0;
+  CHECK(hb_tree_verify_attn(&d, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) == HB_OK);
+
+  CHECK(hb_lmhead_argmax(HB_BF16, 0, 64, 100, NULL, NULL, NULL, NULL, NULL, 0, NULL) == HB_OK);
+  CHECK(hb_lmhead_argmax(HB_BF16, 5, 0, 100, p, p, p, NULL, p, 64, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_lmhead_argmax(3, 5, 64, 100, p, p, p, NULL, p, 64, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_lmhead_argmax(HB_BF16, 5, 64, 100, p, NULL, p, NULL, p, 64, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_lmhead_argmax(HB_BF16, 5, 64, 100, p, p, p, NULL, p, 8, NULL) == HB_ERR_WORKSPACE);
+  CHECK(hb_lmhead_argmax(HB_BF16, 5, 64, 100, p, p, p, NULL, (char *)p + 4, 64, NULL) == HB_ERR_WORKSPACE);
+  CHECK(hb_lmhead_argmax_workspace_bytes(960) == 960 * 8 && hb_lmhead_argmax_workspace_bytes(-3) == 0);
+  CHECK(hb_lmhead_argmax_noalloc(HB_BF16, hb_lmhead_argmax_noalloc_max_rows() + 1, 64, 100, p, p, p, NULL, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_lmhead_argmax_noalloc(HB_BF16, 0, 64, 100, NULL, NULL, NULL, NULL, NULL) == HB_OK);
+  CHECK(hb_lmhead_argmax_noalloc(HB_BF16, 5, 64, 100, NULL, p, p, NULL, NULL) == HB_ERR_INVALID_ARG);
+
+  CHECK(hb_tree_accept(2, 65, p, p, p, p, NULL, 6, p, p, p, p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_tree_accept(2, 60, p, p, p, p, NULL, 0, p, p, p, p, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_tree_accept(2, 60, NULL, p, p, p, p, 6, p, p, p, p, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_tree_accept(0, 60, NULL, NULL, NULL, NULL, NULL, 6, NULL, NULL, NULL, NULL, NULL) == HB_OK);
+
+  d = base_desc();
+  CHECK(hb_kv_compact(&d, p, p, p, p, p, p, p, p, p, 0, NULL, NULL, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_kv_compact(&d, p, p, NULL, p, p, p, p, p, p, 6, NULL, NULL, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_kv_compact(&d, (char *)p + 2, p, p, p, p, p, p, p, p, 6, NULL, NULL, NULL) == HB_ERR_INVALID_ARG);
+  d.batch = 0;
+  CHECK(hb_kv_compact(&d, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 6, NULL, NULL, NULL) == HB_OK);
+  printf("host shim checks passed\n");
+  return 0;
+}
