@@ -14,6 +14,7 @@ target's own greedy stream):
   lm_head.lmhead_argmax_ref        per-node target token = argmax of the LM-head logits
   acceptance.tree_accept_ref       greedy longest accepted root-to-node path, bonus token
   kv_compaction.kv_compact_ref     append the accepted nodes' K/V to the paged cache
+  stochastic_acceptance.tree_accept_sample_ref   sampling acceptance (speculative sampling over a tree)
   toy_decoder.ToyDecoderRef        small random-weight decoder: greedy autoregressive stream and
                                    greedy speculative decoding built from the four functions above
 
@@ -28,6 +29,7 @@ from .lm_head import lmhead_logits_ref, lmhead_argmax_ref
 from .acceptance import tree_accept_ref
 from .kv_compaction import kv_compact_ref
 from .toy_decoder import ToyDecoderRef
+from .stochastic_acceptance import tree_accept_sample_ref
 
 __all__ = [
     "tree_attn_ref",
@@ -37,4 +39,5 @@ __all__ = [
     "tree_accept_ref",
     "kv_compact_ref",
     "ToyDecoderRef",
+    "tree_accept_sample_ref",
 ]
