@@ -184,6 +184,41 @@ int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *nod
                        int32_t *accept_path, int32_t *out_tokens, int32_t *bonus_id, void *stream);
 
 /*
+ * Sampling acceptance (lossless under sampling: the emitted tokens are distributed as the
+ * target's own samples; the paper, Section 1 and Section 4.1 "Setup", states the lossless
+ * validation and defers the procedure to EAGLE-3).  The rule is speculative sampling with several
+ * candidates per position: the children of the current node are tried in index order, child with
+ * token x is accepted with probability min(1, p(x)/q(x)), p / q = the target's / the draft's
+ * distribution of the token after the current node; a rejection replaces p by the renormalised
+ * residual max(p - q, 0) and removes x from q (candidates are drawn without replacement).  When
+ * no child is accepted, or the node has none, or the path holds max_path nodes, the step's last
+ * token is drawn from the current p.  Node 0 is always on the path.  Outputs as hb_tree_accept.
+ *
+ * Every decision is taken in exact integers, reproducible bit for bit: fix(p) = floor(p * 2^30),
+ * S = sum over the vocabulary,
+ *   accept        iff  u * q_x * S(p) < 2^32 * p_x * S(q)
+ *   residual      r_v = max(p_v * S(q) - q_v * S(p), 0),  p_v <- r_v / max(S(r) >> 30, 1)
+ *                 (integer division; p unchanged when S(r) = 0),  q_x <- 0
+ *   last token    the smallest v with p_0 + .. + p_v > (u_bonus * S(p)) >> 32  (-1 when S(p) = 0)
+ *
+ *   p_target, q_draft  device float32 [total_nodes, V]: distributions AFTER each node (entries in
+ *                      [0, 1], each row summing to at most about 1: larger sums overflow the
+ *                      integer products and give unspecified, though memory-safe, results)
+ *   u_accept   device uint32 [total_nodes]: the uniform used when that node is tried as a child
+ *   u_bonus    device uint32 [B]: the uniform of the step's last token
+ *   workspace  device, hb_tree_accept_sample_workspace_bytes(B, V) bytes, 4-byte aligned
+ * Errors: INVALID_ARG, UNSUPPORTED (max_nodes_per_tree > 64), WORKSPACE, DEVICE.  B == 0: no-op.
+ */
+int32_t hb_tree_accept_sample(int32_t B, int32_t max_nodes_per_tree, int32_t V, const int32_t *node_offset,
+                              const int32_t *parent, const int32_t *draft_ids, const float *p_target,
+                              const float *q_draft, const uint32_t *u_accept, const uint32_t *u_bonus,
+                              int32_t max_path, int32_t *accept_len, int32_t *accept_path,
+                              int32_t *out_tokens, int32_t *bonus_id, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+size_t hb_tree_accept_sample_workspace_bytes(int32_t B, int32_t V);
+
+/*
  * Append the accepted path's K/V to the paged cache of one layer (Section 4.1: committed
  * context lives in the KV cache).  For j < accept_len[b]: position p = prefix_len[b] + j,
  * slot = block_table[b][p / page] * page + p % page; the K and V rows (all kv heads) of tree

@@ -19,6 +19,8 @@ from .binding import (
     hb_lmhead_argmax_noalloc,
     hb_lmhead_argmax_noalloc_max_rows,
     hb_tree_accept,
+    hb_tree_accept_sample,
+    hb_tree_accept_sample_workspace_bytes,
     hb_kv_compact,
     HB_F32,
     HB_BF16,

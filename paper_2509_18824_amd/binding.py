@@ -66,6 +66,10 @@ def _load():
     lib.hb_lmhead_argmax_noalloc_max_rows.argtypes = []
     lib.hb_tree_accept.restype = i32
     lib.hb_tree_accept.argtypes = [i32, i32, p, p, p, p, p, i32, p, p, p, p, p]
+    lib.hb_tree_accept_sample.restype = i32
+    lib.hb_tree_accept_sample.argtypes = [i32, i32, i32] + [p] * 7 + [i32] + [p] * 4 + [p, sz, p]
+    lib.hb_tree_accept_sample_workspace_bytes.restype = sz
+    lib.hb_tree_accept_sample_workspace_bytes.argtypes = [i32, i32]
     lib.hb_kv_compact.restype = i32
     lib.hb_kv_compact.argtypes = [C.POINTER(AttnDesc)] + [p] * 9 + [i32, p, p, p]
     return lib
@@ -166,6 +170,23 @@ def hb_tree_accept(B: int, max_nodes_per_tree: int, node_offset, parent, draft_i
     _check(lib.hb_tree_accept(B, max_nodes_per_tree, _ptr(node_offset), _ptr(parent), _ptr(draft_ids),
                               _ptr(target_ids), _ptr(prev_target), max_path, _ptr(accept_len), _ptr(accept_path),
                               _ptr(out_tokens), _ptr(bonus_id), _stream(stream)))
+
+
+def hb_tree_accept_sample_workspace_bytes(B: int, V: int) -> int:
+    return int(lib.hb_tree_accept_sample_workspace_bytes(B, V))
+
+
+def hb_tree_accept_sample(B: int, max_nodes_per_tree: int, node_offset, parent, draft_ids, p_target, q_draft,
+                          u_accept, u_bonus, max_path: int, accept_len, accept_path, out_tokens, bonus_id,
+                          workspace, stream=None) -> None:
+    V = p_target.shape[1]
+    if p_target.dtype != torch.float32 or q_draft.dtype != torch.float32 or q_draft.shape != p_target.shape:
+        raise ValueError("p_target and q_draft must be float32 [total_nodes, V]")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_tree_accept_sample(B, max_nodes_per_tree, V, _ptr(node_offset), _ptr(parent), _ptr(draft_ids),
+                                     _ptr(p_target), _ptr(q_draft), _ptr(u_accept), _ptr(u_bonus), max_path,
+                                     _ptr(accept_len), _ptr(accept_path), _ptr(out_tokens), _ptr(bonus_id),
+                                     _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def hb_kv_compact(desc: AttnDesc, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset,

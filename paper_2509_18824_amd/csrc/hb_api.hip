@@ -298,6 +298,36 @@ int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *nod
   return HB_OK;
 }
 
+size_t hb_tree_accept_sample_workspace_bytes(int32_t B, int32_t V) {
+  return (B > 0 && V > 0) ? (size_t)B * (size_t)V * sizeof(uint32_t) : 0;
+}
+
+int32_t hb_tree_accept_sample(int32_t B, int32_t max_nodes_per_tree, int32_t V, const int32_t *node_offset,
+                              const int32_t *parent, const int32_t *draft_ids, const float *p_target,
+                              const float *q_draft, const uint32_t *u_accept, const uint32_t *u_bonus,
+                              int32_t max_path, int32_t *accept_len, int32_t *accept_path,
+                              int32_t *out_tokens, int32_t *bonus_id, void *workspace,
+                              size_t workspace_bytes, void *stream) {
+  if (B < 0 || max_path <= 0 || max_nodes_per_tree <= 0 || V <= 0)
+    return fail(HB_ERR_INVALID_ARG, "need B >= 0, max_path > 0, max_nodes_per_tree > 0, V > 0");
+  if (max_nodes_per_tree > 64)
+    return fail(HB_ERR_UNSUPPORTED, "max_nodes_per_tree %d: trees of more than 64 nodes are not supported",
+                max_nodes_per_tree);
+  if (B == 0) return HB_OK;
+  if (!node_offset || !parent || !draft_ids || !p_target || !q_draft || !u_accept || !u_bonus || !accept_len ||
+      !accept_path || !out_tokens || !bonus_id)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  const size_t need = hb_tree_accept_sample_workspace_bytes(B, V);
+  if (!workspace || workspace_bytes < need)
+    return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  if ((uintptr_t)workspace % 4) return fail(HB_ERR_WORKSPACE, "workspace must be 4-byte aligned");
+  HB_HIP_TRY(launch_tree_accept_sample(B, max_nodes_per_tree, V, node_offset, parent, draft_ids, p_target, q_draft,
+                                       u_accept, u_bonus, max_path, accept_len, accept_path, out_tokens, bonus_id,
+                                       (uint32_t *)workspace, (hipStream_t)stream));
+  return HB_OK;
+}
+
 int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *v_tree,
                       void *k_pool, void *v_pool, const int32_t *block_table,
                       const int32_t *prefix_len, const int32_t *node_offset,

@@ -92,6 +92,11 @@ hipError_t launch_tree_accept(int32_t B, int32_t max_nodes, const int32_t *node_
                               const int32_t *target_ids, const int32_t *prev_target, int32_t max_path,
                               int32_t *accept_len, int32_t *accept_path, int32_t *out_tokens,
                               int32_t *bonus_id, hipStream_t s);
+hipError_t launch_tree_accept_sample(int32_t B, int32_t max_nodes, int32_t V, const int32_t *node_offset,
+                                     const int32_t *parent, const int32_t *draft_ids, const float *p_target,
+                                     const float *q_draft, const uint32_t *u_accept, const uint32_t *u_bonus,
+                                     int32_t max_path, int32_t *accept_len, int32_t *accept_path,
+                                     int32_t *out_tokens, int32_t *bonus_id, uint32_t *work, hipStream_t s);
 hipError_t launch_kv_compact(const hb_attn_desc &d, const void *k_tree, const void *v_tree,
                              void *k_pool, void *v_pool, const int32_t *block_table,
                              const int32_t *prefix_len, const int32_t *node_offset,

@@ -90,6 +90,20 @@ def tree_accept(node_offset, parent, draft_ids, target_ids, max_path, max_nodes,
     return accept_len, accept_path, out_tokens, bonus
 
 
+def tree_accept_sample(node_offset, parent, draft_ids, p_target, q_draft, u_accept, u_bonus, max_path, max_nodes):
+    """u_accept / u_bonus: int32 tensors holding the bit patterns of the 32-bit uniforms."""
+    B = node_offset.numel() - 1
+    dev = node_offset.device
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    accept_path = torch.empty((B, max_path), dtype=torch.int32, device=dev)
+    out_tokens = torch.empty((B, max_path), dtype=torch.int32, device=dev)
+    bonus = torch.empty(B, dtype=torch.int32, device=dev)
+    ws = alloc_workspace(max(4, hb.hb_tree_accept_sample_workspace_bytes(B, p_target.shape[1])), dev)
+    hb.hb_tree_accept_sample(B, max_nodes, node_offset, parent, draft_ids, p_target, q_draft, u_accept, u_bonus,
+                             max_path, accept_len, accept_path, out_tokens, bonus, ws)
+    return accept_len, accept_path, out_tokens, bonus
+
+
 def kv_compact(desc, dev: DeviceInputs, accept_len, accept_path):
     B, max_path = accept_path.shape
     out_slots = torch.empty((B, max_path), dtype=torch.int32, device=accept_path.device)
