@@ -15,6 +15,7 @@ target's own greedy stream):
   acceptance.tree_accept_ref       greedy longest accepted root-to-node path, bonus token
   kv_compaction.kv_compact_ref     append the accepted nodes' K/V to the paged cache
   stochastic_acceptance.tree_accept_sample_ref   sampling acceptance (speculative sampling over a tree)
+  projections.qkv_rope_project_ref / linear_ref / tree_positions_ref   the projections around the attention
   toy_decoder.ToyDecoderRef        small random-weight decoder: greedy autoregressive stream and
                                    greedy speculative decoding built from the four functions above
 
@@ -30,6 +31,7 @@ from .acceptance import tree_accept_ref
 from .kv_compaction import kv_compact_ref
 from .toy_decoder import ToyDecoderRef
 from .stochastic_acceptance import tree_accept_sample_ref
+from .projections import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref
 
 __all__ = [
     "tree_attn_ref",
@@ -40,4 +42,8 @@ __all__ = [
     "kv_compact_ref",
     "ToyDecoderRef",
     "tree_accept_sample_ref",
+    "tree_positions_ref",
+    "rope_ref",
+    "qkv_rope_project_ref",
+    "linear_ref",
 ]
