@@ -158,6 +158,39 @@ int32_t hb_lmhead_argmax_noalloc(int32_t dtype, int32_t M, int32_t K, int32_t V,
 int32_t hb_lmhead_argmax_noalloc_max_rows(void);
 
 /*
+ * The target's projections around the attention of one decoder layer (the validation pass of
+ * Section 1 runs the whole target model over the drafted tokens; the paper gives no model
+ * dimensions, the shapes are those of the workloads here).  bf16 storage, fp32 accumulation.
+ *
+ * hb_tree_positions: positions[n] = prefix_len[b] + depth of node n in its tree: the position the
+ * drafted token would have in sequential decoding.
+ *   node_offset device int32 [B+1], parent device int32 [total], prefix_len device int32 [B],
+ *   positions device int32 [total] (out).  Trees of at most 64 nodes.
+ * hb_rope_table: cos_out[t, d] = cos(positions[t] * theta^(-d / half)), sin_out likewise,
+ *   d < half = head_dim / 2; device float32 [T, half], computed in double precision.
+ * hb_qkv_rope_project: y = hidden W^T (+ bias); rows of W are the Hq query heads, then the Hkv key
+ *   heads, then the Hkv value heads, 128 features each; queries and keys get the rotary embedding
+ *   (rotate-half convention: feature d < 64 of a head is paired with d + 64 and the pair rotated
+ *   by the angle of the token's row of the table); results go to q [T, Hq, 128], k [T, Hkv, 128],
+ *   v [T, Hkv, 128], the layouts hb_tree_verify_attn takes.
+ *   hidden device bf16 [T, K]; w_qkv device bf16 [(Hq + 2 Hkv) * 128, K]; bias device bf16
+ *   [(Hq + 2 Hkv) * 128] or NULL; cos, sin device float32 [T, 64].  K % 64 == 0, head_dim 128.
+ * hb_out_project: out = x W^T (+ residual): x device bf16 [T, K], w device bf16 [N, K], residual
+ *   device bf16 [T, N] or NULL, out device bf16 [T, N]; K % 64 == 0, N % 4 == 0.
+ * All tensors 16-byte aligned.  Errors: INVALID_ARG, UNSUPPORTED (shape), DEVICE.  T == 0: no-op.
+ */
+int32_t hb_tree_positions(int32_t B, int32_t max_nodes_per_tree, int32_t total_nodes,
+                          const int32_t *node_offset, const int32_t *parent, const int32_t *prefix_len,
+                          int32_t *positions, void *stream);
+int32_t hb_rope_table(int32_t T, int32_t head_dim, double theta, const int32_t *positions, float *cos_out,
+                      float *sin_out, void *stream);
+int32_t hb_qkv_rope_project(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32_t head_dim, const void *hidden,
+                            const void *w_qkv, const void *bias_or_null, const float *cos, const float *sin,
+                            void *q, void *k, void *v, void *stream);
+int32_t hb_out_project(int32_t T, int32_t K, int32_t N, const void *x, const void *w,
+                       const void *residual_or_null, void *out, void *stream);
+
+/*
  * Greedy longest accepted path per sequence.  Node 0 is always accepted; node i > 0 matches
  * when draft_ids[i] == target_ids[parent[i]] and is accepted when it and all its ancestors
  * match.  The deepest accepted node wins (lowest id among equals).  accept_len is the number

@@ -18,6 +18,10 @@ from .binding import (
     hb_lmhead_argmax_workspace_bytes,
     hb_lmhead_argmax_noalloc,
     hb_lmhead_argmax_noalloc_max_rows,
+    hb_tree_positions,
+    hb_rope_table,
+    hb_qkv_rope_project,
+    hb_out_project,
     hb_tree_accept,
     hb_tree_accept_sample,
     hb_tree_accept_sample_workspace_bytes,

@@ -64,6 +64,14 @@ def _load():
     lib.hb_lmhead_argmax_noalloc.argtypes = [i32, i32, i32, i32, p, p, p, p, p]
     lib.hb_lmhead_argmax_noalloc_max_rows.restype = i32
     lib.hb_lmhead_argmax_noalloc_max_rows.argtypes = []
+    lib.hb_tree_positions.restype = i32
+    lib.hb_tree_positions.argtypes = [i32, i32, i32, p, p, p, p, p]
+    lib.hb_rope_table.restype = i32
+    lib.hb_rope_table.argtypes = [i32, i32, C.c_double, p, p, p, p]
+    lib.hb_qkv_rope_project.restype = i32
+    lib.hb_qkv_rope_project.argtypes = [i32] * 5 + [p] * 8 + [p]
+    lib.hb_out_project.restype = i32
+    lib.hb_out_project.argtypes = [i32, i32, i32, p, p, p, p, p]
     lib.hb_tree_accept.restype = i32
     lib.hb_tree_accept.argtypes = [i32, i32, p, p, p, p, p, i32, p, p, p, p, p]
     lib.hb_tree_accept_sample.restype = i32
@@ -162,6 +170,34 @@ def hb_lmhead_argmax_noalloc(hidden, weight, out_ids, out_max=None, stream=None)
         raise ValueError("weight must be [V, K] in the dtype of hidden")
     _check(lib.hb_lmhead_argmax_noalloc(_dtype_code(hidden), M, K, V, _ptr(hidden), _ptr(weight), _ptr(out_ids),
                                         _ptr(out_max), _stream(stream)))
+
+
+def hb_tree_positions(B: int, max_nodes_per_tree: int, node_offset, parent, prefix_len, positions, stream=None) -> None:
+    _check(lib.hb_tree_positions(B, max_nodes_per_tree, positions.numel(), _ptr(node_offset), _ptr(parent),
+                                 _ptr(prefix_len), _ptr(positions), _stream(stream)))
+
+
+def hb_rope_table(head_dim: int, theta: float, positions, cos_out, sin_out, stream=None) -> None:
+    _check(lib.hb_rope_table(positions.numel(), head_dim, float(theta), _ptr(positions), _ptr(cos_out), _ptr(sin_out),
+                             _stream(stream)))
+
+
+def hb_qkv_rope_project(hidden, w_qkv, bias, cos, sin, q, k, v, stream=None) -> None:
+    T, K = hidden.shape
+    _, Hq, D = q.shape
+    Hkv = k.shape[1]
+    if w_qkv.shape != ((Hq + 2 * Hkv) * D, K) or hidden.dtype != torch.bfloat16 or w_qkv.dtype != torch.bfloat16:
+        raise ValueError("w_qkv must be bf16 [(Hq + 2 Hkv) * D, K]")
+    _check(lib.hb_qkv_rope_project(T, K, Hq, Hkv, D, _ptr(hidden), _ptr(w_qkv), _ptr(bias), _ptr(cos), _ptr(sin),
+                                   _ptr(q), _ptr(k), _ptr(v), _stream(stream)))
+
+
+def hb_out_project(x, w, residual, out, stream=None) -> None:
+    T, K = x.shape
+    N = w.shape[0]
+    if w.shape[1] != K or x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16 or out.shape != (T, N):
+        raise ValueError("need bf16 x [T, K], w [N, K], out [T, N]")
+    _check(lib.hb_out_project(T, K, N, _ptr(x), _ptr(w), _ptr(residual), _ptr(out), _stream(stream)))
 
 
 def hb_tree_accept(B: int, max_nodes_per_tree: int, node_offset, parent, draft_ids, target_ids,

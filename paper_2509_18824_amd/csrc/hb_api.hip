@@ -279,6 +279,61 @@ int32_t hb_lmhead_argmax(int32_t dtype, int32_t M, int32_t K, int32_t V, const v
   return lmhead_enqueue(dtype, M, K, V, hidden, weight, out_ids, out_max, keys, s);
 }
 
+int32_t hb_tree_positions(int32_t B, int32_t max_nodes_per_tree, int32_t total_nodes,
+                          const int32_t *node_offset, const int32_t *parent, const int32_t *prefix_len,
+                          int32_t *positions, void *stream) {
+  if (B < 0 || total_nodes < 0 || max_nodes_per_tree <= 0)
+    return fail(HB_ERR_INVALID_ARG, "need B >= 0, total_nodes >= 0, max_nodes_per_tree > 0");
+  if (max_nodes_per_tree > 64)
+    return fail(HB_ERR_UNSUPPORTED, "max_nodes_per_tree %d: trees of more than 64 nodes are not supported",
+                max_nodes_per_tree);
+  if (B == 0 || total_nodes == 0) return HB_OK;
+  if (!node_offset || !parent || !prefix_len || !positions)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  HB_HIP_TRY(launch_tree_positions(B, max_nodes_per_tree, total_nodes, node_offset, parent, prefix_len, positions,
+                                   (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_rope_table(int32_t T, int32_t head_dim, double theta, const int32_t *positions, float *cos_out,
+                      float *sin_out, void *stream) {
+  if (T < 0 || head_dim <= 0 || head_dim % 2 || !(theta > 0.0))
+    return fail(HB_ERR_INVALID_ARG, "need T >= 0, an even head_dim > 0 and theta > 0");
+  if (T == 0) return HB_OK;
+  if (!positions || !cos_out || !sin_out) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  HB_HIP_TRY(launch_rope_table(T, head_dim / 2, theta, positions, cos_out, sin_out, (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_qkv_rope_project(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32_t head_dim, const void *hidden,
+                            const void *w_qkv, const void *bias_or_null, const float *cos, const float *sin,
+                            void *q, void *k, void *v, void *stream) {
+  if (T < 0 || K <= 0 || Hq <= 0 || Hkv <= 0) return fail(HB_ERR_INVALID_ARG, "need T >= 0 and K, Hq, Hkv > 0");
+  if (head_dim != 128) return fail(HB_ERR_UNSUPPORTED, "head_dim %d: the fused projection takes head_dim 128", head_dim);
+  if (K % 64) return fail(HB_ERR_UNSUPPORTED, "K %d: must be a multiple of 64", K);
+  if ((int64_t)(Hq + 2 * Hkv) * 128 > (int64_t)1 << 24) return fail(HB_ERR_UNSUPPORTED, "too many heads");
+  if (T == 0) return HB_OK;
+  if (!hidden || !w_qkv || !cos || !sin || !q || !k || !v)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(hidden) || misaligned(w_qkv) || misaligned(cos) || misaligned(sin) || misaligned(q) || misaligned(k) ||
+      misaligned(v) || (bias_or_null && misaligned(bias_or_null)))
+    return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  HB_HIP_TRY(launch_qkv_rope(T, K, Hq, Hkv, hidden, w_qkv, bias_or_null, cos, sin, q, k, v, (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_out_project(int32_t T, int32_t K, int32_t N, const void *x, const void *w,
+                       const void *residual_or_null, void *out, void *stream) {
+  if (T < 0 || K <= 0 || N <= 0) return fail(HB_ERR_INVALID_ARG, "need T >= 0 and K, N > 0");
+  if (K % 64 || N % 4) return fail(HB_ERR_UNSUPPORTED, "K %d must be a multiple of 64 and N %d of 4", K, N);
+  if (T == 0) return HB_OK;
+  if (!x || !w || !out) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(x) || misaligned(w) || misaligned(out) || (residual_or_null && misaligned(residual_or_null)))
+    return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  HB_HIP_TRY(launch_linear(T, K, N, x, w, residual_or_null, out, (hipStream_t)stream));
+  return HB_OK;
+}
+
 int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,
                        const int32_t *parent, const int32_t *draft_ids, const int32_t *target_ids,
                        const int32_t *prev_target_or_null, int32_t max_path, int32_t *accept_len,

@@ -107,144 +107,9 @@ __global__ __launch_bounds__(128 * WV) void lmhead_mfma_kernel(int M, int K, int
   const int m0 = m_tile * TM;
   const int v0 = v_tile * TV;
 
-  // Global -> LDS without passing through registers (global_load_lds_dwordx4): one instruction
-  // moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS, i.e. 8 consecutive tile rows of 8
-  // pieces.  The XOR swizzle of the LDS layout is applied on the source side: the lane that fills
-  // physical piece p of row r fetches logical piece p ^ f(r).  Wavefront w moves row groups
-  // w, w + 2*WV, ... of the weight tile and of the hidden tile.  Rows past the end are clamped
-  // (their results are dropped in the epilogue).
-  constexpr int NW = 2 * WV;                 // wavefronts
-  constexpr int W_GROUPS = TV / 8 / NW;      // 8-row groups of the weight tile per wavefront
-  constexpr int H_GROUPS = TM / 8 / NW;      // same for the hidden tile
-  const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const int grow = lane >> 3;                // row inside an 8-row group
-  const u32x4 *w_src[W_GROUPS];
-  const u32x4 *h_src[H_GROUPS];
-#pragma unroll
-  for (int i = 0; i < W_GROUPS; ++i) {
-    const int grp = uwave + NW * i;
-    int r = v0 + grp * 8 + grow;
-    r = r < V ? r : V - 1;
-    w_src[i] = weight + (size_t)r * kp + ((lane & 7) ^ (grow ^ (grp & 1)));
-  }
-#pragma unroll
-  for (int i = 0; i < H_GROUPS; ++i) {
-    const int grp = uwave + NW * i;
-    int r = m0 + grp * 8 + grow;
-    r = r < M ? r : M - 1;
-    h_src[i] = hidden + (size_t)r * kp + ((lane & 7) ^ (grow ^ (grp & 1)));
-  }
-
-  f32x16 acc[VT][MT];
-#pragma unroll
-  for (int a = 0; a < VT; ++a)
-#pragma unroll
-    for (int b = 0; b < MT; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-  const int k_steps = K / BK;
-  typedef __attribute__((address_space(1))) const void *gptr_t;
-  typedef __attribute__((address_space(3))) void *lptr_t;
-
-#define HB_ISSUE_W(kt_, slot_)                                                                   \
-  {                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < W_GROUPS; ++i)                                          \
-        __builtin_amdgcn_global_load_lds((gptr_t)(w_src[i] + (kt_) * CH),                        \
-                                         (lptr_t)(lw + (slot_) * TV * CH + (uwave + NW * i) * 64), 16, 0, WNT ? 2 : 0); \
-  }
-#define HB_ISSUE_H(kt_, slot_)                                                                   \
-  {                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < H_GROUPS; ++i)                                          \
-        __builtin_amdgcn_global_load_lds((gptr_t)(h_src[i] + (kt_) * CH),                        \
-                                         (lptr_t)(lh + (slot_) * TM * CH + (uwave + NW * i) * 64), 16, 0, 0); \
-  }
-  // Everything but this wavefront's W_GROUPS newest loads (the weight rows of the step after
-  // next, which stay in flight across the barrier) has landed in LDS; after the barrier,
-  // everybody's has.
-  static_assert(W_GROUPS == 4, "the wait below leaves W_GROUPS loads outstanding");
-#define HB_STEP_DONE() asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory")
-#define HB_LOAD_FRAGS(ks_, slot_)                                                                \
-  {                                                                                              \
-    const int c = (ks_) * 2 + frag_half; /* this lane's 8-k piece of the 16-k MFMA step */       \
-    _Pragma("unroll") for (int i = 0; i < VT; ++i)                                                \
-        a[slot_][i] = __builtin_bit_cast(bf16x8, cw[swz(wv * 32 * VT + i * 32 + frag_row, c)]);  \
-    _Pragma("unroll") for (int j = 0; j < MT; ++j)                                                \
-        b[slot_][j] = __builtin_bit_cast(bf16x8, chh[swz(wm * 32 * MT + j * 32 + frag_row, c)]); \
-  }
-  // The MFMAs of one 16-k sub-step from fragment set set_.
-#define HB_MFMAS(set_)                                                                           \
-  {                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < VT; ++i)                                                \
-      _Pragma("unroll") for (int j = 0; j < MT; ++j)                                              \
-        {                                                                                        \
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set_][i], b[set_][j], acc[i][j], 0, 0, 0); \
-          asm volatile("" : "+a"(acc[i][j])); /* keep the accumulator in place in AGPRs */       \
-        }                                                                                        \
-    __builtin_amdgcn_sched_barrier(0);                                                           \
-  }
-
-  const int frag_row = lane & 31;
-  const int frag_half = lane >> 5;
-  // Pipeline.  Weight tiles (mostly from HBM) are fetched two K steps ahead into a ring of three
-  // LDS stages, hidden tiles (cache resident) one step ahead into two; a fetch past the end
-  // repeats the last step (no branch in the loop) and nothing reads it.  A K step is four 16-k
-  // MFMA sub-steps with two operand fragment sets: the fragments of sub-step s + 1 are read from
-  // LDS before the MFMAs of sub-step s are issued.  The barrier that ends step t sits BEFORE the
-  // MFMAs of its last sub-step, whose fragments are in registers by then: a wavefront is done
-  // with stage t at that point, and behind the barrier it first reads the fragments of
-  // (t + 1, sub-step 0) and then issues the remaining MFMAs of step t, which cover that read.
-  // Between two barriers a wavefront issues the hidden loads of step t + 2 (first, right after
-  // the barrier: they are needed at the next one) and the weight loads of step t + 2 (mid-step);
-  // the wait before a barrier leaves the newest W_GROUPS loads, those weight rows, in flight.
-  const int last = k_steps - 1;
-  HB_ISSUE_H(0, 0);
-  HB_ISSUE_W(0, 0);
-  HB_ISSUE_W((1 < last ? 1 : last), 1);
-  HB_STEP_DONE();
-  HB_ISSUE_H((1 < last ? 1 : last), 1);
-  int w_cur = 0, w_nxt = 1, w_free = 2;  // weight stages of steps kt, kt + 1 and the free one
-  const u32x4 *cw = lw;
-  const u32x4 *chh = lh;
-  bf16x8 a[2][VT], b[2][MT];
-  HB_LOAD_FRAGS(0, 0);
-#pragma unroll 1
-  for (int kt = 0; kt < k_steps; ++kt) {
-    HB_LOAD_FRAGS(1, 1);
-    HB_MFMAS(0);
-    HB_LOAD_FRAGS(2, 0);
-    HB_MFMAS(1);
-    HB_ISSUE_W((kt + 2 < last ? kt + 2 : last), w_free);
-    __builtin_amdgcn_sched_barrier(0);
-    HB_LOAD_FRAGS(3, 1);
-    HB_MFMAS(0);
-    // Every LDS read of step kt must have returned before the barrier frees its stage.  Naming
-    // the last fragment set as an asm operand makes the compiler wait for it here, and lets it
-    // know that the MFMAs behind the barrier have nothing to wait for.
-#pragma unroll
-    for (int i = 0; i < VT; ++i) asm volatile("" : "+v"(a[1][i]));
-#pragma unroll
-    for (int j = 0; j < MT; ++j) asm volatile("" : "+v"(b[1][j]));
-    HB_STEP_DONE();
-    HB_ISSUE_H((kt + 2 < last ? kt + 2 : last), kt & 1);
-    const int t = w_cur;
-    w_cur = w_nxt;
-    w_nxt = w_free;
-    w_free = t;
-    cw = lw + w_cur * TV * CH;
-    chh = lh + ((kt + 1) & 1) * TM * CH;
-    HB_LOAD_FRAGS(0, 0);  // of step kt + 1 (after the last step: unused)
-    __builtin_amdgcn_sched_barrier(0);
-    HB_MFMAS(1);
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();  // all tile loads landed, all operand reads done: LDS is free for row_key
-
-#undef HB_ISSUE_W
-#undef HB_ISSUE_H
-#undef HB_STEP_DONE
-#undef HB_MFMAS
-#undef HB_LOAD_FRAGS
+#define HB_GEMM_W_ROW(t_) (v0 + (t_))
+#include "mfma_gemm_tile.inc"
+#undef HB_GEMM_W_ROW
 
   // Epilogue.  Accumulator r of lane l in tile (i, j) is C^T[v, m] with
   //   v = v0 + wv*32*VT + i*32 + 8*(r/4) + 4*(l/32) + r%4,   m = m0 + wm*32*MT + j*32 + l%32.

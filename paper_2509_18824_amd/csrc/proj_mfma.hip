@@ -1,0 +1,253 @@
+// The target's projections around the tree-verify attention, on the bf16 matrix cores:
+//   * fused query/key/value projection + bias + rotary embedding, written straight into the
+//     layouts hb_tree_verify_attn reads (q [T, Hq, D], k_tree / v_tree [T, Hkv, D]);
+//   * output projection (a plain  out = x W^T (+ residual)  in bf16 with fp32 accumulation);
+//   * the two small kernels that give every tree node its position (prefix length + depth) and
+//     the cosine / sine table of those positions.
+// The matrix work is the tile loop of the LM head (mfma_gemm_tile.inc: C^T = W H^T, weight rows
+// as the MFMA "A" operand, so a lane's accumulators of a 32x32 tile are 16 output features of ONE
+// token).  For the rotary embedding the 256 weight rows of a tile are not taken in memory order:
+// a tile holds two heads, and the rows are arranged so that the two accumulators a lane holds at
+// the same position of its two 32-row sub-tiles are the pair (d, d + 64) of one head, which is
+// what the rotate-half convention rotates together: the rotation costs no exchange at all.
+#include "hb_internal.h"
+
+namespace hb {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BK = 64;
+constexpr int TV = 256;
+constexpr int CH = BK / 8;
+constexpr int kXcds = 8;
+constexpr int kHeadDim = 128;
+
+__device__ inline int swz(int r, int c) { return r * CH + (c ^ ((r & 7) ^ ((r >> 3) & 1))); }
+
+__device__ inline uint32_t pack_bf16(float a, float b) { return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16); }
+
+struct QkvArgs {
+  const bf16_t *bias;      // [(Hq + 2 Hkv) * 128] or null
+  const float *cos, *sin;  // [M, 64]
+  bf16_t *q, *k, *v;       // [M, Hq, 128], [M, Hkv, 128], [M, Hkv, 128]
+  int Hq, Hkv;
+};
+struct StoreArgs {
+  const bf16_t *residual;  // [M, N] or null
+  bf16_t *out;             // [M, N]
+};
+
+// ROPE: query/key/value projection with rotary embedding (V = (Hq + 2 Hkv) * 128 weight rows),
+// else plain projection.  One workgroup per (weight tile, hidden tile); the workgroups that share
+// a weight tile get neighbouring slots of one XCD (ids 8 apart) and find it in that XCD's L2.
+template <int MT, bool ROPE>
+__global__ __launch_bounds__(512) void proj_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles,
+                                                        const u32x4 *__restrict__ hidden,
+                                                        const u32x4 *__restrict__ weight, QkvArgs qa, StoreArgs sa) {
+  constexpr int WV = 4;
+  constexpr bool WNT = false;
+  constexpr int TM = 64 * MT;
+  constexpr int VT = 8 / WV;
+  extern __shared__ u32x4 lds[];
+  u32x4 *lw = lds;
+  u32x4 *lh = lds + 3 * TV * CH;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wv = wave >> 1;
+  const int wm = wave & 1;
+  const int id = blockIdx.x;
+  const int xcd = id % kXcds, slot = id / kXcds;
+  const int v_tile = (slot / m_tiles) * kXcds + xcd;
+  const int m_tile = slot % m_tiles;
+  if (v_tile >= v_tiles) return;
+  const int m0 = m_tile * TM;
+  const int v0 = v_tile * TV;
+  const int kp = K / 8;
+
+  // Tile row t (wavefront row wv = t / 64, sub-tile i = (t % 64) / 32, rr = t % 32) holds, for the
+  // rotary variant, feature  (wv / 2) * 128 + (wv % 2) * 32 + 64 i + rr  of the tile's two heads.
+#define HB_GEMM_W_ROW(t_) (ROPE ? v0 + (((t_) >> 7) << 7) + ((((t_) >> 6) & 1) << 5) + ((((t_) >> 5) & 1) << 6) + ((t_) & 31) \
+                                : v0 + (t_))
+#include "mfma_gemm_tile.inc"
+#undef HB_GEMM_W_ROW
+
+  // Epilogue.  Accumulator r = 4 c + e of lane l in tile (i, j): tile row wv*64 + i*32 + 8 c +
+  // 4 (l / 32) + e, token m0 + wm*32*MT + j*32 + l % 32.
+#pragma unroll
+  for (int j = 0; j < MT; ++j) {
+    const int m = m0 + wm * 32 * MT + j * 32 + frag_row;
+    if (m >= M) continue;
+    if (ROPE) {
+      const int head = (v0 >> 7) + (wv >> 1);
+      const bool rotate = head < qa.Hq + qa.Hkv;
+      bf16_t *dst = head < qa.Hq ? qa.q + ((size_t)m * qa.Hq + head) * kHeadDim
+                    : head < qa.Hq + qa.Hkv ? qa.k + ((size_t)m * qa.Hkv + (head - qa.Hq)) * kHeadDim
+                                            : qa.v + ((size_t)m * qa.Hkv + (head - qa.Hq - qa.Hkv)) * kHeadDim;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int d = (wv & 1) * 32 + 8 * c + 4 * frag_half;  // d .. d + 3 and d + 64 .. d + 67
+        float x1[4], x2[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          x1[e] = acc[0][j][4 * c + e];
+          x2[e] = acc[1][j][4 * c + e];
+        }
+        if (qa.bias) {
+          const u32x2 b1 = *(const u32x2 *)(qa.bias + head * kHeadDim + d);
+          const u32x2 b2 = *(const u32x2 *)(qa.bias + head * kHeadDim + d + 64);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            x1[e] += __uint_as_float((e & 1) ? (b1[e >> 1] & 0xffff0000u) : (b1[e >> 1] << 16));
+            x2[e] += __uint_as_float((e & 1) ? (b2[e >> 1] & 0xffff0000u) : (b2[e >> 1] << 16));
+          }
+        }
+        if (rotate) {
+          const f32x4 cs = *(const f32x4 *)(qa.cos + (size_t)m * 64 + d);
+          const f32x4 sn = *(const f32x4 *)(qa.sin + (size_t)m * 64 + d);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float a = x1[e] * cs[e] - x2[e] * sn[e];
+            const float b = x2[e] * cs[e] + x1[e] * sn[e];
+            x1[e] = a;
+            x2[e] = b;
+          }
+        }
+        *(u32x2 *)(dst + d) = (u32x2){pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
+        *(u32x2 *)(dst + d + 64) = (u32x2){pack_bf16(x2[0], x2[1]), pack_bf16(x2[2], x2[3])};
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < VT; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int n = v0 + wv * 32 * VT + i * 32 + 8 * c + 4 * frag_half;  // n .. n + 3, V % 4 == 0
+          if (n >= V) continue;
+          float x[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = acc[i][j][4 * c + e];
+          if (sa.residual) {
+            const u32x2 r = *(const u32x2 *)(sa.residual + (size_t)m * V + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] += __uint_as_float((e & 1) ? (r[e >> 1] & 0xffff0000u) : (r[e >> 1] << 16));
+          }
+          *(u32x2 *)(sa.out + (size_t)m * V + n) = (u32x2){pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+        }
+    }
+  }
+}
+
+template <int MT, bool ROPE>
+hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, const QkvArgs &qa, const StoreArgs &sa,
+                  hipStream_t s) {
+  constexpr int TM = 64 * MT;
+  const int m_tiles = (M + TM - 1) / TM;
+  const int v_tiles = (V + TV - 1) / TV;
+  const size_t lds_bytes = (size_t)(3 * TV + 2 * TM) * CH * sizeof(u32x4);
+  auto kern = proj_mfma_kernel<MT, ROPE>;
+  hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (e != hipSuccess) return e;
+  dim3 grid((unsigned)((v_tiles + kXcds - 1) / kXcds * kXcds * m_tiles));
+  kern<<<grid, 512, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const u32x4 *)hidden, (const u32x4 *)weight, qa, sa);
+  return hipGetLastError();
+}
+
+// hidden tile height: the tallest (fewest re-reads of the weights) that still gives the chip about
+// one workgroup per CU
+template <bool ROPE>
+hipError_t dispatch(int M, int K, int V, const void *hidden, const void *weight, const QkvArgs &qa, const StoreArgs &sa,
+                    hipStream_t s) {
+  const int v_tiles = (V + TV - 1) / TV;
+  int mt = 1;
+  for (int t = 4; t >= 2; --t)
+    if ((long)v_tiles * ((M + 64 * t - 1) / (64 * t)) >= 200) { mt = t; break; }
+  switch (mt) {
+    case 4: return launch<4, ROPE>(M, K, V, hidden, weight, qa, sa, s);
+    case 3: return launch<3, ROPE>(M, K, V, hidden, weight, qa, sa, s);
+    case 2: return launch<2, ROPE>(M, K, V, hidden, weight, qa, sa, s);
+    default: return launch<1, ROPE>(M, K, V, hidden, weight, qa, sa, s);
+  }
+}
+
+// positions[n] = prefix_len[b] + depth(n); one wavefront per sequence, one lane per node
+__global__ __launch_bounds__(64) void tree_positions_kernel(int max_nodes, int total_nodes,
+                                                           const int32_t *__restrict__ node_offset,
+                                                           const int32_t *__restrict__ parent,
+                                                           const int32_t *__restrict__ prefix_len,
+                                                           int32_t *__restrict__ positions) {
+  __shared__ int32_t spar[64];
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int n0 = node_offset[b];
+  int n = node_offset[b + 1] - n0;
+  n = n < 0 ? 0 : (n > max_nodes ? max_nodes : n);
+  if (n0 < 0 || n0 + n > total_nodes) n = 0;
+  int par = -1;
+  if (lane < n) {
+    par = parent[n0 + lane];
+    if (par >= lane || par < -1) par = -1;  // malformed: a root
+  }
+  spar[lane] = par;
+  __syncthreads();
+  int depth = 0;
+  for (int x = par, guard = 0; x >= 0 && guard < 64; ++guard) {
+    ++depth;
+    x = spar[x];
+  }
+  if (lane < n) positions[n0 + lane] = prefix_len[b] + depth;
+}
+
+// cos / sin of positions[t] * theta^(-d / half), d < half, in double precision (the angle reaches
+// tens of thousands of radians), stored as float
+__global__ __launch_bounds__(256) void rope_table_kernel(int T, int half, double log2_theta,
+                                                        const int32_t *__restrict__ positions,
+                                                        float *__restrict__ cos_out, float *__restrict__ sin_out) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)T * half) return;
+  const int t = (int)(idx / half), d = (int)(idx - (long)t * half);
+  const double inv_freq = exp2(-log2_theta * (double)d / (double)half);
+  const double ang = (double)positions[t] * inv_freq;
+  double sv, cv;
+  sincos(ang, &sv, &cv);
+  cos_out[idx] = (float)cv;
+  sin_out[idx] = (float)sv;
+}
+
+}  // namespace
+
+bool proj_mfma_supports(int32_t M, int32_t K, int32_t N) { return M >= 1 && K >= BK && K % BK == 0 && N >= 4 && N % 4 == 0; }
+
+hipError_t launch_qkv_rope(int32_t M, int32_t K, int32_t Hq, int32_t Hkv, const void *hidden, const void *w_qkv,
+                           const void *bias, const float *cos, const float *sin, void *q, void *k, void *v,
+                           hipStream_t s) {
+  QkvArgs qa = {(const bf16_t *)bias, cos, sin, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, Hq, Hkv};
+  StoreArgs sa = {nullptr, nullptr};
+  return dispatch<true>(M, K, (Hq + 2 * Hkv) * kHeadDim, hidden, w_qkv, qa, sa, s);
+}
+
+hipError_t launch_linear(int32_t M, int32_t K, int32_t N, const void *x, const void *w, const void *residual, void *out,
+                         hipStream_t s) {
+  QkvArgs qa = {};
+  StoreArgs sa = {(const bf16_t *)residual, (bf16_t *)out};
+  return dispatch<false>(M, K, N, x, w, qa, sa, s);
+}
+
+hipError_t launch_tree_positions(int32_t B, int32_t max_nodes, int32_t total_nodes, const int32_t *node_offset,
+                                 const int32_t *parent, const int32_t *prefix_len, int32_t *positions, hipStream_t s) {
+  tree_positions_kernel<<<B, 64, 0, s>>>(max_nodes, total_nodes, node_offset, parent, prefix_len, positions);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(int32_t T, int32_t half, double theta, const int32_t *positions, float *cos, float *sin,
+                             hipStream_t s) {
+  const long n = (long)T * half;
+  rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(T, half, log2(theta), positions, cos, sin);
+  return hipGetLastError();
+}
+
+}  // namespace hb

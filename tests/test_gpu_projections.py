@@ -1,0 +1,118 @@
+"""GPU parity: positions, rotary table, fused QKV projection + rotary embedding, output projection
+against the float64 oracle.
+
+Tolerances (bf16 outputs of fp32-accumulated products of bf16 inputs): the result is rounded once
+to bf16 (relative 2^-9 = 2e-3); fp32 accumulation over K <= 3584 terms adds well under 1e-5
+relative to the sum of magnitudes.  Tested as: max abs error <= 1e-2 * (1 + |ref|) elementwise and
+relative L2 error <= 4e-3."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hb():
+    import paper_2509_18824_amd as m
+    return m
+
+
+def _close(got, ref, label):
+    got = W.widen(got)
+    err = np.abs(got - ref)
+    assert np.isfinite(got).all(), label
+    assert (err <= 1e-2 * (1.0 + np.abs(ref))).all(), f"{label}: max abs err {err.max():.3e}"
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    assert rel <= 4e-3, f"{label}: rel L2 {rel:.3e}"
+
+
+def test_positions_and_rope_table(hb):
+    rng = np.random.default_rng(0)
+    trees = [W.seeded_tree(1), np.array([], dtype=np.int32), W.chain_tree(8), W.seeded_tree(2, n_nodes=64), W.chain_tree(1)]
+    off = np.concatenate([[0], np.cumsum([len(t) for t in trees])]).astype(np.int32)
+    par = np.concatenate(trees).astype(np.int32)
+    L = np.array([32768, 5, 0, 4095, 17], dtype=np.int32)
+    t = lambda a: torch.from_numpy(a).cuda()
+    pos = torch.full((int(off[-1]),), -1, dtype=torch.int32, device="cuda")
+    hb.hb_tree_positions(len(trees), 64, t(off), t(par), t(L), pos)
+    ref = tree_positions_ref(off, par, L)
+    assert np.array_equal(pos.cpu().numpy(), ref)
+    for theta in (1e4, 1e6):
+        cos = torch.empty((pos.numel(), 64), dtype=torch.float32, device="cuda")
+        sin = torch.empty_like(cos)
+        hb.hb_rope_table(128, theta, pos, cos, sin)
+        ang = ref[:, None].astype(np.float64) * theta ** (-np.arange(64) / 64.0)
+        assert np.abs(cos.cpu().numpy() - np.cos(ang)).max() <= 2e-7
+        assert np.abs(sin.cpu().numpy() - np.sin(ang)).max() <= 2e-7
+
+
+@pytest.mark.parametrize("T,K,Hq,Hkv,bias", [(960, 3584, 28, 4, True), (128, 3584, 28, 4, False), (77, 128, 2, 1, True),
+                                             (300, 320, 3, 3, False), (1, 64, 1, 1, True), (513, 192, 8, 2, True)])
+def test_qkv_projection_with_rotary_embedding(hb, T, K, Hq, Hkv, bias):
+    g = torch.Generator().manual_seed(T * 7 + K)
+    hidden = torch.randn((T, K), generator=g).to(torch.bfloat16)
+    w = (torch.randn(((Hq + 2 * Hkv) * 128, K), generator=g) * (1.0 / np.sqrt(K))).to(torch.bfloat16)
+    b = (torch.randn((Hq + 2 * Hkv) * 128, generator=g) * 0.5).to(torch.bfloat16) if bias else None
+    pos = torch.randint(0, 40000, (T,), generator=g, dtype=torch.int32)
+    theta = 1e6
+    cos = torch.empty((T, 64), dtype=torch.float32, device="cuda")
+    sin = torch.empty_like(cos)
+    hb.hb_rope_table(128, theta, pos.cuda(), cos, sin)
+    q = torch.full((T, Hq, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    k = torch.full((T, Hkv, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    v = torch.full((T, Hkv, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    hb.hb_qkv_rope_project(hidden.cuda(), w.cuda(), None if b is None else b.cuda(), cos, sin, q, k, v)
+    torch.cuda.synchronize()
+    rq, rk, rv = qkv_rope_project_ref(W.widen(hidden), W.widen(w), None if b is None else W.widen(b), pos.numpy(),
+                                      Hq, Hkv, 128, theta)
+    _close(q, rq, "q"); _close(k, rk, "k"); _close(v, rv, "v")
+
+
+@pytest.mark.parametrize("T,K,N,res", [(960, 3584, 3584, True), (128, 3584, 3584, False), (50, 64, 4, True),
+                                       (333, 448, 1000, False), (700, 256, 260, True)])
+def test_output_projection(hb, T, K, N, res):
+    g = torch.Generator().manual_seed(T + K + N)
+    x = torch.randn((T, K), generator=g).to(torch.bfloat16)
+    w = (torch.randn((N, K), generator=g) * (1.0 / np.sqrt(K))).to(torch.bfloat16)
+    r = torch.randn((T, N), generator=g).to(torch.bfloat16) if res else None
+    out = torch.full((T, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    hb.hb_out_project(x.cuda(), w.cuda(), None if r is None else r.cuda(), out)
+    torch.cuda.synchronize()
+    _close(out, linear_ref(W.widen(x), W.widen(w), None if r is None else W.widen(r)), "out")
+
+
+def test_projected_qkv_feed_the_attention(hb):
+    """hidden -> QKV + rotary -> tree-verify attention -> output projection, against the oracle
+    chained the same way on the bf16 tensors the GPU hands from step to step."""
+    import paper_2509_18824_amd.step as S
+    from oracle import tree_attn_ref
+    inp = W.make_config(4, scale_down=16)
+    T, Hq, Hkv, D, K = inp.total_nodes, inp.Hq, inp.Hkv, inp.D, 512
+    g = torch.Generator().manual_seed(5)
+    hidden = torch.randn((T, K), generator=g).to(torch.bfloat16)
+    wqkv = (torch.randn(((Hq + 2 * Hkv) * D, K), generator=g) / np.sqrt(K)).to(torch.bfloat16)
+    wo = (torch.randn((K, Hq * D), generator=g) / np.sqrt(Hq * D)).to(torch.bfloat16)
+    dev = S.to_device(inp)
+    pos = torch.empty(T, dtype=torch.int32, device="cuda")
+    hb.hb_tree_positions(inp.B, 64, dev.node_offset, dev.parent, dev.prefix_len, pos)
+    cos = torch.empty((T, 64), dtype=torch.float32, device="cuda"); sin = torch.empty_like(cos)
+    hb.hb_rope_table(D, 1e6, pos, cos, sin)
+    hb.hb_qkv_rope_project(hidden.cuda(), wqkv.cuda(), None, cos, sin, dev.q, dev.k_tree, dev.v_tree)
+    desc = S.desc_for(inp)
+    out, _ = S.tree_verify_attn(desc, dev, want_lse=False)
+    y = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+    hb.hb_out_project(out.view(T, -1), wo.cuda(), hidden.cuda(), y)
+    torch.cuda.synchronize()
+    ref_pos = tree_positions_ref(inp.node_offset.numpy(), inp.parent.numpy(), inp.prefix_len.numpy())
+    rq, rk, rv = qkv_rope_project_ref(W.widen(hidden), W.widen(wqkv), None, ref_pos, Hq, Hkv, D, 1e6)
+    _close(dev.q, rq, "q"); _close(dev.k_tree, rk, "k"); _close(dev.v_tree, rv, "v")
+    ref_attn, _ = tree_attn_ref(W.widen(dev.q), W.widen(dev.k_tree), W.widen(dev.v_tree), W.widen(inp.k_pool),
+                                W.widen(inp.v_pool), inp.block_table.numpy(), inp.prefix_len.numpy(),
+                                inp.node_offset.numpy(), inp.parent.numpy(), inp.softmax_scale)
+    got_attn = W.widen(out)
+    assert np.linalg.norm(got_attn - ref_attn) / np.linalg.norm(ref_attn) <= 1e-2
+    _close(y, linear_ref(got_attn.reshape(T, -1), W.widen(wo), W.widen(hidden)), "layer output")
