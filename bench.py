@@ -325,6 +325,80 @@ def achievable_peaks():
     return out
 
 
+def bench_layer_stack(inp, desc, dv, lm_weight, draft_np, n_steps, n_layers=28):
+    """The step at a realistic depth: 28 layers, each QKV projection + rotary embedding ->
+    tree-verify attention over its own KV pools (2.3 GB in all, so every layer streams its KV from
+    HBM) -> output projection with residual (random weights, hidden size 3584); then the LM head,
+    acceptance, and 28 compactions.  Captured once into a HIP graph and replayed; the eager run
+    gives the share of each kind of call (events on the launch stream)."""
+    import torch
+    import paper_2509_18824_amd.step as S
+
+    T, Hq, D = dv.q.shape
+    Hkv = dv.k_tree.shape[1]
+    K = Hq * D
+    g = torch.Generator(device="cuda").manual_seed(28)
+    mk = lambda *shape, std: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+    w_qkv = [mk((Hq + 2 * Hkv) * D, K, std=K ** -0.5) for _ in range(n_layers)]
+    w_o = [mk(K, K, std=0.3 * K ** -0.5) for _ in range(n_layers)]
+    hidden0 = mk(T, K, std=1.0)
+    pools = [(dv.k_pool, dv.v_pool)] + [(dv.k_pool.clone(), dv.v_pool.clone()) for _ in range(n_layers - 1)]
+    draft = torch.from_numpy(draft_np).to(torch.int32).cuda()
+    stack = S.VerifyLayerStack(desc, dv, pools, w_qkv, w_o, lm_weight, draft, inp.max_path, hidden0)
+
+    for _ in range(2):
+        stack.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_steps):
+        stack.run()
+    torch.cuda.synchronize()
+    ms_eager = (time.perf_counter() - t0) * 1e3 / n_steps
+    # share of each kind of call: one eager step with an event before every call
+    marks = []
+    def on_call(name):
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        marks.append((name, ev))
+    stack.run(on_call=on_call)
+    torch.cuda.synchronize()
+    share = {}
+    for (name, ev), (_, nxt) in zip(marks[:-1], marks[1:]):
+        share[name] = share.get(name, 0.0) + ev.elapsed_time(nxt)
+    # graph: capture on a side stream, replay on it
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        stack.run()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            stack.run()
+        for _ in range(2):
+            graph.replay()
+        side.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            graph.replay()
+        side.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / n_steps
+    target_graph = stack.target_ids.clone()
+    stack.run()
+    torch.cuda.synchronize()
+    same = bool(torch.equal(target_graph, stack.target_ids))
+    kv_bytes = inp.kv_bytes()
+    gemm_flops = 2.0 * T * K * ((Hq + 2 * Hkv) * D + K)
+    return {
+        "layers": n_layers, "steps": n_steps, "ms_per_step": ms_graph, "ms_per_step_eager": ms_eager,
+        "tree_tokens_per_s": T / (ms_graph * 1e-3), "graph_replay_equals_eager": same,
+        "eager_ms_by_call": share,
+        "attn_ms_per_layer": share.get("tree_verify_attn", 0.0) / n_layers,
+        "kv_GBps": kv_bytes / (share.get("tree_verify_attn", 1e9) / n_layers * 1e-3) / 1e9,
+        "projection_TFLOPs": gemm_flops * n_layers / ((share.get("qkv_rope_project", 0) + share.get("out_project", 1e9)) * 1e-3) / 1e12,
+        "what": "per layer: QKV projection + rotary embedding, tree-verify attention, output projection with residual "
+                "(no MLP, no norms); then LM head + argmax, acceptance, 28 compactions; one HIP graph per step",
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -424,46 +498,7 @@ def main():
         result["parity"] = parity_check(run, weight)
     draft_np = run["draft_np"]
     if not args.no_stack:
-        # The same step with a realistic depth: 28 attention layers over 28 distinct KV pools (2.3 GB,
-        # so every layer streams its KV from HBM), one LM head, one acceptance, 28 compactions.
-        # Reported next to the headline figure, which is the one-layer step.
-        n_layers, n_stack = 28, max(5, args.steps // 5)
-        pools = [(dv.k_pool, dv.v_pool)] + [(dv.k_pool.clone(), dv.v_pool.clone()) for _ in range(n_layers - 1)]
-
-        def stack_step(ev=None):
-            if ev: ev[0].record()
-            for kp, vp in pools:
-                hb.hb_tree_verify_attn(desc, dv.q, dv.k_tree, dv.v_tree, kp, vp, dv.block_table, dv.prefix_len,
-                                       dv.node_offset, dv.parent, step.out, None, step.ws_attn)
-            if ev: ev[1].record()
-            hb.hb_lmhead_argmax(step.out.view(inp.total_nodes, -1), wdev, step.target_ids, None, step.ws_lm)
-            hb.hb_tree_accept(desc.batch, desc.max_nodes_per_tree, dv.node_offset, dv.parent, step.draft_ids,
-                              step.target_ids, step.max_path, step.accept_len, step.accept_path,
-                              step.out_tokens, step.bonus)
-            for kp, vp in pools:
-                hb.hb_kv_compact(desc, dv.k_tree, dv.v_tree, kp, vp, dv.block_table, dv.prefix_len,
-                                 dv.node_offset, step.accept_len, step.accept_path, step.max_path,
-                                 step.out_slots, step.new_len)
-
-        for _ in range(2):
-            stack_step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n_stack):
-            stack_step()
-        torch.cuda.synchronize()
-        ms_stack = (time.perf_counter() - t0) * 1e3 / n_stack
-        ev = _events(n_stack)
-        for i in range(n_stack):
-            stack_step(ev[i])
-        torch.cuda.synchronize()
-        ms_attn_layer = _mean_ms(ev) / n_layers
-        result["stack28"] = {
-            "layers": n_layers, "steps": n_stack, "ms_per_step": ms_stack,
-            "tree_tokens_per_s": M / (ms_stack * 1e-3), "attn_ms_per_layer": ms_attn_layer,
-            "kv_GBps": kv_bytes / (ms_attn_layer * 1e-3) / 1e9,
-        }
-        del pools
+        result["stack28"] = bench_layer_stack(inp, desc, dv, wdev, run["draft_np"], max(5, args.steps // 5))
     other = "chain8" if args.tree == "tree" else "tree"
     if not args.no_chain:
         # The same step with the other draft shape (the paper measures chain drafts: Section 1,

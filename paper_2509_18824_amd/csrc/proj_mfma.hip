@@ -158,15 +158,22 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, c
   return hipGetLastError();
 }
 
-// hidden tile height: the tallest (fewest re-reads of the weights) that still gives the chip about
-// one workgroup per CU
+// Hidden tile height (64 MT rows) by a small cost model: a workgroup's time per K step is about
+// 1 + 0.55 MT units (staging of the 256-row weight tile + MT x the matrix work of 64 rows, from
+// the LM head's measured 2100 clocks at MT = 3); one workgroup per CU at a time, so the launch
+// takes ceil(units / 256) rounds of that.  960 x 4608: MT = 2 (144 units, one round) beats MT = 1
+// (270 units: a second round for 14 of them) and MT = 3 (90 units).
 template <bool ROPE>
 hipError_t dispatch(int M, int K, int V, const void *hidden, const void *weight, const QkvArgs &qa, const StoreArgs &sa,
                     hipStream_t s) {
   const int v_tiles = (V + TV - 1) / TV;
   int mt = 1;
-  for (int t = 4; t >= 2; --t)
-    if ((long)v_tiles * ((M + 64 * t - 1) / (64 * t)) >= 200) { mt = t; break; }
+  double best = 1e30;
+  for (int t = 1; t <= 4; ++t) {
+    const long units = (long)v_tiles * ((M + 64 * t - 1) / (64 * t));
+    const double cost = (double)((units + 255) / 256) * (1.0 + 0.55 * t);
+    if (cost < best - 1e-9) { best = cost; mt = t; }
+  }
   switch (mt) {
     case 4: return launch<4, ROPE>(M, K, V, hidden, weight, qa, sa, s);
     case 3: return launch<3, ROPE>(M, K, V, hidden, weight, qa, sa, s);

@@ -147,3 +147,76 @@ class VerifyStep:
             hb.hb_kv_compact(desc, dev.k_tree, dev.v_tree, dev.k_pool, dev.v_pool, dev.block_table,
                              dev.prefix_len, dev.node_offset, self.accept_len, self.accept_path, self.max_path,
                              self.out_slots, self.new_len)
+
+
+class VerifyLayerStack:
+    """Buffers and call chain of one verification step through ``n_layers`` decoder layers reduced
+    to their attention half (QKV projection + rotary embedding -> tree-verify attention over that
+    layer's KV pools -> output projection with residual), then LM head with argmax, acceptance,
+    and the append of the accepted nodes' K/V to every layer's pools.  ``run`` only enqueues
+    kernels on the current stream (no allocation, no host synchronisation), so a step can be
+    captured into a HIP graph once and replayed."""
+
+    def __init__(self, desc: hb.AttnDesc, dev: DeviceInputs, pools, w_qkv, w_o, lm_weight, draft_ids, max_path: int,
+                 hidden0: torch.Tensor, theta: float = 1e6):
+        self.desc, self.dev, self.pools, self.w_qkv, self.w_o = desc, dev, pools, w_qkv, w_o
+        self.lm_weight, self.draft_ids, self.max_path, self.theta = lm_weight, draft_ids, max_path, theta
+        d = hidden0.device
+        T, Hq, D = dev.q.shape
+        Hkv = dev.k_tree.shape[1]
+        B = desc.batch
+        self.n_layers = len(pools)
+        self.hidden = [hidden0] + [torch.empty_like(hidden0) for _ in range(2)]  # input, ping, pong
+        self.positions = torch.empty(T, dtype=torch.int32, device=d)
+        self.cos = torch.empty((T, D // 2), dtype=torch.float32, device=d)
+        self.sin = torch.empty_like(self.cos)
+        self.q = torch.empty_like(dev.q)
+        self.k_tree = [torch.empty_like(dev.k_tree) for _ in range(self.n_layers)]  # kept for the compaction
+        self.v_tree = [torch.empty_like(dev.v_tree) for _ in range(self.n_layers)]
+        self.attn_out = torch.empty_like(dev.q)
+        self.ws_attn = alloc_workspace(hb.hb_tree_verify_attn_workspace_bytes(desc), d)
+        self.ws_lm = alloc_workspace(max(8, hb.hb_lmhead_argmax_workspace_bytes(T)), d)
+        self.target_ids = torch.empty(T, dtype=torch.int32, device=d)
+        self.accept_len = torch.empty(B, dtype=torch.int32, device=d)
+        self.accept_path = torch.empty((B, max_path), dtype=torch.int32, device=d)
+        self.out_tokens = torch.empty((B, max_path), dtype=torch.int32, device=d)
+        self.bonus = torch.empty(B, dtype=torch.int32, device=d)
+        self.out_slots = torch.empty((B, max_path), dtype=torch.int32, device=d)
+        self.new_len = torch.empty(B, dtype=torch.int32, device=d)
+
+    def run(self, compact=True, on_call=None):
+        """``on_call(name)`` (optional) is invoked before every library call, e.g. to record events."""
+        dev, desc = self.dev, self.desc
+        T = self.q.shape[0]
+        mark = on_call or (lambda name: None)
+        mark("positions")
+        hb.hb_tree_positions(desc.batch, desc.max_nodes_per_tree, dev.node_offset, dev.parent, dev.prefix_len,
+                             self.positions)
+        hb.hb_rope_table(self.q.shape[2], self.theta, self.positions, self.cos, self.sin)
+        x = self.hidden[0]
+        for l in range(self.n_layers):
+            y = self.hidden[1 + (l & 1)]
+            kp, vp = self.pools[l]
+            mark("qkv_rope_project")
+            hb.hb_qkv_rope_project(x, self.w_qkv[l], None, self.cos, self.sin, self.q, self.k_tree[l], self.v_tree[l])
+            mark("tree_verify_attn")
+            hb.hb_tree_verify_attn(desc, self.q, self.k_tree[l], self.v_tree[l], kp, vp, dev.block_table,
+                                   dev.prefix_len, dev.node_offset, dev.parent, self.attn_out, None, self.ws_attn)
+            mark("out_project")
+            hb.hb_out_project(self.attn_out.view(T, -1), self.w_o[l], x, y)
+            x = y
+        self.final_hidden = x
+        mark("lmhead_argmax")
+        hb.hb_lmhead_argmax(x, self.lm_weight, self.target_ids, None, self.ws_lm)
+        mark("tree_accept")
+        hb.hb_tree_accept(desc.batch, desc.max_nodes_per_tree, dev.node_offset, dev.parent, self.draft_ids,
+                          self.target_ids, self.max_path, self.accept_len, self.accept_path, self.out_tokens,
+                          self.bonus)
+        if compact:
+            mark("kv_compact")
+            for l in range(self.n_layers):
+                kp, vp = self.pools[l]
+                hb.hb_kv_compact(desc, self.k_tree[l], self.v_tree[l], kp, vp, dev.block_table, dev.prefix_len,
+                                 dev.node_offset, self.accept_len, self.accept_path, self.max_path, self.out_slots,
+                                 self.new_len)
+        mark("end")
