@@ -41,9 +41,24 @@ def _silu(x):
     return x / (1.0 + np.exp(-x))
 
 
+def round_bf16(x):
+    """Round float64 values to the nearest bfloat16 (ties to even), returned as float64: the
+    rounding a bf16 kernel interface applies to what it is handed."""
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
 class ToyDecoderRef:
-    def __init__(self, w):
+    def __init__(self, w, quant=None):
+        """``quant`` (optional, default identity) is applied where a decoder that keeps its
+        attention inputs, attention output and LM-head input in a narrower storage type rounds
+        them: to q, k, v after the rotary embedding, to the attention output, and to the
+        normalised hidden state that feeds the LM head.  With ``round_bf16`` the three decoding
+        modes below describe such a bf16 decoder exactly, in float64 arithmetic."""
         self.w = w
+        self.quant = quant if quant is not None else (lambda a: a)
 
     # -- pieces shared by every decoding mode (plain per-token maths) ---------------------
     def _qkv(self, layer, x, pos):
@@ -53,16 +68,18 @@ class ToyDecoderRef:
         q = (h @ w.wq[layer]).reshape(T, w.Hq, w.Dh)
         k = (h @ w.wk[layer]).reshape(T, w.Hkv, w.Dh)
         v = (h @ w.wv[layer]).reshape(T, w.Hkv, w.Dh)
-        return _rope(q, pos, w.rope_base), _rope(k, pos, w.rope_base), v
+        qt = self.quant
+        return qt(_rope(q, pos, w.rope_base)), qt(_rope(k, pos, w.rope_base)), qt(v)
 
     def _after_attn(self, layer, x, attn):
         w = self.w
+        attn = self.quant(attn)
         x = x + attn.reshape(x.shape[0], -1) @ w.wo[layer]
         h = _rms_norm(x, w.norm2[layer])
         return x + (_silu(h @ w.w_gate[layer]) * (h @ w.w_up[layer])) @ w.w_down[layer]
 
     def _logits(self, x):
-        return _rms_norm(x, self.w.norm_f) @ self.w.lm_head.T
+        return self.quant(_rms_norm(x, self.w.norm_f)) @ self.w.lm_head.T
 
     # -- reference 1: whole-sequence causal forward, no cache ----------------------------
     def full_forward(self, tokens):
@@ -167,7 +184,7 @@ class ToyDecoderRef:
                                         prefix_len, node_offset, parent, scale)
                 tree_kv.append((k, v))
                 x = self._after_attn(layer, x, attn)
-            hidden = _rms_norm(x, w.norm_f)
+            hidden = self.quant(_rms_norm(x, w.norm_f))
             target_ids, _ = lmhead_argmax_ref(hidden, w.lm_head)
             alen, apath, otoks, _ = tree_accept_ref(node_offset, parent, draft_ids, target_ids, max_path)
             for layer in range(w.n_layers):

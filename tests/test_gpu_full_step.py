@@ -97,6 +97,55 @@ def test_greedy_losslessness_on_the_toy_decoder(kind, topology):
         assert all(l == full for l in lens[:-1])
 
 
+def _bf16_toy():
+    """A toy whose verification step runs on the matrix-core kernels (bf16, head_dim 128, 8 query /
+    2 kv heads, vocabulary 4096), with a seed and prompt for which the plain greedy stream of its
+    exact description (float64 arithmetic, bf16 rounding where the kernels' interfaces round) keeps
+    a top-1 margin of at least 1.0 logit at every step: about 3 % of the logits' spread and more
+    than an order of magnitude above what bf16 rounding noise (one step in the last place of some
+    attention outputs and hidden states) moves a logit by.  The seed search is deterministic."""
+    from oracle.toy_decoder import round_bf16
+    for seed in range(200):
+        w = W.make_toy_weights(seed, d=256, n_layers=2, Hq=8, Hkv=2, Dh=128, ffn=512, vocab=4096, lm_head_bf16=True)
+        ref = ToyDecoderRef(w, quant=round_bf16)
+        prompt = [int(t) for t in np.random.default_rng(seed).integers(0, w.vocab, size=24)]
+        stream, margin = ref.greedy_ar(prompt, 16)
+        if margin >= 1.0:
+            return w, prompt, stream
+    raise AssertionError("no seed with a wide enough margin")
+
+
+@pytest.fixture(scope="module")
+def bf16_toy():
+    return _bf16_toy()
+
+
+@pytest.mark.parametrize("kind", ["random", "replay", "corrupting"])
+@pytest.mark.parametrize("topology", ["tree60", "chain4", "single"])
+def test_greedy_losslessness_with_the_matrix_core_kernels_in_the_loop(bf16_toy, kind, topology):
+    """The draft-verify-accept-compact loop on the bf16 path (MFMA attention, both workgroup
+    shapes; MFMA LM head; acceptance; compaction into bf16 pools) emits the plain greedy stream of
+    the decoder's exact description.  "single" is plain autoregressive decoding through the same
+    kernels (one node per step)."""
+    from toy_gpu import ToyDecoderGpu
+    w, prompt, stream = bf16_toy
+    n_new = len(stream)
+    drafter = {
+        "random": W.random_drafter(1, w.vocab),
+        "replay": W.replay_drafter(1, w.vocab, len(prompt), stream),
+        "corrupting": W.replay_drafter(1, w.vocab, len(prompt), stream, wrong_after=(0, 4)),
+    }[kind]
+    tree = {"tree60": lambda s: W.seeded_tree(s), "chain4": lambda s: W.chain_tree(4),
+            "single": lambda s: W.chain_tree(1)}[topology]
+    table = np.random.default_rng(3).permutation(16)
+    gpu = ToyDecoderGpu(w, n_blocks=16, dtype="bf16")
+    out, lens = gpu.spec_decode(prompt, n_new, drafter, tree, table)
+    assert out == stream
+    if kind == "replay" and topology != "single":
+        full = 6 if topology == "tree60" else 4
+        assert all(l == full for l in lens[:-1])
+
+
 def test_full_step_replays_from_a_hip_graph(S):
     """The four calls only enqueue kernels on the caller's stream (no allocation, no memset, no
     host synchronisation), so a step can be captured into a HIP graph.  The graph is replayed

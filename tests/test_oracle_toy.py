@@ -59,3 +59,24 @@ def test_speculative_decoding_emits_the_autoregressive_stream(setup, kind, topol
         assert all(l == full for l in lens[:-1])  # a perfect drafter is accepted to full depth
     if kind == "random":
         assert np.mean(lens) < 1.5
+
+
+def test_bf16_rounding_hook():
+    """round_bf16 against torch's conversion (library routine), incl. ties and negative values; with
+    the hook on, cached decoding still equals the whole-sequence forward and speculative decoding
+    still emits the plain greedy stream (the hook rounds the same quantities in every mode)."""
+    import torch
+    from oracle.toy_decoder import round_bf16
+    x = np.concatenate([np.random.default_rng(0).standard_normal(2000) * 37.0,
+                        [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -1.0 - 2.0 ** -8, 0.0, 2.0 ** -130, 65280.0]])
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(round_bf16(x), want)
+    w = W.make_toy_weights(3, lm_head_bf16=True)
+    ref = ToyDecoderRef(w, quant=round_bf16)
+    prompt = [int(t) for t in np.random.default_rng(5).integers(0, w.vocab, size=12)]
+    stream, margin = ref.greedy_ar(prompt, 10)
+    full = ref.full_forward(prompt + stream[:-1])
+    assert [int(np.argmax(full[len(prompt) - 1 + i])) for i in range(10)] == stream
+    out, _ = ref.spec_decode(prompt, 10, W.random_drafter(2, w.vocab), lambda s: W.chain_tree(4),
+                             np.random.default_rng(1).permutation(8))
+    assert out == stream

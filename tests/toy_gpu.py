@@ -13,15 +13,19 @@ import paper_2509_18824_amd.step as S
 
 
 class ToyDecoderGpu:
-    def __init__(self, w, page=16, n_blocks=16, device="cuda"):
+    def __init__(self, w, page=16, n_blocks=16, device="cuda", dtype="f32"):
+        """dtype "bf16": q, k, v, the KV pools, the attention output and the LM head's inputs are
+        bf16 (the matrix-core kernels run); everything between the library calls stays fp32."""
         self.w, self.page, self.n_blocks, self.dev = w, page, n_blocks, device
+        self.dtype = dtype
+        self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
         f = lambda a: torch.tensor(a, dtype=torch.float32, device=device)
         self.embed = f(w.embed)
         self.layers = [dict(wq=f(w.wq[i]), wk=f(w.wk[i]), wv=f(w.wv[i]), wo=f(w.wo[i]), wg=f(w.w_gate[i]),
                             wu=f(w.w_up[i]), wd=f(w.w_down[i]), n1=f(w.norm1[i]), n2=f(w.norm2[i]))
                        for i in range(w.n_layers)]
         self.norm_f = f(w.norm_f)
-        self.lm_head = f(w.lm_head).contiguous()
+        self.lm_head = f(w.lm_head).to(self.tdt).contiguous()
         half = w.Dh // 2
         self.inv_freq = torch.tensor([w.rope_base ** (-i / half) for i in range(half)], dtype=torch.float64,
                                      device=device)
@@ -44,18 +48,18 @@ class ToyDecoderGpu:
         q = self._rope((h @ lw["wq"]).view(T, w.Hq, w.Dh), pos)
         k = self._rope((h @ lw["wk"]).view(T, w.Hkv, w.Dh), pos)
         v = (h @ lw["wv"]).view(T, w.Hkv, w.Dh)
-        return q.contiguous(), k.contiguous(), v.contiguous()
+        return q.to(self.tdt).contiguous(), k.to(self.tdt).contiguous(), v.to(self.tdt).contiguous()
 
     def _mlp(self, lw, x, attn):
-        x = x + attn.reshape(x.shape[0], -1) @ lw["wo"]
+        x = x + attn.float().reshape(x.shape[0], -1) @ lw["wo"]
         h = self._rms(x, lw["n2"])
         return x + (torch.nn.functional.silu(h @ lw["wg"]) * (h @ lw["wu"])) @ lw["wd"]
 
     def spec_decode(self, prompt, n_new, drafter, tree_for_step, block_table, algo=0):
         w, dev, page = self.w, self.dev, self.page
         bt = torch.tensor(np.asarray(block_table).reshape(1, -1), dtype=torch.int32, device=dev)
-        pools = [(torch.zeros((self.n_blocks, w.Hkv, page, w.Dh), device=dev),
-                  torch.zeros((self.n_blocks, w.Hkv, page, w.Dh), device=dev)) for _ in self.layers]
+        pools = [(torch.zeros((self.n_blocks, w.Hkv, page, w.Dh), device=dev, dtype=self.tdt),
+                  torch.zeros((self.n_blocks, w.Hkv, page, w.Dh), device=dev, dtype=self.tdt)) for _ in self.layers]
         toks = [int(t) for t in prompt]
         L = 0  # cached positions
         prefix_len = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -77,7 +81,7 @@ class ToyDecoderGpu:
             apath = torch.arange(n, dtype=torch.int32, device=dev).view(1, n).contiguous()
             for lw, (kp, vp) in zip(self.layers, pools):
                 q, k, v = self._qkv(lw, x, pos)
-                desc = S.make_desc("f32", 1, w.Hq, w.Hkv, w.Dh, page, bt.shape[1], self.n_blocks, n, n, scale,
+                desc = S.make_desc(self.dtype, 1, w.Hq, w.Hkv, w.Dh, page, bt.shape[1], self.n_blocks, n, n, scale,
                                    algo=algo)
                 d = S.DeviceInputs(q, k, v, kp, vp, bt, prefix_len, node_offset, parent)
                 attn, _ = S.tree_verify_attn(desc, d, want_lse=False)
@@ -99,7 +103,7 @@ class ToyDecoderGpu:
             draft_ids = torch.from_numpy(draft).to(dev)
             x = self.embed[draft_ids.long()]
             pos = torch.from_numpy(L + depth).to(dev)
-            desc = S.make_desc("f32", 1, w.Hq, w.Hkv, w.Dh, page, bt.shape[1], self.n_blocks, n, n, scale, algo=algo)
+            desc = S.make_desc(self.dtype, 1, w.Hq, w.Hkv, w.Dh, page, bt.shape[1], self.n_blocks, n, n, scale, algo=algo)
             tree_kv = []
             for lw, (kp, vp) in zip(self.layers, pools):
                 q, k, v = self._qkv(lw, x, pos)
@@ -107,7 +111,7 @@ class ToyDecoderGpu:
                 attn, _ = S.tree_verify_attn(desc, d, want_lse=False)
                 tree_kv.append(d)
                 x = self._mlp(lw, x, attn)
-            hidden = self._rms(x, self.norm_f).contiguous()
+            hidden = self._rms(x, self.norm_f).to(self.tdt).contiguous()
             target_ids, _ = S.lmhead_argmax(hidden, self.lm_head, want_max=False)
             alen, apath, otoks, _ = S.tree_accept(node_offset, parent, draft_ids, target_ids, max_path, n)
             new_len = None

@@ -380,7 +380,9 @@ class ToyWeights:
 
 
 def make_toy_weights(seed: int, d: int = 64, n_layers: int = 2, Hq: int = 4, Hkv: int = 1,
-                     Dh: int = 64, ffn: int = 256, vocab: int = 1000) -> ToyWeights:
+                     Dh: int = 64, ffn: int = 256, vocab: int = 1000, lm_head_bf16: bool = False) -> ToyWeights:
+    """``lm_head_bf16``: the LM-head matrix holds bf16-representable values (for the toy whose
+    verification step runs in bf16)."""
     rng = np.random.default_rng(seed * 16 + 11)
 
     def mat(i, o, gain=1.0):
@@ -400,5 +402,6 @@ def make_toy_weights(seed: int, d: int = 64, n_layers: int = 2, Hq: int = 4, Hkv
         norm1=[np.ones(d) for _ in range(n_layers)],
         norm2=[np.ones(d) for _ in range(n_layers)],
         norm_f=np.ones(d),
-        lm_head=(rng.standard_normal((vocab, d)) * 2.0).astype(np.float32).astype(np.float64),
+        lm_head=(lambda m: torch.from_numpy(m).to(torch.bfloat16).to(torch.float64).numpy() if lm_head_bf16
+                 else m.astype(np.float64))((rng.standard_normal((vocab, d)) * 2.0).astype(np.float32)),
     )
