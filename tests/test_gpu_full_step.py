@@ -123,8 +123,7 @@ def bf16_toy():
 @pytest.mark.parametrize("kind", ["random", "replay", "corrupting"])
 @pytest.mark.parametrize("topology", ["tree60", "chain4", "single"])
 def test_greedy_losslessness_with_the_matrix_core_kernels_in_the_loop(bf16_toy, kind, topology):
-    """The draft-verify-accept-compact loop on the bf16 path (MFMA attention, both workgroup
-    shapes; MFMA LM head; acceptance; compaction into bf16 pools) emits the plain greedy stream of
+    """The draft-verify-accept-compact loop on the bf16 path (MFMA attention; MFMA LM head; acceptance; compaction into bf16 pools) emits the plain greedy stream of
     the decoder's exact description.  "single" is plain autoregressive decoding through the same
     kernels (one node per step)."""
     from toy_gpu import ToyDecoderGpu
