@@ -26,21 +26,28 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # HBM traffic of one LM-head launch on this workload, from hardware counters (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB device copy in the same
 # run: `--copy-probe`).  Valid only for the kernel source it was measured on: keyed by the
-# first 16 hex digits of the SHA-256 of csrc/lmhead_mfma.hip, anything else reports null.
+# first 16 hex digits of the SHA-256 over csrc/lmhead_mfma.hip followed by
+# csrc/mfma_gemm_tile.inc (the tile loop the kernel includes); anything else reports null.
+# "tree": the 960-row launch of the headline step; "chain8": the 128-row launch of the chain run.
 LMHEAD_TRAFFIC = {
-    "8d9e67b829a12391": {"fetch_bytes": 1.8464e9, "write_bytes": 1.9e5, "bytes": 1.8466e9,
-                         "algorithmic_bytes": 152064 * 3584 * 2 + 960 * 3584 * 2},
+    "5590a872aae69250": {
+        "tree": {"fetch_bytes": 1.8424e9, "write_bytes": 1.9e5, "bytes": 1.8426e9,
+                 "algorithmic_bytes": 152064 * 3584 * 2 + 960 * 3584 * 2},
+        "chain8": {"fetch_bytes": 1.1139e9, "write_bytes": 3.5e4, "bytes": 1.1140e9,
+                   "algorithmic_bytes": 152064 * 3584 * 2 + 128 * 3584 * 2},
+    },
 }
 
 
-def _lmhead_traffic():
+def _lmhead_traffic(which="tree"):
     import hashlib
-    path = os.path.join(ROOT, "paper_2509_18824_amd", "csrc", "lmhead_mfma.hip")
+    h = hashlib.sha256()
     try:
-        key = hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+        for name in ("lmhead_mfma.hip", "mfma_gemm_tile.inc"):
+            h.update(open(os.path.join(ROOT, "paper_2509_18824_amd", "csrc", name), "rb").read())
     except OSError:
         return None
-    return LMHEAD_TRAFFIC.get(key)
+    return (LMHEAD_TRAFFIC.get(h.hexdigest()[:16]) or {}).get(which)
 
 
 def _events(n):
@@ -482,8 +489,8 @@ def main():
             "peak": PEAK_BF16_TFLOPS if M >= 512 else PEAK_HBM_GBS,
             "unit": "TFLOP/s" if M >= 512 else "GB/s",
             "frac": (lm_tflops / PEAK_BF16_TFLOPS) if M >= 512 else lm_bytes / (ms_lm * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "traffic": (_lmhead_traffic() or {}).get("bytes") if args.tree == "tree" else None,
-            "traffic_detail": _lmhead_traffic() if args.tree == "tree" else None,
+            "traffic": (_lmhead_traffic(args.tree) or {}).get("bytes"),
+            "traffic_detail": _lmhead_traffic(args.tree),
             "ms": ms_lm,
         },
         "kernels_ms": {"tree_verify_attn": ms_attn, "lmhead_argmax": ms_lm, "tree_accept": ms_acc,
@@ -518,6 +525,7 @@ def main():
             "lmhead_bound": "hbm" if M2 < 512 else "mfma",
             "lmhead_GBps": lm_gbps, "lmhead_frac_of_hbm_peak": lm_gbps / PEAK_HBM_GBS,
             "lmhead_TFLOPs": 2.0 * M2 * K * V / (r2["ms_lm"] * 1e-3) / 1e12,
+            "lmhead_traffic": (_lmhead_traffic(other) or {}).get("bytes"),
             "kv_bytes": kv2, "kv_GBps": kv2 / (r2["ms_attn"] * 1e-3) / 1e9,
             "kv_frac_of_hbm_peak": kv2 / (r2["ms_attn"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
         }
