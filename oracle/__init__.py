@@ -16,6 +16,7 @@ target's own greedy stream):
   kv_compaction.kv_compact_ref     append the accepted nodes' K/V to the paged cache
   stochastic_acceptance.tree_accept_sample_ref   sampling acceptance (speculative sampling over a tree)
   projections.qkv_rope_project_ref / linear_ref / tree_positions_ref   the projections around the attention
+  draft_tree.topk_logprob_ref / DraftTreeRef / build_draft_tree_ref   the draft tree's construction
   toy_decoder.ToyDecoderRef        small random-weight decoder: greedy autoregressive stream and
                                    greedy speculative decoding built from the four functions above
 
@@ -31,6 +32,7 @@ from .acceptance import tree_accept_ref
 from .kv_compaction import kv_compact_ref
 from .toy_decoder import ToyDecoderRef
 from .stochastic_acceptance import tree_accept_sample_ref
+from .draft_tree import topk_logprob_ref, DraftTreeRef, build_draft_tree_ref
 from .projections import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref
 
 __all__ = [
@@ -46,4 +48,7 @@ __all__ = [
     "rope_ref",
     "qkv_rope_project_ref",
     "linear_ref",
+    "topk_logprob_ref",
+    "DraftTreeRef",
+    "build_draft_tree_ref",
 ]
