@@ -269,6 +269,76 @@ int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *
                       const int32_t *accept_len, const int32_t *accept_path, int32_t max_path,
                       int32_t *out_slots, int32_t *new_len, void *stream);
 
+/*
+ * Construction of the draft tree from the draft model's outputs: the step before the
+ * verification (the paper drafts in the EAGLE-3 manner, Section 3.1, and leaves the arrangement of
+ * the drafted tokens open; its measurements use chains, Section 4.2).  This is the dynamic tree of
+ * that line of work: the draft model runs level by level; a node's K most probable next tokens are
+ * its candidate children, a candidate's score is the log-probability of its whole path; of each
+ * level's candidates the K best are run again; after T levels all candidates are re-ranked and
+ * the n - 1 best form, with the root, the tree that the target verifies.
+ *
+ * hb_topk_logprob: per row of logits the k best tokens, ordered by (logit descending, token id
+ * ascending; -0 equals +0), and their log-probabilities logit - logsumexp(row) (float32, never
+ * above 0).  The ids depend on comparisons only and are exact; NaN logits rank as -inf.
+ *   dtype      HB_F32 or HB_BF16 (type of logits)
+ *   logits     device [M, V] row-major
+ *   out_ids    device int32 [M, k];  out_logp  device float32 [M, k]
+ *   workspace  device, hb_topk_logprob_workspace_bytes(M, V, k) bytes, 8-byte aligned
+ * Errors: INVALID_ARG (M < 0, V <= 0, k < 1, k > V, NULL pointers), UNSUPPORTED (k > 32),
+ * WORKSPACE, DEVICE.  M == 0 is a no-op.
+ */
+int32_t hb_topk_logprob(int32_t dtype, int32_t M, int32_t V, int32_t k, const void *logits, int32_t *out_ids,
+                        float *out_logp, void *workspace, size_t workspace_bytes, void *stream);
+
+size_t hb_topk_logprob_workspace_bytes(int32_t M, int32_t V, int32_t k);
+
+/* Candidates a pool holds per sequence after T levels: K + (T - 1) K^2. */
+int32_t hb_draft_tree_candidates(int32_t K, int32_t T);
+
+/*
+ * One level of the draft tree.  Level 0 takes the root's K children (F = 1 row per sequence):
+ * candidates 0 .. K-1, all of them form the frontier.  Level l >= 1 takes the K children of each
+ * of the K frontier nodes (F = K rows per sequence, in frontier order): candidate
+ * K + (l - 1) K^2 + f K + j for frontier slot f and child rank j, with
+ *   score = score(parent) + child_logp      (ONE float32 addition, round to nearest; NaN -> -inf)
+ * and the K best of them (higher score first, equal scores: lower candidate index) become the
+ * new frontier, best first.
+ *   child_ids, child_logp   device int32 / float32 [B, F, K] (hb_topk_logprob's outputs for the
+ *                           B * F rows the draft model just ran on; log-probabilities <= 0)
+ *   cand_score, cand_token, cand_parent   device float32 / int32 / int32 [B, C], C =
+ *                           hb_draft_tree_candidates(K, T): the pool, owned by the caller, appended
+ *                           to by every level (cand_parent = candidate index of the parent, -1 = root)
+ *   frontier       device int32 [B, K]: in (level >= 1) the candidate indices the rows belong to,
+ *                  out the new frontier; frontier_slot device int32 [B, K]: out, the slot f of
+ *                  each new frontier node's parent (which row of this level it descends from)
+ * Errors: INVALID_ARG (B < 0, K < 1, T < 1, level outside [0, T), NULL pointers), UNSUPPORTED
+ * (K > 32), DEVICE.  B == 0 is a no-op.
+ */
+int32_t hb_tree_grow(int32_t B, int32_t K, int32_t T, int32_t level, const int32_t *child_ids,
+                     const float *child_logp, float *cand_score, int32_t *cand_token, int32_t *cand_parent,
+                     int32_t *frontier, int32_t *frontier_slot, void *stream);
+
+/*
+ * Re-ranking: of the C = hb_draft_tree_candidates(K, T) candidates of each sequence the
+ * n_nodes - 1 best are kept (order as in hb_tree_grow) and numbered 1 .. n_nodes-1 in candidate
+ * order, which puts every parent before its children; node 0 is the root.  Log-probabilities
+ * <= 0 make scores fall along a path, so a kept node's parent is kept; otherwise (malformed
+ * input) the node is hung under the root.  Outputs are in the verification calls' layout:
+ *   root_token   device int32 [B]: the pending committed token of each sequence
+ *   node_offset  device int32 [B + 1] = b * n_nodes
+ *   parent, draft_ids, depth   device int32 [B * n_nodes] (tree-local parents, -1 for the root)
+ *   anc_mask     device uint64 [B * n_nodes]: bit j of entry i set iff node j is i or an ancestor of i
+ *   node_cand    device int32 [B * n_nodes]: the node's candidate index (-1 for the root)
+ *   node_score   device float32 [B * n_nodes]: the node's path log-probability (0 for the root)
+ * Errors: INVALID_ARG (n_nodes < 1 or n_nodes - 1 > C, NULL pointers), UNSUPPORTED (n_nodes > 64,
+ * K > 32, C > 4096), DEVICE.  B == 0 is a no-op.
+ */
+int32_t hb_tree_finalize(int32_t B, int32_t K, int32_t T, int32_t n_nodes, const float *cand_score,
+                         const int32_t *cand_token, const int32_t *cand_parent, const int32_t *root_token,
+                         int32_t *node_offset, int32_t *parent, int32_t *draft_ids, int32_t *depth,
+                         uint64_t *anc_mask, int32_t *node_cand, float *node_score, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,6 +26,11 @@ from .binding import (
     hb_tree_accept_sample,
     hb_tree_accept_sample_workspace_bytes,
     hb_kv_compact,
+    hb_topk_logprob,
+    hb_topk_logprob_workspace_bytes,
+    hb_draft_tree_candidates,
+    hb_tree_grow,
+    hb_tree_finalize,
     HB_F32,
     HB_BF16,
     HB_ATTN_AUTO,

@@ -78,6 +78,16 @@ def _load():
     lib.hb_tree_accept_sample.argtypes = [i32, i32, i32] + [p] * 7 + [i32] + [p] * 4 + [p, sz, p]
     lib.hb_tree_accept_sample_workspace_bytes.restype = sz
     lib.hb_tree_accept_sample_workspace_bytes.argtypes = [i32, i32]
+    lib.hb_topk_logprob.restype = i32
+    lib.hb_topk_logprob.argtypes = [i32, i32, i32, i32, p, p, p, p, sz, p]
+    lib.hb_topk_logprob_workspace_bytes.restype = sz
+    lib.hb_topk_logprob_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.hb_draft_tree_candidates.restype = i32
+    lib.hb_draft_tree_candidates.argtypes = [i32, i32]
+    lib.hb_tree_grow.restype = i32
+    lib.hb_tree_grow.argtypes = [i32, i32, i32, i32] + [p] * 7 + [p]
+    lib.hb_tree_finalize.restype = i32
+    lib.hb_tree_finalize.argtypes = [i32, i32, i32, i32] + [p] * 11 + [p]
     lib.hb_kv_compact.restype = i32
     lib.hb_kv_compact.argtypes = [C.POINTER(AttnDesc)] + [p] * 9 + [i32, p, p, p]
     return lib
@@ -223,6 +233,36 @@ def hb_tree_accept_sample(B: int, max_nodes_per_tree: int, node_offset, parent, 
                                      _ptr(p_target), _ptr(q_draft), _ptr(u_accept), _ptr(u_bonus), max_path,
                                      _ptr(accept_len), _ptr(accept_path), _ptr(out_tokens), _ptr(bonus_id),
                                      _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def hb_topk_logprob_workspace_bytes(M: int, V: int, k: int) -> int:
+    return int(lib.hb_topk_logprob_workspace_bytes(M, V, k))
+
+
+def hb_topk_logprob(logits, k: int, out_ids, out_logp, workspace, stream=None) -> None:
+    if logits.dtype not in (torch.float32, torch.bfloat16) or logits.dim() != 2 or not logits.is_contiguous():
+        raise ValueError("logits must be a contiguous float32 or bfloat16 [M, V] tensor")
+    M, V = logits.shape
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_topk_logprob(HB_BF16 if logits.dtype == torch.bfloat16 else HB_F32, M, V, k, _ptr(logits),
+                               _ptr(out_ids), _ptr(out_logp), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def hb_draft_tree_candidates(K: int, T: int) -> int:
+    return int(lib.hb_draft_tree_candidates(K, T))
+
+
+def hb_tree_grow(B: int, K: int, T: int, level: int, child_ids, child_logp, cand_score, cand_token, cand_parent,
+                 frontier, frontier_slot, stream=None) -> None:
+    _check(lib.hb_tree_grow(B, K, T, level, _ptr(child_ids), _ptr(child_logp), _ptr(cand_score), _ptr(cand_token),
+                            _ptr(cand_parent), _ptr(frontier), _ptr(frontier_slot), _stream(stream)))
+
+
+def hb_tree_finalize(B: int, K: int, T: int, n_nodes: int, cand_score, cand_token, cand_parent, root_token,
+                     node_offset, parent, draft_ids, depth, anc_mask, node_cand, node_score, stream=None) -> None:
+    _check(lib.hb_tree_finalize(B, K, T, n_nodes, _ptr(cand_score), _ptr(cand_token), _ptr(cand_parent),
+                                _ptr(root_token), _ptr(node_offset), _ptr(parent), _ptr(draft_ids), _ptr(depth),
+                                _ptr(anc_mask), _ptr(node_cand), _ptr(node_score), _stream(stream)))
 
 
 def hb_kv_compact(desc: AttnDesc, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset,

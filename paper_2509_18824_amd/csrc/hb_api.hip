@@ -383,6 +383,68 @@ int32_t hb_tree_accept_sample(int32_t B, int32_t max_nodes_per_tree, int32_t V, 
   return HB_OK;
 }
 
+size_t hb_topk_logprob_workspace_bytes(int32_t M, int32_t V, int32_t k) {
+  return (M > 0 && V > 0 && k > 0) ? topk_workspace_bytes(M, V, k) : 0;
+}
+
+int32_t hb_topk_logprob(int32_t dtype, int32_t M, int32_t V, int32_t k, const void *logits, int32_t *out_ids,
+                        float *out_logp, void *workspace, size_t workspace_bytes, void *stream) {
+  if (dtype != HB_F32 && dtype != HB_BF16) return fail(HB_ERR_INVALID_ARG, "dtype %d", dtype);
+  if (M < 0 || V <= 0 || k < 1 || k > V) return fail(HB_ERR_INVALID_ARG, "need M >= 0, V > 0, 1 <= k <= V");
+  if (k > 32) return fail(HB_ERR_UNSUPPORTED, "k %d: at most 32 tokens per row", k);
+  if (M > 65535) return fail(HB_ERR_UNSUPPORTED, "M %d: at most 65535 rows per call", M);
+  if (M == 0) return HB_OK;
+  if (!logits || !out_ids || !out_logp) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if ((uintptr_t)logits % (dtype == HB_BF16 ? 2 : 4)) return fail(HB_ERR_INVALID_ARG, "logits are not aligned to their type");
+  const size_t need = hb_topk_logprob_workspace_bytes(M, V, k);
+  if (!workspace || workspace_bytes < need)
+    return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  if ((uintptr_t)workspace % 8) return fail(HB_ERR_WORKSPACE, "workspace must be 8-byte aligned");
+  HB_HIP_TRY(launch_topk_logprob(dtype, M, V, k, logits, out_ids, out_logp, workspace, (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_draft_tree_candidates(int32_t K, int32_t T) {
+  if (K < 1 || T < 1 || K > 32 || T > 64) return 0;
+  return K + (T - 1) * K * K;
+}
+
+int32_t hb_tree_grow(int32_t B, int32_t K, int32_t T, int32_t level, const int32_t *child_ids,
+                     const float *child_logp, float *cand_score, int32_t *cand_token, int32_t *cand_parent,
+                     int32_t *frontier, int32_t *frontier_slot, void *stream) {
+  if (B < 0 || K < 1 || T < 1 || level < 0 || level >= T)
+    return fail(HB_ERR_INVALID_ARG, "need B >= 0, K >= 1, T >= 1, 0 <= level < T");
+  if (K > 32 || T > 64) return fail(HB_ERR_UNSUPPORTED, "K %d, T %d: at most 32 children per node and 64 levels", K, T);
+  if (B == 0) return HB_OK;
+  if (!child_ids || !child_logp || !cand_score || !cand_token || !cand_parent || !frontier || !frontier_slot)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  HB_HIP_TRY(launch_tree_grow(B, K, level, hb_draft_tree_candidates(K, T), child_ids, child_logp, cand_score,
+                              cand_token, cand_parent, frontier, frontier_slot, (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_tree_finalize(int32_t B, int32_t K, int32_t T, int32_t n_nodes, const float *cand_score,
+                         const int32_t *cand_token, const int32_t *cand_parent, const int32_t *root_token,
+                         int32_t *node_offset, int32_t *parent, int32_t *draft_ids, int32_t *depth,
+                         uint64_t *anc_mask, int32_t *node_cand, float *node_score, void *stream) {
+  if (B < 0 || K < 1 || T < 1) return fail(HB_ERR_INVALID_ARG, "need B >= 0, K >= 1, T >= 1");
+  if (K > 32 || T > 64) return fail(HB_ERR_UNSUPPORTED, "K %d, T %d: at most 32 children per node and 64 levels", K, T);
+  const int32_t C = hb_draft_tree_candidates(K, T);
+  if (C > 4096) return fail(HB_ERR_UNSUPPORTED, "%d candidates per sequence: at most 4096", C);
+  if (n_nodes < 1 || n_nodes - 1 > C) return fail(HB_ERR_INVALID_ARG, "n_nodes %d with %d candidates", n_nodes, C);
+  if (n_nodes > 64) return fail(HB_ERR_UNSUPPORTED, "n_nodes %d: trees of more than 64 nodes are not supported", n_nodes);
+  if ((int64_t)B * n_nodes > INT32_MAX) return fail(HB_ERR_INVALID_ARG, "B * n_nodes overflows int32");
+  if (B == 0) return HB_OK;
+  if (!cand_score || !cand_token || !cand_parent || !root_token || !node_offset || !parent || !draft_ids || !depth ||
+      !anc_mask || !node_cand || !node_score)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  HB_HIP_TRY(launch_tree_finalize(B, C, n_nodes, cand_score, cand_token, cand_parent, root_token, node_offset, parent,
+                                  draft_ids, depth, (unsigned long long *)anc_mask, node_cand, node_score,
+                                  (hipStream_t)stream));
+  return HB_OK;
+}
+
 int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *v_tree,
                       void *k_pool, void *v_pool, const int32_t *block_table,
                       const int32_t *prefix_len, const int32_t *node_offset,

@@ -108,6 +108,16 @@ hipError_t launch_tree_accept_sample(int32_t B, int32_t max_nodes, int32_t V, co
                                      const float *q_draft, const uint32_t *u_accept, const uint32_t *u_bonus,
                                      int32_t max_path, int32_t *accept_len, int32_t *accept_path,
                                      int32_t *out_tokens, int32_t *bonus_id, uint32_t *work, hipStream_t s);
+size_t topk_workspace_bytes(int32_t M, int32_t V, int32_t k);
+hipError_t launch_topk_logprob(int32_t dtype, int32_t M, int32_t V, int32_t k, const void *logits, int32_t *out_ids,
+                               float *out_logp, void *work, hipStream_t s);
+hipError_t launch_tree_grow(int32_t B, int32_t K, int32_t level, int32_t C, const int32_t *child_ids,
+                            const float *child_logp, float *cand_score, int32_t *cand_token, int32_t *cand_parent,
+                            int32_t *frontier, int32_t *frontier_slot, hipStream_t s);
+hipError_t launch_tree_finalize(int32_t B, int32_t C, int32_t n, const float *cand_score, const int32_t *cand_token,
+                                const int32_t *cand_parent, const int32_t *root_token, int32_t *node_offset,
+                                int32_t *parent, int32_t *draft_ids, int32_t *depth, unsigned long long *anc,
+                                int32_t *node_cand, float *node_score, hipStream_t s);
 hipError_t launch_kv_compact(const hb_attn_desc &d, const void *k_tree, const void *v_tree,
                              void *k_pool, void *v_pool, const int32_t *block_table,
                              const int32_t *prefix_len, const int32_t *node_offset,

@@ -104,6 +104,53 @@ def tree_accept_sample(node_offset, parent, draft_ids, p_target, q_draft, u_acce
     return accept_len, accept_path, out_tokens, bonus
 
 
+def topk_logprob(logits, k):
+    """ids int32 [M, k], logp float32 [M, k] of the k best tokens of every row."""
+    M, V = logits.shape
+    dev = logits.device
+    ids = torch.empty((M, k), dtype=torch.int32, device=dev)
+    logp = torch.empty((M, k), dtype=torch.float32, device=dev)
+    ws = alloc_workspace(max(8, hb.hb_topk_logprob_workspace_bytes(M, V, k)), dev)
+    hb.hb_topk_logprob(logits, k, ids, logp, ws)
+    return ids, logp
+
+
+class DraftTreeBuilder:
+    """Device state of the draft tree's construction for a batch: the candidate pool and the
+    frontier.  ``grow`` takes the top-k outputs of the rows the draft model just ran on (the
+    root at level 0, then the frontier nodes in order); ``finalize`` emits the tree in the
+    verification calls' layout."""
+
+    def __init__(self, B: int, K: int, T: int, device="cuda"):
+        self.B, self.K, self.T, self.level = B, K, T, 0
+        C = hb.hb_draft_tree_candidates(K, T)
+        if C <= 0:
+            raise ValueError("unsupported K / T")
+        self.C = C
+        self.cand_score = torch.zeros((B, C), dtype=torch.float32, device=device)
+        self.cand_token = torch.zeros((B, C), dtype=torch.int32, device=device)
+        self.cand_parent = torch.full((B, C), -1, dtype=torch.int32, device=device)
+        self.frontier = torch.zeros((B, K), dtype=torch.int32, device=device)
+        self.frontier_slot = torch.zeros((B, K), dtype=torch.int32, device=device)
+
+    def grow(self, child_ids, child_logp):
+        hb.hb_tree_grow(self.B, self.K, self.T, self.level, child_ids, child_logp, self.cand_score, self.cand_token,
+                        self.cand_parent, self.frontier, self.frontier_slot)
+        self.level += 1
+        return self.frontier, self.frontier_slot
+
+    def finalize(self, n_nodes: int, root_token):
+        B, dev = self.B, self.cand_score.device
+        i32 = lambda *shape: torch.empty(shape, dtype=torch.int32, device=dev)
+        out = dict(node_offset=i32(B + 1), parent=i32(B * n_nodes), draft_ids=i32(B * n_nodes), depth=i32(B * n_nodes),
+                   anc_mask=torch.empty(B * n_nodes, dtype=torch.int64, device=dev), node_cand=i32(B * n_nodes),
+                   node_score=torch.empty(B * n_nodes, dtype=torch.float32, device=dev))
+        hb.hb_tree_finalize(B, self.K, self.T, n_nodes, self.cand_score, self.cand_token, self.cand_parent, root_token,
+                            out["node_offset"], out["parent"], out["draft_ids"], out["depth"], out["anc_mask"],
+                            out["node_cand"], out["node_score"])
+        return out
+
+
 def kv_compact(desc, dev: DeviceInputs, accept_len, accept_path):
     B, max_path = accept_path.shape
     out_slots = torch.empty((B, max_path), dtype=torch.int32, device=accept_path.device)

@@ -110,3 +110,25 @@ def test_lmhead_accept_compact_argument_errors():
     assert L.hb_kv_compact(None, p, p, p, p, p, p, p, p, p, 6, None, None, None) == 1
     assert L.hb_kv_compact(C.byref(d), C.c_void_p(0x1002), p, p, p, p, p, p, p, p, 6, None, None, None) == 1
     assert "aligned" in hb.hb_last_error()
+
+
+def test_draft_tree_argument_errors():
+    L, p = hb.lib, C.c_void_p(0x1000)
+    assert L.hb_draft_tree_candidates(10, 5) == 410 and L.hb_draft_tree_candidates(1, 5) == 5
+    assert L.hb_draft_tree_candidates(33, 2) == 0
+    assert L.hb_topk_logprob(hb.HB_F32, 4, 100, 0, p, p, p, p, 1 << 20, None) == 1
+    assert L.hb_topk_logprob(hb.HB_F32, 4, 100, 101, p, p, p, p, 1 << 20, None) == 1
+    assert L.hb_topk_logprob(hb.HB_F32, 4, 100, 33, p, p, p, p, 1 << 20, None) == 2
+    assert L.hb_topk_logprob(7, 4, 100, 5, p, p, p, p, 1 << 20, None) == 1
+    assert L.hb_topk_logprob(hb.HB_F32, 4, 100, 5, None, p, p, p, 1 << 20, None) == 1
+    assert L.hb_topk_logprob(hb.HB_F32, 4, 100, 5, p, p, p, p, 8, None) == 3
+    assert L.hb_topk_logprob(hb.HB_F32, 0, 100, 5, None, None, None, None, 0, None) == 0
+    assert hb.hb_topk_logprob_workspace_bytes(160, 152064, 10) == 160 * 10 * (8 + 80)
+    assert L.hb_tree_grow(2, 10, 5, 5, p, p, p, p, p, p, p, None) == 1  # level outside [0, T)
+    assert L.hb_tree_grow(2, 33, 5, 0, p, p, p, p, p, p, p, None) == 2
+    assert L.hb_tree_grow(2, 10, 5, 0, p, None, p, p, p, p, p, None) == 1
+    assert L.hb_tree_grow(0, 10, 5, 0, None, None, None, None, None, None, None, None) == 0
+    assert L.hb_tree_finalize(2, 10, 5, 65, p, p, p, p, p, p, p, p, p, p, p, None) == 2
+    assert L.hb_tree_finalize(2, 2, 2, 8, p, p, p, p, p, p, p, p, p, p, p, None) == 1  # 7 > 6 candidates
+    assert L.hb_tree_finalize(2, 32, 6, 60, p, p, p, p, p, p, p, p, p, p, p, None) == 2  # 5152 candidates
+    assert L.hb_tree_finalize(2, 10, 5, 60, p, p, p, None, p, p, p, p, p, p, p, None) == 1

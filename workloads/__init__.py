@@ -7,6 +7,7 @@ GPU library without coupling them.
 """
 from .trees import chain_tree, seeded_tree, tree_depths, validate_parents
 from .drafters import random_drafter, replay_drafter
+from .draft import make_draft_logits
 from .configs import (
     CONFIG_NAMES,
     VerifyInputs,
@@ -35,4 +36,5 @@ __all__ = [
     "widen",
     "random_drafter",
     "replay_drafter",
+    "make_draft_logits",
 ]
