@@ -332,6 +332,66 @@ def achievable_peaks():
     return out
 
 
+def bench_draft_tree(steps, warmup, B=16, K=10, T=5, N=60, V=152064):
+    """Construction of the 60-node draft trees of the batch-16 workload from synthetic draft
+    logits: per level one top-k pass over the logits of the rows the draft model ran on (16 at the
+    root level, then 160) and one hb_tree_grow; hb_tree_finalize at the end.  The draft model's
+    own forward passes are not part of it.  The top-k pass is bound by HBM (it reads every logit
+    once); three sets of logits rotate so that a pass does not find them in the last-level cache."""
+    import torch
+    import workloads as W
+    import paper_2509_18824_amd as hb
+    import paper_2509_18824_amd.step as S
+
+    sets = [torch.from_numpy(W.make_draft_logits(70 + i, B * K, V)).cuda() for i in range(3)]
+    roots = [x[:B].contiguous() for x in sets]
+    ids0, lp0 = (torch.empty((B, K), dtype=t, device="cuda") for t in (torch.int32, torch.float32))
+    ids1, lp1 = (torch.empty((B * K, K), dtype=t, device="cuda") for t in (torch.int32, torch.float32))
+    ws = S.alloc_workspace(hb.hb_topk_logprob_workspace_bytes(B * K, V, K))
+    builder = S.DraftTreeBuilder(B, K, T)
+    root_token = torch.arange(B, dtype=torch.int32, device="cuda")
+    n = B * N
+    i32 = lambda m: torch.empty(m, dtype=torch.int32, device="cuda")
+    outs = (i32(B + 1), i32(n), i32(n), i32(n), torch.empty(n, dtype=torch.int64, device="cuda"), i32(n),
+            torch.empty(n, dtype=torch.float32, device="cuda"))
+
+    def build(i, ev=None):
+        for level in range(T):
+            x = roots[(i + level) % 3] if level == 0 else sets[(i + level) % 3]
+            ids, lp = (ids0, lp0) if level == 0 else (ids1, lp1)
+            if ev is not None and level == 1:
+                ev[0].record()
+            hb.hb_topk_logprob(x, K, ids, lp, ws)
+            if ev is not None and level == 1:
+                ev[1].record()
+            hb.hb_tree_grow(B, K, T, level, ids, lp, builder.cand_score, builder.cand_token, builder.cand_parent,
+                            builder.frontier, builder.frontier_slot)
+        hb.hb_tree_finalize(B, K, T, N, builder.cand_score, builder.cand_token, builder.cand_parent, root_token, *outs)
+
+    for i in range(warmup):
+        build(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        build(i)
+    torch.cuda.synchronize()
+    ms_build = (time.perf_counter() - t0) * 1e3 / steps
+    ev = _events(steps)
+    for i, e in enumerate(ev):
+        build(i, e)
+    torch.cuda.synchronize()
+    ms_topk = _mean_ms(ev)
+    level_bytes = B * K * V * 4
+    return {
+        "what": f"{B} trees of {N} nodes from {K} children per node over {T} levels, vocabulary {V}, float32 logits; "
+                "top-k + grow per level, finalize; the draft model's forward passes are not included",
+        "ms_per_build": ms_build, "trees_per_s": B / (ms_build * 1e-3),
+        "topk_level_ms": ms_topk, "topk_level_rows": B * K, "topk_level_bytes": level_bytes,
+        "topk_GBps": level_bytes / (ms_topk * 1e-3) / 1e9,
+        "topk_frac_of_hbm_peak": level_bytes / (ms_topk * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
+
+
 def bench_layer_stack(inp, desc, dv, lm_weight, draft_np, n_steps, n_layers=28):
     """The step at a realistic depth: 28 layers, each QKV projection + rotary embedding ->
     tree-verify attention over its own KV pools (2.3 GB in all, so every layer streams its KV from
@@ -417,6 +477,7 @@ def main():
                     "ragged-batch and long-context workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stack", action="store_true", help="skip the 28-layer variant of the step")
+    ap.add_argument("--no-draft-tree", action="store_true", help="skip the draft tree's construction")
     ap.add_argument("--no-chain", action="store_true", help="skip the 8-node-chain run of the step")
     ap.add_argument("--no-achievable", action="store_true", help="skip the library-kernel yardsticks")
     ap.add_argument("--no-parity", action="store_true", help="skip the comparison with the CPU oracle")
@@ -537,6 +598,9 @@ def main():
         del wdev
         torch.cuda.empty_cache()
         result["attention_only"] = [bench_attention_only(c, max(args.steps, 20), args.warmup) for c in (2, 3)]
+    if not args.no_draft_tree:
+        torch.cuda.empty_cache()
+        result["draft_tree"] = bench_draft_tree(max(args.steps, 20), args.warmup)
     if not args.no_achievable:
         torch.cuda.empty_cache()
         result["achievable"] = achievable_peaks()

@@ -4,10 +4,10 @@
 //
 //   topk_logprob   per row of draft logits: the k best tokens (ties: lower id) and their
 //                  log-probabilities.  Pass 1, one workgroup per (row, chunk of the vocabulary):
-//                  the chunk is read from memory once into LDS, reduced to its maximum and its
-//                  sum of exponentials, and its k best entries are picked in k rounds of a
-//                  workgroup-wide maximum over order-preserving integer keys.  Pass 2, one
-//                  workgroup per row: the same selection over the chunks' winners.
+//                  the chunk is read from memory once, reduced to its maximum and its sum of
+//                  exponentials, and its k best entries are picked as order-preserving integer
+//                  keys.  Pass 2, one workgroup per row: the k best of the chunks' winners and
+//                  the row's logsumexp from the chunks' partials.
 //   tree_grow      one level: scores of the new candidates (ONE float32 addition each,
 //                  parent's score + log-probability), the K best of them become the frontier.
 //   tree_finalize  re-ranking of all candidates, the N - 1 best are kept and numbered in
@@ -62,75 +62,158 @@ __device__ __forceinline__ float wg_sum_f(float x, float *red) {
 // key of (value, index): larger value first, then lower index; -0 counts as +0
 __device__ __forceinline__ unsigned long long sel_key(float v, uint32_t idx) { return argmax_key(v + 0.f, idx); }
 
-struct Partial {  // one per (row, chunk), followed in memory by k keys
-  float max, sum;
-};
-
-// The k best keys among vals[0 .. n) (index of element i is base + i), best first, into out[0 .. k);
-// missing ones (n < k) are 0.  Every thread returns with out[] complete and visible.
-__device__ __forceinline__ void select_k(const float *vals, int n, uint32_t base, int k, unsigned long long *out,
-                                         unsigned long long *red) {
-  unsigned long long last = ~0ull;
-  for (int r = 0; r < k; ++r) {
-    unsigned long long best = 0ull;
-    for (int i = threadIdx.x; i < n; i += kThreads) {
-      const unsigned long long key = sel_key(vals[i], base + (uint32_t)i);
-      best = (key < last && key > best) ? key : best;
-    }
-    best = wg_max_key(best, red);
-    if (threadIdx.x == 0) out[r] = best;
-    last = best ? best : 0ull;  // nothing left: the remaining rounds find nothing either
+// The k largest of the distinct keys[0 .. cnt) into win[0 .. k), largest first, by counting: the
+// rank of a key is the number of keys above it.  Slots without a key (cnt < k) are 0.  The caller
+// has made keys[] visible; win[] is visible to every thread on return.
+__device__ __forceinline__ void rank_select(const unsigned long long *keys, int cnt, int k, unsigned long long *win) {
+  if (threadIdx.x < k) win[threadIdx.x] = 0ull;
+  __syncthreads();
+  for (int i = threadIdx.x; i < cnt; i += kThreads) {
+    const unsigned long long mine = keys[i];
+    int rank = 0;
+#pragma unroll 8
+    for (int j = 0; j < cnt; ++j) rank += keys[j] > mine ? 1 : 0;
+    if (rank < k) win[rank] = mine;
   }
   __syncthreads();
 }
 
+struct Partial {  // one per (row, chunk), followed in memory by k keys
+  float max, sum;
+};
+
+constexpr int kChunkMax = 16384;            // logits per chunk: 64 per thread, held in registers
+constexpr int kPerThread = kChunkMax / kThreads;
+constexpr int kListCap = 2048;              // candidates that pass the threshold
+
+// Position inside the chunk of a thread's j-th value, or n when the thread has no such value.
+// Vector layout (rows whose chunk starts 16-byte aligned; loads of PER values, consecutive lanes
+// consecutive loads): value e of load q sits at (q * 256 + tid) * PER + e while that load lies
+// inside the n_full full vectors of the chunk; value kPerThread is the thread's share of the up
+// to PER - 1 values behind them.  Scalar layout: value j sits at j * 256 + tid.
+template <int PER>
+__device__ __forceinline__ int pos_of(bool vec, int j, int n, int n_full) {
+  const int tid = (int)threadIdx.x;
+  if (!vec) return j < kPerThread ? min(n, j * kThreads + tid) : n;
+  if (j == kPerThread) return min(n, n_full * PER + tid);
+  return (j / PER) * kThreads + tid < n_full ? ((j / PER) * kThreads + tid) * PER + (j % PER) : n;
+}
+
+// Pass 1 of the top-k: one workgroup per (chunk, row).  The chunk goes from memory straight into
+// registers (every load is in flight before the first value is used).  The k best entries are
+// found without sorting: the k-th largest of the 256 per-thread maxima is a lower bound T of the
+// chunk's k-th largest value, so only values >= T can be among the k best; those few are
+// collected in LDS (as order-preserving keys) and the k best picked there by counting ranks.
+// Many equal values can let more pass than the list holds; then k rounds of a workgroup-wide
+// maximum run over the registers instead (same result, slower).
 template <typename T>
 __global__ __launch_bounds__(kThreads) void topk_chunk_kernel(int V, int k, int chunk, int n_chunks,
                                                               const T *__restrict__ logits,
                                                               unsigned char *__restrict__ work) {
-  extern __shared__ float vals[];  // chunk floats
   __shared__ unsigned long long red[kThreads / 64];
   __shared__ float fred[kThreads / 64];
   __shared__ unsigned long long win[kMaxTopK];
+  __shared__ unsigned long long list[kListCap];
+  __shared__ unsigned long long tmax[kThreads];
+  __shared__ int list_n;
+  __shared__ float thr_s;
+  constexpr int PER = 16 / (int)sizeof(T);
   const int c = blockIdx.x, m = blockIdx.y;
+  const int tid = threadIdx.x;
   const int v0 = c * chunk;
   const int n = min(chunk, V - v0);
   const T *row = logits + (size_t)m * V + v0;
-  // vector path: 16-byte loads when the chunk's first element is 16-byte aligned
-  constexpr int PER = 16 / (int)sizeof(T);
-  const bool aligned = (((size_t)row) & 15) == 0;
-  const int n_vec = aligned ? n / PER : 0;
-  for (int i = threadIdx.x; i < n_vec; i += kThreads) {
-    const u32x4 x = ((const u32x4 *)row)[i];
-    if (sizeof(T) == 4) {
+  const int n_full = n / PER;
+  const bool vec = (((size_t)row) & 15) == 0 && n_full > 0;
+  const float ninf = -__builtin_huge_valf();
+  // every load is unconditional (addresses clamped into the chunk) so that all of them are in
+  // flight together; what a thread does not own is replaced by -inf afterwards
+  float x[kPerThread + 1];
+  if (vec) {
+    u32x4 w[kPerThread / PER];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) vals[4 * i + e] = __uint_as_float(x[e]);
-    } else {
+    for (int q = 0; q < kPerThread / PER; ++q) w[q] = ((const u32x4 *)row)[min(q * kThreads + tid, n_full - 1)];
+    const float tail = load_f32<T>(row + min(n_full * PER + tid, n - 1));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vals[8 * i + 2 * e] = __uint_as_float(x[e] << 16);
-        vals[8 * i + 2 * e + 1] = __uint_as_float(x[e] & 0xffff0000u);
+    for (int q = 0; q < kPerThread / PER; ++q) {
+      const bool own = q * kThreads + tid < n_full;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        float f;
+        if (sizeof(T) == 4) f = __uint_as_float(w[q][e]);
+        else f = __uint_as_float((e & 1) ? (w[q][e >> 1] & 0xffff0000u) : (w[q][e >> 1] << 16));
+        x[q * PER + e] = (own && f == f) ? f : ninf;
       }
     }
+    x[kPerThread] = (n_full * PER + tid < n && tail == tail) ? tail : ninf;
+  } else {
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int p = j * kThreads + tid;
+      const float f = load_f32<T>(row + min(p, n - 1));
+      x[j] = (p < n && f == f) ? f : ninf;
+    }
+    x[kPerThread] = ninf;
   }
-  for (int i = n_vec * PER + threadIdx.x; i < n; i += kThreads) vals[i] = load_f32<T>(row + i);
+  if (tid == 0) list_n = 0;
+  float mt = ninf;
+#pragma unroll
+  for (int j = 0; j <= kPerThread; ++j) mt = fmaxf(mt, x[j]);
+  const float mx = wg_max_f(mt, fred);
+  // T = the k-th largest of the threads' maxima (threads without a value do not take part):
+  // every thread counts the maxima above its own; the one that finds k - 1 holds T
+  const bool has = pos_of<PER>(vec, 0, n, n_full) < n || pos_of<PER>(vec, kPerThread, n, n_full) < n;
+  const unsigned long long mine = has ? sel_key(mt, (uint32_t)tid) : 0ull;
+  tmax[tid] = mine;
+  if (tid == 0) thr_s = ninf;  // fewer than k threads hold values: everything passes
   __syncthreads();
-  float mx = -__builtin_huge_valf();
-  for (int i = threadIdx.x; i < n; i += kThreads) mx = fmaxf(mx, vals[i]);
-  mx = wg_max_f(mx, fred);
+  {
+    int rank = 0;
+#pragma unroll 8
+    for (int j = 0; j < kThreads; ++j) rank += tmax[j] > mine ? 1 : 0;
+    if (has && rank == k - 1) thr_s = mt;
+  }
+  __syncthreads();
+  const float thr = thr_s;
   float sum = 0.f;
-  if (mx > -__builtin_huge_valf())
-    for (int i = threadIdx.x; i < n; i += kThreads) sum += __expf(vals[i] - mx);
-  sum = wg_sum_f(sum, fred);
-  select_k(vals, n, (uint32_t)v0, k, win, red);
+  const bool any = mx > ninf;
+#pragma unroll
+  for (int j = 0; j <= kPerThread; ++j) {
+    const int p = pos_of<PER>(vec, j, n, n_full);
+    if (any) sum += __expf(x[j] - mx);  // values the thread does not own are -inf and add 0
+    if (p < n && x[j] >= thr) {
+      const int at = atomicAdd(&list_n, 1);
+      if (at < kListCap) list[at] = sel_key(x[j], (uint32_t)(v0 + p));
+    }
+  }
+  sum = wg_sum_f(sum, fred);  // its barriers also publish list and list_n
+  const int cnt = list_n;
+  if (cnt <= kListCap) {
+    rank_select(list, cnt, k, win);
+  } else {
+    unsigned long long last = ~0ull;
+    for (int r = 0; r < k; ++r) {
+      unsigned long long best = 0ull;
+#pragma unroll
+      for (int j = 0; j <= kPerThread; ++j) {
+        const int p = pos_of<PER>(vec, j, n, n_full);
+        const unsigned long long key = p < n ? sel_key(x[j], (uint32_t)(v0 + p)) : 0ull;
+        best = (key < last && key > best) ? key : best;
+      }
+      best = wg_max_key(best, red);
+      if (tid == 0) win[r] = best;
+      last = best;
+    }
+  }
+  __syncthreads();
   unsigned char *slot = work + ((size_t)m * n_chunks + c) * (sizeof(Partial) + (size_t)k * 8);
-  if (threadIdx.x == 0) {
+  if (tid == 0) {
     Partial p;
     p.max = mx;
     p.sum = sum;
     *(Partial *)slot = p;
   }
-  if (threadIdx.x < k) ((unsigned long long *)(slot + sizeof(Partial)))[threadIdx.x] = win[threadIdx.x];
+  if (tid < k) ((unsigned long long *)(slot + sizeof(Partial)))[tid] = win[tid];
 }
 
 __global__ __launch_bounds__(kThreads) void topk_merge_kernel(int V, int k, int n_chunks,
@@ -140,6 +223,7 @@ __global__ __launch_bounds__(kThreads) void topk_merge_kernel(int V, int k, int 
   __shared__ unsigned long long red[kThreads / 64];
   __shared__ float fred[kThreads / 64];
   __shared__ unsigned long long win[kMaxTopK];
+  __shared__ unsigned long long list[kListCap];
   const int m = blockIdx.x;
   const size_t stride = sizeof(Partial) + (size_t)k * 8;
   const unsigned char *base = work + (size_t)m * n_chunks * stride;
@@ -153,20 +237,27 @@ __global__ __launch_bounds__(kThreads) void topk_merge_kernel(int V, int k, int 
   }
   sum = wg_sum_f(sum, fred);
   const float lse = mx + __logf(sum);
-  // the chunks' winners are keys already: k rounds of the maximum below the last one
-  unsigned long long last = ~0ull;
+  // the chunks' winners are keys already
   const int n = n_chunks * k;
-  for (int r = 0; r < k; ++r) {
-    unsigned long long best = 0ull;
-    for (int i = threadIdx.x; i < n; i += kThreads) {
-      const unsigned long long key = ((const unsigned long long *)(base + (i / k) * stride + sizeof(Partial)))[i % k];
-      best = (key < last && key > best) ? key : best;
+  if (n <= kListCap) {
+    for (int i = threadIdx.x; i < n; i += kThreads)
+      list[i] = ((const unsigned long long *)(base + (i / k) * stride + sizeof(Partial)))[i % k];
+    __syncthreads();
+    rank_select(list, n, k, win);
+  } else {  // k rounds of the maximum below the last one
+    unsigned long long last = ~0ull;
+    for (int r = 0; r < k; ++r) {
+      unsigned long long best = 0ull;
+      for (int i = threadIdx.x; i < n; i += kThreads) {
+        const unsigned long long key = ((const unsigned long long *)(base + (i / k) * stride + sizeof(Partial)))[i % k];
+        best = (key < last && key > best) ? key : best;
+      }
+      best = wg_max_key(best, red);
+      if (threadIdx.x == 0) win[r] = best;
+      last = best;
     }
-    best = wg_max_key(best, red);
-    if (threadIdx.x == 0) win[r] = best;
-    last = best;
+    __syncthreads();
   }
-  __syncthreads();
   if (threadIdx.x < k) {
     const unsigned long long key = win[threadIdx.x];
     const bool ok = key != 0ull;
@@ -209,6 +300,7 @@ __global__ __launch_bounds__(kThreads) void tree_grow_kernel(int K, int level, i
     if (level > 0) {
       const float s = s_new[t];
       rank = 0;
+#pragma unroll 8
       for (int u = 0; u < n_new; ++u) rank += beats(s_new[u], u, s, t) ? 1 : 0;
     }
     if (rank < K) {
@@ -243,6 +335,7 @@ __global__ __launch_bounds__(kThreads) void tree_finalize_kernel(
   for (int c = c0; c < c1; ++c) {
     const float sc = s[c];
     int rank = 0;
+#pragma unroll 8
     for (int u = 0; u < C; ++u) rank += beats(s[u], u, sc, c) ? 1 : 0;
     if (rank < keep) { kept_bits |= 1ull << (c - c0); ++cnt; }
   }
@@ -301,7 +394,7 @@ int32_t topk_chunk_elems(int32_t M, int32_t V) {
   int64_t want = (1024 + M - 1) / (M > 0 ? M : 1);
   if (want < 1) want = 1;
   int64_t chunk = ((int64_t)V + want - 1) / want;
-  chunk = (chunk + 1023) / 1024 * 1024;
+  chunk = (chunk + 1023) / 1024 * 1024;  // 16-byte alignment of a chunk's start follows the row's
   if (chunk < 2048) chunk = 2048;
   if (chunk > 16384) chunk = 16384;
   return (int32_t)chunk;
@@ -318,18 +411,12 @@ hipError_t launch_topk_logprob(int32_t dtype, int32_t M, int32_t V, int32_t k, c
   const int chunk = topk_chunk_elems(M, V);
   const int n_chunks = (V + chunk - 1) / chunk;
   dim3 grid((unsigned)n_chunks, (unsigned)M);
-  const size_t lds = (size_t)chunk * sizeof(float);
-  if (dtype == HB_BF16) {
-    auto kern = topk_chunk_kernel<bf16_t>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    kern<<<grid, kThreads, lds, s>>>(V, k, chunk, n_chunks, (const bf16_t *)logits, (unsigned char *)work);
-  } else {
-    auto kern = topk_chunk_kernel<float>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    kern<<<grid, kThreads, lds, s>>>(V, k, chunk, n_chunks, (const float *)logits, (unsigned char *)work);
-  }
+  if (dtype == HB_BF16)
+    topk_chunk_kernel<bf16_t><<<grid, kThreads, 0, s>>>(V, k, chunk, n_chunks, (const bf16_t *)logits,
+                                                        (unsigned char *)work);
+  else
+    topk_chunk_kernel<float><<<grid, kThreads, 0, s>>>(V, k, chunk, n_chunks, (const float *)logits,
+                                                       (unsigned char *)work);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   topk_merge_kernel<<<M, kThreads, 0, s>>>(V, k, n_chunks, (const unsigned char *)work, out_ids, out_logp);
