@@ -17,6 +17,7 @@ target's own greedy stream):
   stochastic_acceptance.tree_accept_sample_ref   sampling acceptance (speculative sampling over a tree)
   projections.qkv_rope_project_ref / linear_ref / tree_positions_ref   the projections around the attention
   draft_tree.topk_logprob_ref / DraftTreeRef / build_draft_tree_ref   the draft tree's construction
+  meta_query.meta_query_attn_ref / fc_concat_ref   the draft's intermediate layer (Section 3.1.1, Eq. 1)
   toy_decoder.ToyDecoderRef        small random-weight decoder: greedy autoregressive stream and
                                    greedy speculative decoding built from the four functions above
 
@@ -33,6 +34,7 @@ from .kv_compaction import kv_compact_ref
 from .toy_decoder import ToyDecoderRef
 from .stochastic_acceptance import tree_accept_sample_ref
 from .draft_tree import topk_logprob_ref, DraftTreeRef, build_draft_tree_ref
+from .meta_query import meta_query_attn_ref, fc_concat_ref
 from .projections import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref
 
 __all__ = [
@@ -51,4 +53,6 @@ __all__ = [
     "topk_logprob_ref",
     "DraftTreeRef",
     "build_draft_tree_ref",
+    "meta_query_attn_ref",
+    "fc_concat_ref",
 ]
