@@ -392,6 +392,66 @@ def bench_draft_tree(steps, warmup, B=16, K=10, T=5, N=60, V=152064):
     }
 
 
+def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
+    """The draft model's intermediate layer (meta-query cross-attention over the target's layer
+    features, output projection with skip connection, fc1) on the tokens one step commits at most
+    (16 sequences x 6), random weights.  Per call: value projection GEMM [n_tok * L, D] x [D, D],
+    the fused scores / softmax / mixing kernel, output projection, fc1."""
+    import torch
+    import workloads as W
+    import paper_2509_18824_amd as hb
+    import paper_2509_18824_amd.step as S
+
+    x = {k: v.cuda() for k, v in W.make_meta_inputs(90, n_tok, L, D, H, Q).items()}
+    layer = S.MetaQueryLayer(x["f_q"], x["w_q"], x["w_k"], x["w_v"], x["w_o"], x["w_fc1"], H, residual_layers=[2, L // 2, L - 1])
+    feats = x["feats"]
+    bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    v_proj, pre, res, f_c, out = bf(n_tok * L, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok, D)
+    names = ("value_projection", "meta_query_attn", "output_projection", "fc1")
+
+    def call(ev=None):
+        marks = []
+        def mark():
+            if ev is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                marks.append(e)
+        mark()
+        hb.hb_out_project(feats.view(n_tok * L, D), layer.w_v, None, v_proj)
+        mark()
+        hb.hb_meta_query_attn(H, Q, feats, v_proj.view(n_tok, L, D), layer.a_fold, layer.residual_layers,
+                              pre.view(n_tok, Q, D), res.view(n_tok, Q, D))
+        mark()
+        hb.hb_out_project(pre, layer.w_o, res, f_c)
+        mark()
+        hb.hb_out_project(f_c.view(n_tok, Q * D), layer.w_fc1, None, out)
+        mark()
+        if ev is not None:
+            ev.append(marks)
+
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        call()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev = []
+    for _ in range(steps):
+        call(ev)
+    torch.cuda.synchronize()
+    parts = {n: sum(m[i].elapsed_time(m[i + 1]) for m in ev) / steps for i, n in enumerate(names)}
+    attn_bytes = 2 * n_tok * L * D * 2 + 2 * n_tok * Q * D * 2
+    return {
+        "what": f"{n_tok} tokens x {L} layer features of size {D}, {H} heads, {Q} meta queries, bf16, random weights",
+        "ms_per_call": ms, "tokens_per_s": n_tok / (ms * 1e-3), "ms_by_call": parts,
+        "value_projection_TFLOPs": 2.0 * n_tok * L * D * D / (parts["value_projection"] * 1e-3) / 1e12,
+        "meta_query_attn_bytes": attn_bytes,
+        "meta_query_attn_GBps": attn_bytes / (parts["meta_query_attn"] * 1e-3) / 1e9,
+    }
+
+
 def bench_layer_stack(inp, desc, dv, lm_weight, draft_np, n_steps, n_layers=28):
     """The step at a realistic depth: 28 layers, each QKV projection + rotary embedding ->
     tree-verify attention over its own KV pools (2.3 GB in all, so every layer streams its KV from
@@ -478,6 +538,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stack", action="store_true", help="skip the 28-layer variant of the step")
     ap.add_argument("--no-draft-tree", action="store_true", help="skip the draft tree's construction")
+    ap.add_argument("--no-meta-query", action="store_true", help="skip the draft's intermediate layer")
     ap.add_argument("--no-chain", action="store_true", help="skip the 8-node-chain run of the step")
     ap.add_argument("--no-achievable", action="store_true", help="skip the library-kernel yardsticks")
     ap.add_argument("--no-parity", action="store_true", help="skip the comparison with the CPU oracle")
@@ -601,6 +662,9 @@ def main():
     if not args.no_draft_tree:
         torch.cuda.empty_cache()
         result["draft_tree"] = bench_draft_tree(max(args.steps, 20), args.warmup)
+    if not args.no_meta_query:
+        torch.cuda.empty_cache()
+        result["meta_query"] = bench_meta_query(max(args.steps, 20), args.warmup)
     if not args.no_achievable:
         torch.cuda.empty_cache()
         result["achievable"] = achievable_peaks()

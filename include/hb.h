@@ -339,6 +339,47 @@ int32_t hb_tree_finalize(int32_t B, int32_t K, int32_t T, int32_t n_nodes, const
                          int32_t *node_offset, int32_t *parent, int32_t *draft_ids, int32_t *depth,
                          uint64_t *anc_mask, int32_t *node_cand, float *node_score, void *stream);
 
+/*
+ * Target-feature aggregation with meta queries, the draft model's intermediate layer (Section
+ * 3.1.1, Eq. 1; skip connection and the fully connected layers around it: Section 3.1.2).  Read
+ * as multi-head cross-attention (H heads of size d = D / H, no biases, weights in the y = x W^T
+ * layout, scores scaled by 1 / sqrt(d)) of Q token-independent queries f_q over the L layer
+ * features f_i of every token:
+ *   f_c^i = flatten( concat_h( softmax(q_h k_{i,h}^T / sqrt(d)) v_{i,h} ) W_o^T + f_i[residual layers] ),
+ *   q = f_q W_q^T,  k_i = f_i W_k^T,  v_i = f_i W_v^T.
+ * The calls split it so that every dense product runs on the matrix cores and the key projection
+ * disappears: (1) once per set of weights, hb_meta_query_fold builds A[h Q + q] =
+ * (f_q W_q^T)_{q,h} W_k[h d .. (h+1) d, :] / sqrt(d), so that score(q, h, l) = A[h Q + q] . f_i[l];
+ * (2) per batch of tokens, v_proj = feats W_v^T by hb_out_project(S * L, D, D, feats, w_v, NULL,
+ * v_proj); (3) hb_meta_query_attn computes the scores, the softmax over the layers and
+ * pre[i, q, c] = sum_l P[i, head(c), q, l] v_proj[i, l, c], and copies the residual rows; (4)
+ * f_c = hb_out_project(S * Q, D, D, pre, w_o, residual, f_c), read as [S, Q * D]; fc1 and fc2 are
+ * further hb_out_project calls (fc2 over a concatenation [a, b] as two calls, the second with the
+ * first's output as residual).  All tensors bf16, 16-byte aligned, row-major.
+ *
+ * hb_meta_query_fold:
+ *   f_q [Q, D], w_q [D, D], w_k [D, D]   device
+ *   a_fold      device, hb_meta_query_fold_bytes(Q, D, H) bytes: two bf16 matrices
+ *               [rows_pad, D] (value rounded to bf16, and the rounded remainder), rows_pad =
+ *               H * Q rounded up to a multiple of 16
+ *   workspace   device, Q * D floats
+ * hb_meta_query_attn:
+ *   feats, v_proj [S, L, D] device;  a_fold from hb_meta_query_fold
+ *   residual_layers_or_null   HOST int32 [Q]: the layer whose feature is each query's residual
+ *   pre [S, Q, D] device;  residual_out_or_null [S, Q, D] device (written iff residual layers given)
+ * Errors: INVALID_ARG (sizes < 1, H not dividing D, residual layer outside [0, L), NULL or
+ * misaligned pointers), UNSUPPORTED (D % 128 != 0, (D / H) % 8 != 0, H * Q > 96, Q > 4, L > 32),
+ * WORKSPACE, DEVICE.  S == 0 is a no-op.
+ */
+size_t hb_meta_query_fold_bytes(int32_t Q, int32_t D, int32_t H);
+
+int32_t hb_meta_query_fold(int32_t Q, int32_t D, int32_t H, const void *f_q, const void *w_q, const void *w_k,
+                           void *a_fold, void *workspace, size_t workspace_bytes, void *stream);
+
+int32_t hb_meta_query_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q, const void *feats,
+                           const void *v_proj, const void *a_fold, const int32_t *residual_layers_or_null,
+                           void *pre, void *residual_out_or_null, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

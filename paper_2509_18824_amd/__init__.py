@@ -31,6 +31,9 @@ from .binding import (
     hb_draft_tree_candidates,
     hb_tree_grow,
     hb_tree_finalize,
+    hb_meta_query_fold_bytes,
+    hb_meta_query_fold,
+    hb_meta_query_attn,
     HB_F32,
     HB_BF16,
     HB_ATTN_AUTO,

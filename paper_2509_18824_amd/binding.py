@@ -88,6 +88,12 @@ def _load():
     lib.hb_tree_grow.argtypes = [i32, i32, i32, i32] + [p] * 7 + [p]
     lib.hb_tree_finalize.restype = i32
     lib.hb_tree_finalize.argtypes = [i32, i32, i32, i32] + [p] * 11 + [p]
+    lib.hb_meta_query_fold_bytes.restype = sz
+    lib.hb_meta_query_fold_bytes.argtypes = [i32, i32, i32]
+    lib.hb_meta_query_fold.restype = i32
+    lib.hb_meta_query_fold.argtypes = [i32, i32, i32, p, p, p, p, p, sz, p]
+    lib.hb_meta_query_attn.restype = i32
+    lib.hb_meta_query_attn.argtypes = [i32] * 5 + [p, p, p, C.POINTER(i32), p, p, p]
     lib.hb_kv_compact.restype = i32
     lib.hb_kv_compact.argtypes = [C.POINTER(AttnDesc)] + [p] * 9 + [i32, p, p, p]
     return lib
@@ -263,6 +269,31 @@ def hb_tree_finalize(B: int, K: int, T: int, n_nodes: int, cand_score, cand_toke
     _check(lib.hb_tree_finalize(B, K, T, n_nodes, _ptr(cand_score), _ptr(cand_token), _ptr(cand_parent),
                                 _ptr(root_token), _ptr(node_offset), _ptr(parent), _ptr(draft_ids), _ptr(depth),
                                 _ptr(anc_mask), _ptr(node_cand), _ptr(node_score), _stream(stream)))
+
+
+def hb_meta_query_fold_bytes(Q: int, D: int, H: int) -> int:
+    return int(lib.hb_meta_query_fold_bytes(Q, D, H))
+
+
+def hb_meta_query_fold(H: int, f_q, w_q, w_k, a_fold, workspace, stream=None) -> None:
+    Q, D = f_q.shape
+    for t in (f_q, w_q, w_k, a_fold):
+        if t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise ValueError("bf16 contiguous tensors expected")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_meta_query_fold(Q, D, H, _ptr(f_q), _ptr(w_q), _ptr(w_k), _ptr(a_fold), _ptr(workspace), ws_bytes,
+                                  _stream(stream)))
+
+
+def hb_meta_query_attn(H: int, Q: int, feats, v_proj, a_fold, residual_layers, pre, residual_out=None,
+                       stream=None) -> None:
+    S, L, D = feats.shape
+    for t in (feats, v_proj, a_fold, pre):
+        if t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise ValueError("bf16 contiguous tensors expected")
+    layers = (C.c_int32 * Q)(*[int(x) for x in residual_layers]) if residual_layers is not None else None
+    _check(lib.hb_meta_query_attn(S, L, D, H, Q, _ptr(feats), _ptr(v_proj), _ptr(a_fold), layers, _ptr(pre),
+                                  _ptr(residual_out), _stream(stream)))
 
 
 def hb_kv_compact(desc: AttnDesc, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset,

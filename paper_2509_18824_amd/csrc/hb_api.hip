@@ -445,6 +445,59 @@ int32_t hb_tree_finalize(int32_t B, int32_t K, int32_t T, int32_t n_nodes, const
   return HB_OK;
 }
 
+static int32_t check_meta_shape(int32_t L, int32_t D, int32_t H, int32_t Q) {
+  if (L < 1 || D < 1 || H < 1 || Q < 1) return fail(HB_ERR_INVALID_ARG, "need L, D, H, Q >= 1");
+  if (D % H) return fail(HB_ERR_INVALID_ARG, "H %d does not divide D %d", H, D);
+  if (D % 128 || (D / H) % 8)
+    return fail(HB_ERR_UNSUPPORTED, "D %d must be a multiple of 128 and the head size %d of 8", D, D / H);
+  if (Q > 4 || (int64_t)H * Q > 96 || L > 32)
+    return fail(HB_ERR_UNSUPPORTED, "at most 4 queries, 96 (head, query) rows and 32 layers (Q %d, H %d, L %d)", Q, H, L);
+  return HB_OK;
+}
+
+size_t hb_meta_query_fold_bytes(int32_t Q, int32_t D, int32_t H) {
+  if (Q < 1 || D < 1 || H < 1) return 0;
+  return (size_t)2 * meta_rows_pad(H, Q) * (size_t)D * sizeof(bf16_t);
+}
+
+int32_t hb_meta_query_fold(int32_t Q, int32_t D, int32_t H, const void *f_q, const void *w_q, const void *w_k,
+                           void *a_fold, void *workspace, size_t workspace_bytes, void *stream) {
+  int32_t rc = check_meta_shape(1, D, H, Q);
+  if (rc) return rc;
+  if (!f_q || !w_q || !w_k || !a_fold) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(f_q) || misaligned(w_q) || misaligned(w_k) || misaligned(a_fold))
+    return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  const size_t need = (size_t)Q * D * sizeof(float);
+  if (!workspace || workspace_bytes < need)
+    return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  if ((uintptr_t)workspace % 4) return fail(HB_ERR_WORKSPACE, "workspace must be 4-byte aligned");
+  HB_HIP_TRY(launch_meta_fold(Q, D, H, f_q, w_q, w_k, a_fold, (float *)workspace, (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_meta_query_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q, const void *feats,
+                           const void *v_proj, const void *a_fold, const int32_t *residual_layers_or_null,
+                           void *pre, void *residual_out_or_null, void *stream) {
+  if (S < 0) return fail(HB_ERR_INVALID_ARG, "S must be >= 0");
+  int32_t rc = check_meta_shape(L, D, H, Q);
+  if (rc) return rc;
+  if (residual_layers_or_null) {
+    for (int q = 0; q < Q; ++q)
+      if (residual_layers_or_null[q] < 0 || residual_layers_or_null[q] >= L)
+        return fail(HB_ERR_INVALID_ARG, "residual layer %d of query %d outside [0, %d)", residual_layers_or_null[q], q, L);
+    if (!residual_out_or_null) return fail(HB_ERR_INVALID_ARG, "residual layers given without residual_out");
+  }
+  if (S == 0) return HB_OK;
+  if (!feats || !v_proj || !a_fold || !pre) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(feats) || misaligned(v_proj) || misaligned(a_fold) || misaligned(pre) ||
+      (residual_out_or_null && misaligned(residual_out_or_null)))
+    return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  HB_HIP_TRY(launch_meta_attn(S, L, D, H, Q, feats, v_proj, a_fold, residual_layers_or_null, pre,
+                              residual_layers_or_null ? residual_out_or_null : nullptr, (hipStream_t)stream));
+  return HB_OK;
+}
+
 int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *v_tree,
                       void *k_pool, void *v_pool, const int32_t *block_table,
                       const int32_t *prefix_len, const int32_t *node_offset,

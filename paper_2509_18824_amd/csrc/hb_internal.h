@@ -118,6 +118,12 @@ hipError_t launch_tree_finalize(int32_t B, int32_t C, int32_t n, const float *ca
                                 const int32_t *cand_parent, const int32_t *root_token, int32_t *node_offset,
                                 int32_t *parent, int32_t *draft_ids, int32_t *depth, unsigned long long *anc,
                                 int32_t *node_cand, float *node_score, hipStream_t s);
+int32_t meta_rows_pad(int32_t H, int32_t Q);
+hipError_t launch_meta_fold(int32_t Q, int32_t D, int32_t H, const void *f_q, const void *w_q, const void *w_k,
+                            void *a_fold, float *qproj, hipStream_t s);
+hipError_t launch_meta_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q, const void *feats, const void *v_proj,
+                            const void *a_fold, const int32_t *residual_layers, void *pre, void *res_out,
+                            hipStream_t s);
 hipError_t launch_kv_compact(const hb_attn_desc &d, const void *k_tree, const void *v_tree,
                              void *k_pool, void *v_pool, const int32_t *block_table,
                              const int32_t *prefix_len, const int32_t *node_offset,

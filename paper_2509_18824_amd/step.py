@@ -151,6 +151,48 @@ class DraftTreeBuilder:
         return out
 
 
+class MetaQueryLayer:
+    """The draft model's intermediate layer up to fc1: meta-query cross-attention over the layer
+    features of every token, output projection with the skip connection, fc1.  Weights bf16 in
+    the y = x W^T layout; the key projection is folded into the queries at construction."""
+
+    def __init__(self, f_q, w_q, w_k, w_v, w_o, w_fc1, H: int, residual_layers=None):
+        self.Q, self.D = f_q.shape
+        self.H, self.residual_layers = H, residual_layers
+        self.w_v, self.w_o, self.w_fc1 = w_v, w_o, w_fc1
+        dev = f_q.device
+        self.a_fold = torch.empty(hb.hb_meta_query_fold_bytes(self.Q, self.D, H) // 2, dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(self.Q * self.D, dtype=torch.float32, device=dev)
+        hb.hb_meta_query_fold(H, f_q, w_q, w_k, self.a_fold, ws)
+
+    def run(self, feats):
+        """feats bf16 [S, L, D] -> (F_c [S, Q * D], fc1 output [S, N1])."""
+        S, L, D = feats.shape
+        Q, dev = self.Q, feats.device
+        bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        v_proj, pre, f_c = bf(S * L, D), bf(S * Q, D), bf(S * Q, D)
+        res = bf(S * Q, D) if self.residual_layers is not None else None
+        hb.hb_out_project(feats.view(S * L, D), self.w_v, None, v_proj)
+        hb.hb_meta_query_attn(self.H, Q, feats, v_proj.view(S, L, D), self.a_fold, self.residual_layers,
+                              pre.view(S, Q, D), None if res is None else res.view(S, Q, D))
+        hb.hb_out_project(pre, self.w_o, res, f_c)
+        f_c = f_c.view(S, Q * D)
+        out = bf(S, self.w_fc1.shape[0])
+        hb.hb_out_project(f_c, self.w_fc1, None, out)
+        return f_c, out
+
+
+def fc_concat(a, b, w_a, w_b):
+    """fc over the concatenation [a, b]: a w_a^T + b w_b^T (w_a, w_b: the two column blocks of the
+    layer's weight, stored as separate matrices)."""
+    T = a.shape[0]
+    tmp = torch.empty((T, w_a.shape[0]), dtype=torch.bfloat16, device=a.device)
+    out = torch.empty_like(tmp)
+    hb.hb_out_project(a, w_a, None, tmp)
+    hb.hb_out_project(b, w_b, tmp, out)
+    return out
+
+
 def kv_compact(desc, dev: DeviceInputs, accept_len, accept_path):
     B, max_path = accept_path.shape
     out_slots = torch.empty((B, max_path), dtype=torch.int32, device=accept_path.device)

@@ -132,3 +132,23 @@ def test_draft_tree_argument_errors():
     assert L.hb_tree_finalize(2, 2, 2, 8, p, p, p, p, p, p, p, p, p, p, p, None) == 1  # 7 > 6 candidates
     assert L.hb_tree_finalize(2, 32, 6, 60, p, p, p, p, p, p, p, p, p, p, p, None) == 2  # 5152 candidates
     assert L.hb_tree_finalize(2, 10, 5, 60, p, p, p, None, p, p, p, p, p, p, p, None) == 1
+
+
+def test_meta_query_argument_errors():
+    L, p = hb.lib, C.c_void_p(0x1000)
+    assert hb.hb_meta_query_fold_bytes(3, 3584, 28) == 2 * 96 * 3584 * 2
+    assert L.hb_meta_query_fold(3, 3584, 28, p, p, p, p, p, 16, None) == 3
+    assert L.hb_meta_query_fold(3, 3584, 27, p, p, p, p, p, 1 << 20, None) == 1      # H does not divide D
+    assert L.hb_meta_query_fold(3, 3520, 5, p, p, p, p, p, 1 << 20, None) == 2       # D % 128
+    assert L.hb_meta_query_fold(5, 3584, 28, p, p, p, p, p, 1 << 20, None) == 2      # Q > 4
+    assert L.hb_meta_query_fold(3, 3584, 28, None, p, p, p, p, 1 << 20, None) == 1
+    assert L.hb_meta_query_fold(3, 3584, 28, C.c_void_p(0x1002), p, p, p, p, 1 << 20, None) == 1
+    layers = (C.c_int32 * 3)(0, 14, 28)
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers, p, p, None) == 1  # layer 28 of 28
+    ok_layers = (C.c_int32 * 3)(0, 14, 27)
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, ok_layers, p, None, None) == 1  # no residual_out
+    assert L.hb_meta_query_attn(4, 33, 3584, 28, 3, p, p, p, None, p, None, None) == 2       # L > 32
+    assert L.hb_meta_query_attn(4, 28, 3584, 56, 3, p, p, p, None, p, None, None) == 2       # 168 rows
+    assert L.hb_meta_query_attn(-1, 28, 3584, 28, 3, p, p, p, None, p, None, None) == 1
+    assert L.hb_meta_query_attn(0, 28, 3584, 28, 3, None, None, None, None, None, None, None) == 0
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, None, p, p, None, p, None, None) == 1

@@ -8,6 +8,7 @@ GPU library without coupling them.
 from .trees import chain_tree, seeded_tree, tree_depths, validate_parents
 from .drafters import random_drafter, replay_drafter
 from .draft import make_draft_logits
+from .meta import make_meta_inputs
 from .configs import (
     CONFIG_NAMES,
     VerifyInputs,
@@ -37,4 +38,5 @@ __all__ = [
     "random_drafter",
     "replay_drafter",
     "make_draft_logits",
+    "make_meta_inputs",
 ]
