@@ -368,7 +368,7 @@ int32_t hb_tree_finalize(int32_t B, int32_t K, int32_t T, int32_t n_nodes, const
  *   residual_layers_or_null   HOST int32 [Q]: the layer whose feature is each query's residual
  *   pre [S, Q, D] device;  residual_out_or_null [S, Q, D] device (written iff residual layers given)
  * Errors: INVALID_ARG (sizes < 1, H not dividing D, residual layer outside [0, L), NULL or
- * misaligned pointers), UNSUPPORTED (D % 128 != 0, (D / H) % 8 != 0, H * Q > 96, Q > 4, L > 32),
+ * misaligned pointers), UNSUPPORTED (D % 256 != 0, (D / H) % 8 != 0, H * Q > 96, Q > 4, L > 32),
  * WORKSPACE, DEVICE.  S == 0 is a no-op.
  */
 size_t hb_meta_query_fold_bytes(int32_t Q, int32_t D, int32_t H);

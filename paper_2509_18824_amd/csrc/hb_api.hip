@@ -448,8 +448,8 @@ int32_t hb_tree_finalize(int32_t B, int32_t K, int32_t T, int32_t n_nodes, const
 static int32_t check_meta_shape(int32_t L, int32_t D, int32_t H, int32_t Q) {
   if (L < 1 || D < 1 || H < 1 || Q < 1) return fail(HB_ERR_INVALID_ARG, "need L, D, H, Q >= 1");
   if (D % H) return fail(HB_ERR_INVALID_ARG, "H %d does not divide D %d", H, D);
-  if (D % 128 || (D / H) % 8)
-    return fail(HB_ERR_UNSUPPORTED, "D %d must be a multiple of 128 and the head size %d of 8", D, D / H);
+  if (D % 256 || (D / H) % 8)
+    return fail(HB_ERR_UNSUPPORTED, "D %d must be a multiple of 256 and the head size %d of 8", D, D / H);
   if (Q > 4 || (int64_t)H * Q > 96 || L > 32)
     return fail(HB_ERR_UNSUPPORTED, "at most 4 queries, 96 (head, query) rows and 32 layers (Q %d, H %d, L %d)", Q, H, L);
   return HB_OK;

@@ -10,7 +10,7 @@
 // (value rounded to bf16 plus the rounded remainder), so that folding costs the scores no
 // accuracy against projecting keys in fp32.
 //
-// meta_attn_kernel, one workgroup per token: the four wavefronts split D, each accumulates its
+// meta_attn_kernel, one workgroup per token: the eight wavefronts split D, each accumulates its
 // share of the [H Q, L] scores with MFMA 16x16x32 (operands straight from memory in fragment
 // layout: the A rows come from L2, the token's features from HBM), the partial scores meet in
 // LDS, one thread per (head, query) row does the softmax over the L layers, and every thread then
@@ -28,11 +28,15 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 256;       // the two set-up kernels
 constexpr int kWaves = 4;
+constexpr int kAttnWaves = 8;       // wavefronts of meta_attn_kernel: each takes an eighth of D
+constexpr int kAttnThreads = 64 * kAttnWaves;
+constexpr int kBRing = 4;           // steps that the token's feature fragments are loaded ahead
 constexpr int kMaxRowTiles = 6;   // H * Q <= 96
 constexpr int kMaxRows = 16 * kMaxRowTiles;
 constexpr int kMaxL = 32;
+constexpr int kLdsL = kMaxL + 1;    // row stride of the score tables in LDS: one thread per row reads without bank conflicts
 constexpr int kMaxQ = 4;
 
 // qproj[q, n] = sum_c f_q[q, c] w_q[n, c]: one wavefront per output
@@ -75,14 +79,15 @@ struct ResidualLayers {
   int32_t on;
 };
 
-__global__ __launch_bounds__(kThreads) void meta_attn_kernel(int L, int D, int H, int Q, int row_tiles,
-                                                             const u32x4 *__restrict__ feats,
-                                                             const u32x4 *__restrict__ v_proj,
-                                                             const u32x4 *__restrict__ a_hi,
-                                                             const u32x4 *__restrict__ a_lo, ResidualLayers res,
-                                                             u32x4 *__restrict__ pre, u32x4 *__restrict__ res_out) {
-  __shared__ float part[kWaves][kMaxRows][kMaxL];  // partial scores of the four wavefronts
-  __shared__ float prob[kMaxRows][kMaxL];
+__global__ __launch_bounds__(kAttnThreads) void meta_attn_kernel(int L, int D, int H, int Q, int row_tiles,
+                                                                 const u32x4 *__restrict__ feats,
+                                                                 const u32x4 *__restrict__ v_proj,
+                                                                 const u32x4 *__restrict__ a_hi,
+                                                                 const u32x4 *__restrict__ a_lo, ResidualLayers res,
+                                                                 u32x4 *__restrict__ pre, u32x4 *__restrict__ res_out) {
+  extern __shared__ float meta_lds[];
+  float (*part)[kMaxRows][kLdsL] = reinterpret_cast<float (*)[kMaxRows][kLdsL]>(meta_lds);  // [kAttnWaves]
+  float (*prob)[kLdsL] = reinterpret_cast<float (*)[kLdsL]>(meta_lds + kAttnWaves * kMaxRows * kLdsL);
   const int s = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j16 = lane & 15, kq = lane >> 4;
@@ -91,14 +96,16 @@ __global__ __launch_bounds__(kThreads) void meta_attn_kernel(int L, int D, int H
   const u32x4 *g_tok = v_proj + (size_t)s * L * dp;
   const int rows = H * Q;
 
-  // ---- scores: this wavefront's quarter of D ---------------------------------------------
+  // ---- scores: this wavefront's eighth of D ------------------------------------------------
+  // The A rows come from L2 (every token re-reads them), one step ahead; the token's own
+  // features come from HBM and are requested kBRing - 1 steps ahead.
   f32x4 acc[kMaxRowTiles][2];
 #pragma unroll
   for (int mt = 0; mt < kMaxRowTiles; ++mt) {
     acc[mt][0] = (f32x4){0.f, 0.f, 0.f, 0.f};
     acc[mt][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
-  const int steps = D / (32 * kWaves);        // 32 features per MFMA step
+  const int steps = D / (32 * kAttnWaves);    // 32 features per MFMA step
   const int piece0 = wave * steps * 4 + kq;   // 16-byte piece of the lane's fragment at step 0
   const u32x4 zero = {0u, 0u, 0u, 0u};
   const int l0 = j16, l1 = 16 + j16;          // the lane's layers (B operand columns)
@@ -106,11 +113,14 @@ __global__ __launch_bounds__(kThreads) void meta_attn_kernel(int L, int D, int H
   const u32x4 *b1 = f_tok + (size_t)(l1 < L ? l1 : 0) * dp + piece0;
   const u32x4 *ah = a_hi + (size_t)j16 * dp + piece0;
   const u32x4 *al = a_lo + (size_t)j16 * dp + piece0;
-  u32x4 fb[2][2], fh[2][kMaxRowTiles], fl[2][kMaxRowTiles];
-#define HB_META_LOAD(buf_, step_)                                              \
+  u32x4 fb[kBRing][2], fh[2][kMaxRowTiles], fl[2][kMaxRowTiles];
+#define HB_META_LOAD_B(buf_, step_)                                            \
   {                                                                            \
     fb[buf_][0] = b0[(step_) * 4];                                             \
     fb[buf_][1] = b1[(step_) * 4];                                             \
+  }
+#define HB_META_LOAD_A(buf_, step_)                                            \
+  {                                                                            \
     _Pragma("unroll") for (int mt = 0; mt < kMaxRowTiles; ++mt) {               \
       if (mt < row_tiles) {                                                    \
         fh[buf_][mt] = ah[(size_t)mt * 16 * dp + (step_) * 4];                 \
@@ -118,14 +128,14 @@ __global__ __launch_bounds__(kThreads) void meta_attn_kernel(int L, int D, int H
       }                                                                        \
     }                                                                          \
   }
-#define HB_META_MMA(buf_)                                                                                        \
+#define HB_META_MMA(abuf_, bbuf_)                                                                                \
   {                                                                                                              \
-    const bf16x8 x0 = __builtin_bit_cast(bf16x8, l0 < L ? fb[buf_][0] : zero);                                   \
-    const bf16x8 x1 = __builtin_bit_cast(bf16x8, l1 < L ? fb[buf_][1] : zero);                                   \
+    const bf16x8 x0 = __builtin_bit_cast(bf16x8, l0 < L ? fb[bbuf_][0] : zero);                                  \
+    const bf16x8 x1 = __builtin_bit_cast(bf16x8, l1 < L ? fb[bbuf_][1] : zero);                                  \
     _Pragma("unroll") for (int mt = 0; mt < kMaxRowTiles; ++mt) {                                                 \
       if (mt < row_tiles) {                                                                                      \
-        const bf16x8 h8 = __builtin_bit_cast(bf16x8, fh[buf_][mt]);                                              \
-        const bf16x8 l8 = __builtin_bit_cast(bf16x8, fl[buf_][mt]);                                              \
+        const bf16x8 h8 = __builtin_bit_cast(bf16x8, fh[abuf_][mt]);                                             \
+        const bf16x8 l8 = __builtin_bit_cast(bf16x8, fl[abuf_][mt]);                                             \
         acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(h8, x0, acc[mt][0], 0, 0, 0);                       \
         acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(h8, x1, acc[mt][1], 0, 0, 0);                       \
         acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(l8, x0, acc[mt][0], 0, 0, 0);                       \
@@ -133,16 +143,23 @@ __global__ __launch_bounds__(kThreads) void meta_attn_kernel(int L, int D, int H
       }                                                                                                          \
     }                                                                                                            \
   }
-  HB_META_LOAD(0, 0);
-  for (int st = 0; st < steps; st += 2) {
-    if (st + 1 < steps) HB_META_LOAD(1, st + 1);
-    HB_META_MMA(0);
-    if (st + 1 < steps) {
-      if (st + 2 < steps) HB_META_LOAD(0, st + 2);
-      HB_META_MMA(1);
+#pragma unroll
+  for (int u = 0; u < kBRing - 1; ++u)
+    if (u < steps) HB_META_LOAD_B(u, u);
+  HB_META_LOAD_A(0, 0);
+  for (int st = 0; st < steps; st += kBRing) {
+#pragma unroll
+    for (int u = 0; u < kBRing; ++u) {
+      const int cur = st + u;
+      if (cur < steps) {
+        if (cur + kBRing - 1 < steps) HB_META_LOAD_B((u + kBRing - 1) % kBRing, cur + kBRing - 1);
+        if (cur + 1 < steps) HB_META_LOAD_A((u + 1) & 1, cur + 1);
+        HB_META_MMA(u & 1, u);
+      }
     }
   }
-#undef HB_META_LOAD
+#undef HB_META_LOAD_A
+#undef HB_META_LOAD_B
 #undef HB_META_MMA
   // lane (j16, kq) holds rows 16 mt + 4 kq + r of layer 16 ct + j16
 #pragma unroll
@@ -162,7 +179,10 @@ __global__ __launch_bounds__(kThreads) void meta_attn_kernel(int L, int D, int H
     float mx = -__builtin_huge_valf();
 #pragma unroll
     for (int l = 0; l < kMaxL; ++l) {
-      sc[l] = (part[0][tid][l] + part[1][tid][l]) + (part[2][tid][l] + part[3][tid][l]);
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) t += part[w][tid][l];
+      sc[l] = t;
       if (l < L) mx = fmaxf(mx, sc[l]);
     }
     float sum = 0.f;
@@ -179,14 +199,14 @@ __global__ __launch_bounds__(kThreads) void meta_attn_kernel(int L, int D, int H
 
   // ---- mix the projected values: eight feature columns per thread, all queries ---------------
   const int d8 = (D / H) / 8;  // 16-byte pieces per head
-  for (int cg = tid; cg < dp; cg += kThreads) {
+  for (int cg = tid; cg < dp; cg += kAttnThreads) {
     const int h = cg / d8;
     float o[kMaxQ][8];
 #pragma unroll
     for (int q = 0; q < kMaxQ; ++q)
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[q][e] = 0.f;
-#pragma unroll 4
+#pragma unroll 8
     for (int l = 0; l < L; ++l) {
       const u32x4 g = g_tok[(size_t)l * dp + cg];
       float gv[8];
@@ -246,7 +266,10 @@ hipError_t launch_meta_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t 
     for (int q = 0; q < Q; ++q) res.layer[q] = residual_layers[q];
   }
   const bf16_t *a_hi = (const bf16_t *)a_fold, *a_lo = a_hi + (size_t)rows_pad * D;
-  meta_attn_kernel<<<S, kThreads, 0, s>>>(L, D, H, Q, rows_pad / 16, (const u32x4 *)feats, (const u32x4 *)v_proj,
+  constexpr size_t kLds = (size_t)(kAttnWaves + 1) * kMaxRows * kLdsL * sizeof(float);
+  hipError_t e = hipFuncSetAttribute((const void *)meta_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+  if (e != hipSuccess) return e;
+  meta_attn_kernel<<<S, kAttnThreads, kLds, s>>>(L, D, H, Q, rows_pad / 16, (const u32x4 *)feats, (const u32x4 *)v_proj,
                                           (const u32x4 *)a_hi, (const u32x4 *)a_lo, res, (u32x4 *)pre, (u32x4 *)res_out);
   return hipGetLastError();
 }

@@ -139,7 +139,7 @@ def test_meta_query_argument_errors():
     assert hb.hb_meta_query_fold_bytes(3, 3584, 28) == 2 * 96 * 3584 * 2
     assert L.hb_meta_query_fold(3, 3584, 28, p, p, p, p, p, 16, None) == 3
     assert L.hb_meta_query_fold(3, 3584, 27, p, p, p, p, p, 1 << 20, None) == 1      # H does not divide D
-    assert L.hb_meta_query_fold(3, 3520, 5, p, p, p, p, p, 1 << 20, None) == 2       # D % 128
+    assert L.hb_meta_query_fold(3, 3200, 5, p, p, p, p, p, 1 << 20, None) == 2       # D % 256
     assert L.hb_meta_query_fold(5, 3584, 28, p, p, p, p, p, 1 << 20, None) == 2      # Q > 4
     assert L.hb_meta_query_fold(3, 3584, 28, None, p, p, p, p, 1 << 20, None) == 1
     assert L.hb_meta_query_fold(3, 3584, 28, C.c_void_p(0x1002), p, p, p, p, 1 << 20, None) == 1

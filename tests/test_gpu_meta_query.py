@@ -47,9 +47,9 @@ def _run(S, seed, n_tok, L, D, H, Q, layers, peaked=False, zero_wo=False):
 @pytest.mark.parametrize("n_tok,L,D,H,Q,layers", [
     (5, 6, 256, 2, 3, [0, 2, 5]),        # small: one row tile, layers in one column tile
     (3, 28, 512, 4, 3, [1, 13, 27]),     # 28 layers (two column tiles, the second ragged)
-    (7, 32, 384, 3, 4, None),            # 32 layers, four queries, no skip connection
+    (7, 32, 768, 3, 4, None),            # 32 layers, four queries, no skip connection
     (2, 17, 1024, 32, 3, [0, 8, 16]),    # 96 (head, query) rows: every row tile
-    (1, 1, 128, 1, 1, [0]),              # one layer, one head, one query
+    (1, 1, 256, 2, 1, [0]),              # one layer, one head, one query
 ])
 def test_small_shapes(S, n_tok, L, D, H, Q, layers):
     _run(S, 3 + n_tok, n_tok, L, D, H, Q, layers)

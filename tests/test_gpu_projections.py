@@ -51,7 +51,9 @@ def test_positions_and_rope_table(hb):
 
 
 @pytest.mark.parametrize("T,K,Hq,Hkv,bias", [(960, 3584, 28, 4, True), (128, 3584, 28, 4, False), (77, 128, 2, 1, True),
-                                             (300, 320, 3, 3, False), (1, 64, 1, 1, True), (513, 192, 8, 2, True)])
+                                             (300, 320, 3, 3, False), (1, 64, 1, 1, True), (513, 192, 8, 2, True),
+                                             (100, 256, 2, 1, True), (1, 512, 1, 1, True), (16, 768, 3, 3, False),
+                                             (128, 1024, 4, 2, True)])
 def test_qkv_projection_with_rotary_embedding(hb, T, K, Hq, Hkv, bias):
     g = torch.Generator().manual_seed(T * 7 + K)
     hidden = torch.randn((T, K), generator=g).to(torch.bfloat16)
@@ -73,7 +75,9 @@ def test_qkv_projection_with_rotary_embedding(hb, T, K, Hq, Hkv, bias):
 
 
 @pytest.mark.parametrize("T,K,N,res", [(960, 3584, 3584, True), (128, 3584, 3584, False), (50, 64, 4, True),
-                                       (333, 448, 1000, False), (700, 256, 260, True)])
+                                       (333, 448, 1000, False), (700, 256, 260, True),
+                                       (128, 3584, 3584, True), (37, 256, 20, True), (5, 512, 1000, False),
+                                       (96, 10752, 3584, False), (1, 256, 4, True)])
 def test_output_projection(hb, T, K, N, res):
     g = torch.Generator().manual_seed(T + K + N)
     x = torch.randn((T, K), generator=g).to(torch.bfloat16)
