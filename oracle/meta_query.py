@@ -20,7 +20,7 @@ y = x W^T, scores scaled by 1 / sqrt(d), softmax over the L layers:
   o_i[:, head h] = softmax(q_h k_{i,h}^T / sqrt(d)) v_{i,h}
   f_c^i = flatten(o_i W_o^T + f_i[residual_layers])       (residual_layers: Q layer indices)
 
-Everything in float64.  The paper's quality figures for this layer (Table 3) need training and
+Everything in float64.  The paper's quality figures for this layer (Table 1, the ablation rows) need training and
 stay parity unpinned; what is pinned is the arithmetic above (see tests/test_oracle_meta_query.py).
 """
 from __future__ import annotations
