@@ -408,6 +408,7 @@ def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
     bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device="cuda")
     v_proj, pre, res, f_c, out = bf(n_tok * L, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok, D)
     names = ("value_projection", "meta_query_attn", "output_projection", "fc1")
+    ws_fc1 = S.alloc_workspace(hb.hb_proj_workspace_bytes(n_tok, Q * D, D))  # split-K partials (few tokens only)
 
     def call(ev=None):
         marks = []
@@ -424,7 +425,7 @@ def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
         mark()
         hb.hb_out_project(pre, layer.w_o, res, f_c)
         mark()
-        hb.hb_out_project(f_c.view(n_tok, Q * D), layer.w_fc1, None, out)
+        hb.hb_out_project_ws(f_c.view(n_tok, Q * D), layer.w_fc1, None, out, ws_fc1)
         mark()
         if ev is not None:
             ev.append(marks)
@@ -653,6 +654,11 @@ def main():
         }
         if not args.no_parity:
             result[other]["parity"] = parity_check(r2, weight)
+        if not args.no_stack:
+            # the 28-layer variant with this draft shape too: with 128 tokens the projections are
+            # weight streams and take the split-K path
+            result[other]["stack28"] = bench_layer_stack(r2["inp"], r2["desc"], r2["dev"], wdev, r2["draft_np"],
+                                                         max(5, args.steps // 5))
         del r2
     if not args.no_attn_extra and args.tree == "tree":
         step = run = None

@@ -191,6 +191,28 @@ int32_t hb_out_project(int32_t T, int32_t K, int32_t N, const void *x, const voi
                        const void *residual_or_null, void *out, void *stream);
 
 /*
+ * The same two projections for small token counts (chain drafts, the draft model's batches), the
+ * setting of the paper's own measurements (Section 4.2: chain decoding).  With at most 128 tokens
+ * a projection is a stream of its weight matrix from HBM, and one workgroup per 256-row weight
+ * tile leaves most of the chip idle; given a workspace these calls cut K into parts, one
+ * workgroup per (weight tile, K part), keep the parts' fp32 partial results in the workspace and
+ * finish (sum in fixed order, bias, rotary embedding, residual) in a second kernel.  Results are
+ * deterministic; they differ from the calls above in fp32 summation order only.
+ *   workspace   device, hb_proj_workspace_bytes(T, K, N) bytes (N = (Hq + 2 Hkv) * 128 for the
+ *               QKV projection), 16-byte aligned.  That size is 0 when the split does not apply
+ *               (T > 128); with a NULL, short or misaligned workspace the calls behave exactly as
+ *               the ones above.
+ * Errors as above.
+ */
+size_t hb_proj_workspace_bytes(int32_t T, int32_t K, int32_t N);
+int32_t hb_qkv_rope_project_ws(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32_t head_dim, const void *hidden,
+                               const void *w_qkv, const void *bias_or_null, const float *cos, const float *sin,
+                               void *q, void *k, void *v, void *workspace, size_t workspace_bytes, void *stream);
+int32_t hb_out_project_ws(int32_t T, int32_t K, int32_t N, const void *x, const void *w,
+                          const void *residual_or_null, void *out, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/*
  * Greedy longest accepted path per sequence.  Node 0 is always accepted; node i > 0 matches
  * when draft_ids[i] == target_ids[parent[i]] and is accepted when it and all its ancestors
  * match.  The deepest accepted node wins (lowest id among equals).  accept_len is the number

@@ -22,6 +22,9 @@ from .binding import (
     hb_rope_table,
     hb_qkv_rope_project,
     hb_out_project,
+    hb_proj_workspace_bytes,
+    hb_qkv_rope_project_ws,
+    hb_out_project_ws,
     hb_tree_accept,
     hb_tree_accept_sample,
     hb_tree_accept_sample_workspace_bytes,

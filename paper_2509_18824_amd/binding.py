@@ -72,6 +72,12 @@ def _load():
     lib.hb_qkv_rope_project.argtypes = [i32] * 5 + [p] * 8 + [p]
     lib.hb_out_project.restype = i32
     lib.hb_out_project.argtypes = [i32, i32, i32, p, p, p, p, p]
+    lib.hb_proj_workspace_bytes.restype = sz
+    lib.hb_proj_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.hb_qkv_rope_project_ws.restype = i32
+    lib.hb_qkv_rope_project_ws.argtypes = [i32] * 5 + [p] * 8 + [p, sz, p]
+    lib.hb_out_project_ws.restype = i32
+    lib.hb_out_project_ws.argtypes = [i32, i32, i32, p, p, p, p, p, sz, p]
     lib.hb_tree_accept.restype = i32
     lib.hb_tree_accept.argtypes = [i32, i32, p, p, p, p, p, i32, p, p, p, p, p]
     lib.hb_tree_accept_sample.restype = i32
@@ -214,6 +220,31 @@ def hb_out_project(x, w, residual, out, stream=None) -> None:
     if w.shape[1] != K or x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16 or out.shape != (T, N):
         raise ValueError("need bf16 x [T, K], w [N, K], out [T, N]")
     _check(lib.hb_out_project(T, K, N, _ptr(x), _ptr(w), _ptr(residual), _ptr(out), _stream(stream)))
+
+
+def hb_proj_workspace_bytes(T: int, K: int, N: int) -> int:
+    return int(lib.hb_proj_workspace_bytes(T, K, N))
+
+
+def hb_qkv_rope_project_ws(hidden, w_qkv, bias, cos, sin, q, k, v, workspace, stream=None) -> None:
+    T, K = hidden.shape
+    _, Hq, D = q.shape
+    Hkv = k.shape[1]
+    if w_qkv.shape != ((Hq + 2 * Hkv) * D, K) or hidden.dtype != torch.bfloat16 or w_qkv.dtype != torch.bfloat16:
+        raise ValueError("w_qkv must be bf16 [(Hq + 2 Hkv) * D, K]")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_qkv_rope_project_ws(T, K, Hq, Hkv, D, _ptr(hidden), _ptr(w_qkv), _ptr(bias), _ptr(cos), _ptr(sin),
+                                      _ptr(q), _ptr(k), _ptr(v), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def hb_out_project_ws(x, w, residual, out, workspace, stream=None) -> None:
+    T, K = x.shape
+    N = w.shape[0]
+    if w.shape[1] != K or x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16 or out.shape != (T, N):
+        raise ValueError("need bf16 x [T, K], w [N, K], out [T, N]")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_out_project_ws(T, K, N, _ptr(x), _ptr(w), _ptr(residual), _ptr(out), _ptr(workspace), ws_bytes,
+                                 _stream(stream)))
 
 
 def hb_tree_accept(B: int, max_nodes_per_tree: int, node_offset, parent, draft_ids, target_ids,

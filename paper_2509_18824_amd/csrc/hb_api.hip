@@ -305,9 +305,21 @@ int32_t hb_rope_table(int32_t T, int32_t head_dim, double theta, const int32_t *
   return HB_OK;
 }
 
-int32_t hb_qkv_rope_project(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32_t head_dim, const void *hidden,
-                            const void *w_qkv, const void *bias_or_null, const float *cos, const float *sin,
-                            void *q, void *k, void *v, void *stream) {
+// Workspace of the split-K path: usable when present, large enough and 16-byte aligned; the
+// calls fall back to one workgroup per tile otherwise.
+static float *proj_part(int32_t T, int32_t K, int32_t N, void *workspace, size_t workspace_bytes) {
+  const size_t need = proj_workspace_bytes(T, K, N);
+  if (need == 0 || !workspace || workspace_bytes < need || misaligned(workspace)) return nullptr;
+  return (float *)workspace;
+}
+
+size_t hb_proj_workspace_bytes(int32_t T, int32_t K, int32_t N) {
+  return (T > 0 && K > 0 && N > 0) ? proj_workspace_bytes(T, K, N) : 0;
+}
+
+static int32_t qkv_rope_project(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32_t head_dim, const void *hidden,
+                                const void *w_qkv, const void *bias_or_null, const float *cos, const float *sin,
+                                void *q, void *k, void *v, void *workspace, size_t workspace_bytes, void *stream) {
   if (T < 0 || K <= 0 || Hq <= 0 || Hkv <= 0) return fail(HB_ERR_INVALID_ARG, "need T >= 0 and K, Hq, Hkv > 0");
   if (head_dim != 128) return fail(HB_ERR_UNSUPPORTED, "head_dim %d: the fused projection takes head_dim 128", head_dim);
   if (K % 64) return fail(HB_ERR_UNSUPPORTED, "K %d: must be a multiple of 64", K);
@@ -318,20 +330,46 @@ int32_t hb_qkv_rope_project(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32
   if (misaligned(hidden) || misaligned(w_qkv) || misaligned(cos) || misaligned(sin) || misaligned(q) || misaligned(k) ||
       misaligned(v) || (bias_or_null && misaligned(bias_or_null)))
     return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
-  HB_HIP_TRY(launch_qkv_rope(T, K, Hq, Hkv, hidden, w_qkv, bias_or_null, cos, sin, q, k, v, (hipStream_t)stream));
+  HB_HIP_TRY(launch_qkv_rope(T, K, Hq, Hkv, hidden, w_qkv, bias_or_null, cos, sin, q, k, v,
+                             proj_part(T, K, (Hq + 2 * Hkv) * 128, workspace, workspace_bytes), (hipStream_t)stream));
   return HB_OK;
 }
 
-int32_t hb_out_project(int32_t T, int32_t K, int32_t N, const void *x, const void *w,
-                       const void *residual_or_null, void *out, void *stream) {
+static int32_t out_project(int32_t T, int32_t K, int32_t N, const void *x, const void *w, const void *residual_or_null,
+                           void *out, void *workspace, size_t workspace_bytes, void *stream) {
   if (T < 0 || K <= 0 || N <= 0) return fail(HB_ERR_INVALID_ARG, "need T >= 0 and K, N > 0");
   if (K % 64 || N % 4) return fail(HB_ERR_UNSUPPORTED, "K %d must be a multiple of 64 and N %d of 4", K, N);
   if (T == 0) return HB_OK;
   if (!x || !w || !out) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
   if (misaligned(x) || misaligned(w) || misaligned(out) || (residual_or_null && misaligned(residual_or_null)))
     return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
-  HB_HIP_TRY(launch_linear(T, K, N, x, w, residual_or_null, out, (hipStream_t)stream));
+  HB_HIP_TRY(launch_linear(T, K, N, x, w, residual_or_null, out, proj_part(T, K, N, workspace, workspace_bytes),
+                           (hipStream_t)stream));
   return HB_OK;
+}
+
+int32_t hb_qkv_rope_project(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32_t head_dim, const void *hidden,
+                            const void *w_qkv, const void *bias_or_null, const float *cos, const float *sin,
+                            void *q, void *k, void *v, void *stream) {
+  return qkv_rope_project(T, K, Hq, Hkv, head_dim, hidden, w_qkv, bias_or_null, cos, sin, q, k, v, nullptr, 0, stream);
+}
+
+int32_t hb_qkv_rope_project_ws(int32_t T, int32_t K, int32_t Hq, int32_t Hkv, int32_t head_dim, const void *hidden,
+                               const void *w_qkv, const void *bias_or_null, const float *cos, const float *sin,
+                               void *q, void *k, void *v, void *workspace, size_t workspace_bytes, void *stream) {
+  return qkv_rope_project(T, K, Hq, Hkv, head_dim, hidden, w_qkv, bias_or_null, cos, sin, q, k, v, workspace,
+                          workspace_bytes, stream);
+}
+
+int32_t hb_out_project(int32_t T, int32_t K, int32_t N, const void *x, const void *w,
+                       const void *residual_or_null, void *out, void *stream) {
+  return out_project(T, K, N, x, w, residual_or_null, out, nullptr, 0, stream);
+}
+
+int32_t hb_out_project_ws(int32_t T, int32_t K, int32_t N, const void *x, const void *w,
+                          const void *residual_or_null, void *out, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+  return out_project(T, K, N, x, w, residual_or_null, out, workspace, workspace_bytes, stream);
 }
 
 int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,

@@ -88,11 +88,13 @@ hipError_t launch_lmhead_finish(const unsigned long long *keys, int32_t M, int32
                                 int32_t *out_ids, float *out_max, hipStream_t s);
 
 bool proj_mfma_supports(int32_t M, int32_t K, int32_t N);
+// part: fp32 scratch of proj_workspace_bytes(M, K, N) bytes for the split-K path, or null (then: one workgroup per tile)
+size_t proj_workspace_bytes(int32_t M, int32_t K, int32_t N);
 hipError_t launch_qkv_rope(int32_t M, int32_t K, int32_t Hq, int32_t Hkv, const void *hidden, const void *w_qkv,
                            const void *bias, const float *cos, const float *sin, void *q, void *k, void *v,
-                           hipStream_t s);
+                           float *part, hipStream_t s);
 hipError_t launch_linear(int32_t M, int32_t K, int32_t N, const void *x, const void *w, const void *residual,
-                         void *out, hipStream_t s);
+                         void *out, float *part, hipStream_t s);
 hipError_t launch_tree_positions(int32_t B, int32_t max_nodes, int32_t total_nodes, const int32_t *node_offset,
                                  const int32_t *parent, const int32_t *prefix_len, int32_t *positions, hipStream_t s);
 hipError_t launch_rope_table(int32_t T, int32_t half, double theta, const int32_t *positions, float *cos, float *sin,

@@ -86,6 +86,7 @@ __global__ __launch_bounds__(512) void proj_mfma_kernel(int M, int K, int V, int
     if (m >= M) continue;
     if (ROPE) {
       const int head = (v0 >> 7) + (wv >> 1);
+      if (head >= qa.Hq + 2 * qa.Hkv) continue;  // second half of the last tile when the heads are odd in number
       const bool rotate = head < qa.Hq + qa.Hkv;
       bf16_t *dst = head < qa.Hq ? qa.q + ((size_t)m * qa.Hq + head) * kHeadDim
                     : head < qa.Hq + qa.Hkv ? qa.k + ((size_t)m * qa.Hkv + (head - qa.Hq)) * kHeadDim
@@ -155,6 +156,158 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, c
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)((v_tiles + kXcds - 1) / kXcds * kXcds * m_tiles));
   kern<<<grid, 512, lds_bytes, s>>>(M, K, V, m_tiles, v_tiles, (const u32x4 *)hidden, (const u32x4 *)weight, qa, sa);
+  return hipGetLastError();
+}
+
+// ---- at most 128 tokens: split K ------------------------------------------------------------
+// With so few tokens a projection is a stream of its weight matrix from HBM, and one workgroup
+// per 256-row weight tile would give work to a dozen CUs only.  Here the K range of every tile is
+// cut into `ks` parts, one workgroup each (ids round-robin over the XCDs put the workgroups of
+// one K part, which read the same slice of the hidden rows, on one XCD); a workgroup runs the
+// same tile loop over its part and stores its fp32 accumulators to the caller's workspace as
+// part[kpart][weight row][token] (tokens contiguous: a lane's 32 neighbours hold consecutive
+// tokens of one weight row).  proj_reduce_kernel then sums the parts in order and applies the
+// epilogue (bias, rotary embedding, residual), one thread per token and group of four features
+// (for the rotary variant: four (d, d + 64) pairs).
+template <int MT>
+__global__ __launch_bounds__(512) void proj_splitk_kernel(int M, int Kfull, int V, int ks, int v_pad,
+                                                          const u32x4 *__restrict__ hidden_full,
+                                                          const u32x4 *__restrict__ weight_full,
+                                                          float *__restrict__ part) {
+  constexpr int WV = 4;
+  constexpr bool WNT = true;  // nobody shares a weight tile: stream it past the hidden rows in L2
+  constexpr int TM = 64 * MT;
+  constexpr int VT = 8 / WV;
+  extern __shared__ u32x4 lds[];
+  u32x4 *lw = lds;
+  u32x4 *lh = lds + 3 * TV * CH;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wv = wave >> 1;
+  const int wm = wave & 1;
+  const int v_tile = blockIdx.x / ks, kpart = blockIdx.x % ks;
+  const int m0 = 0;
+  const int v0 = v_tile * TV;
+  const int K = Kfull / ks;          // this workgroup's share
+  const int kp = Kfull / 8;          // row stride in 16-byte pieces
+  const u32x4 *hidden = hidden_full + (size_t)kpart * (K / 8);
+  const u32x4 *weight = weight_full + (size_t)kpart * (K / 8);
+#define HB_GEMM_W_ROW(t_) (v0 + (t_))
+#include "mfma_gemm_tile.inc"
+#undef HB_GEMM_W_ROW
+  float *dst = part + ((size_t)kpart * v_pad + v0) * TM;
+#pragma unroll
+  for (int i = 0; i < VT; ++i)
+#pragma unroll
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = wv * 32 * VT + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        dst[(size_t)row * TM + wm * 32 * MT + j * 32 + frag_row] = acc[i][j][r];
+      }
+}
+
+template <bool ROPE>
+__global__ __launch_bounds__(256) void proj_reduce_kernel(int M, int V, int ks, int v_pad, int tm,
+                                                          const float *__restrict__ part, QkvArgs qa, StoreArgs sa) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  const int m = (int)(idx % tm);
+  const int g = (int)(idx / tm);
+  if (m >= M) return;
+  if (ROPE) {
+    const int head = g >> 4, d = (g & 15) * 4;
+    if (head >= qa.Hq + 2 * qa.Hkv) return;
+    float x1[4] = {0.f, 0.f, 0.f, 0.f}, x2[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int kpart = 0; kpart < ks; ++kpart) {
+      const float *src = part + ((size_t)kpart * v_pad + head * kHeadDim + d) * tm + m;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        x1[e] += src[(size_t)e * tm];
+        x2[e] += src[(size_t)(64 + e) * tm];
+      }
+    }
+    if (qa.bias) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        x1[e] += bf16_to_f32(qa.bias[head * kHeadDim + d + e]);
+        x2[e] += bf16_to_f32(qa.bias[head * kHeadDim + 64 + d + e]);
+      }
+    }
+    const bool rotate = head < qa.Hq + qa.Hkv;
+    bf16_t *dst = head < qa.Hq ? qa.q + ((size_t)m * qa.Hq + head) * kHeadDim
+                  : head < qa.Hq + qa.Hkv ? qa.k + ((size_t)m * qa.Hkv + (head - qa.Hq)) * kHeadDim
+                                          : qa.v + ((size_t)m * qa.Hkv + (head - qa.Hq - qa.Hkv)) * kHeadDim;
+    if (rotate) {
+      const f32x4 cs = *(const f32x4 *)(qa.cos + (size_t)m * 64 + d);
+      const f32x4 sn = *(const f32x4 *)(qa.sin + (size_t)m * 64 + d);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a = x1[e] * cs[e] - x2[e] * sn[e];
+        const float b = x2[e] * cs[e] + x1[e] * sn[e];
+        x1[e] = a;
+        x2[e] = b;
+      }
+    }
+    *(u32x2 *)(dst + d) = (u32x2){pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
+    *(u32x2 *)(dst + d + 64) = (u32x2){pack_bf16(x2[0], x2[1]), pack_bf16(x2[2], x2[3])};
+  } else {
+    const int n = g * 4;
+    if (n >= V) return;
+    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int kpart = 0; kpart < ks; ++kpart) {
+      const float *src = part + ((size_t)kpart * v_pad + n) * tm + m;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] += src[(size_t)e * tm];
+    }
+    if (sa.residual) {
+      const u32x2 r = *(const u32x2 *)(sa.residual + (size_t)m * V + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] += __uint_as_float((e & 1) ? (r[e >> 1] & 0xffff0000u) : (r[e >> 1] << 16));
+    }
+    *(u32x2 *)(sa.out + (size_t)m * V + n) = (u32x2){pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+  }
+}
+
+// K parts for the split: a divisor of the K steps that leaves every part at least kMinSteps steps
+// and gives as many workgroups as there are CUs, or as close to that as it gets from below.
+constexpr int kSplitMaxM = 128;
+constexpr int kMinSteps = 8;
+int split_parts(int M, int K, int V) {
+  if (M > kSplitMaxM || K % BK) return 1;
+  const int steps = K / BK, v_tiles = (V + TV - 1) / TV;
+  int best = 1;
+  for (int d = 1; d <= steps; ++d) {
+    if (steps % d || steps / d < kMinSteps) continue;
+    if (v_tiles * d <= 256 && d > best) best = d;
+  }
+  return best;
+}
+
+template <bool ROPE>
+hipError_t launch_splitk(int M, int K, int V, int ks, const void *hidden, const void *weight, const QkvArgs &qa,
+                         const StoreArgs &sa, float *part, hipStream_t s) {
+  const int mt = M <= 64 ? 1 : 2;
+  const int tm = 64 * mt;
+  const int v_tiles = (V + TV - 1) / TV, v_pad = v_tiles * TV;
+  const size_t lds_bytes = (size_t)(3 * TV + 2 * tm) * CH * sizeof(u32x4);
+  hipError_t e;
+  if (mt == 1) {
+    auto kern = proj_splitk_kernel<1>;
+    e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    kern<<<v_tiles * ks, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, (const u32x4 *)hidden, (const u32x4 *)weight, part);
+  } else {
+    auto kern = proj_splitk_kernel<2>;
+    e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    kern<<<v_tiles * ks, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, (const u32x4 *)hidden, (const u32x4 *)weight, part);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long groups = ROPE ? (long)(V / kHeadDim) * 16 : (V + 3) / 4;
+  const long threads = groups * tm;
+  proj_reduce_kernel<ROPE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(M, V, ks, v_pad, tm, part, qa, sa);
   return hipGetLastError();
 }
 
@@ -229,18 +382,30 @@ __global__ __launch_bounds__(256) void rope_table_kernel(int T, int half, double
 
 bool proj_mfma_supports(int32_t M, int32_t K, int32_t N) { return M >= 1 && K >= BK && K % BK == 0 && N >= 4 && N % 4 == 0; }
 
+size_t proj_workspace_bytes(int32_t M, int32_t K, int32_t N) {
+  const int ks = split_parts(M, K, N);
+  if (ks <= 1) return 0;
+  const size_t v_pad = (size_t)((N + TV - 1) / TV) * TV;
+  return (size_t)ks * v_pad * (M <= 64 ? 64 : 128) * sizeof(float);
+}
+
 hipError_t launch_qkv_rope(int32_t M, int32_t K, int32_t Hq, int32_t Hkv, const void *hidden, const void *w_qkv,
                            const void *bias, const float *cos, const float *sin, void *q, void *k, void *v,
-                           hipStream_t s) {
+                           float *part, hipStream_t s) {
   QkvArgs qa = {(const bf16_t *)bias, cos, sin, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, Hq, Hkv};
   StoreArgs sa = {nullptr, nullptr};
-  return dispatch<true>(M, K, (Hq + 2 * Hkv) * kHeadDim, hidden, w_qkv, qa, sa, s);
+  const int V = (Hq + 2 * Hkv) * kHeadDim;
+  const int ks = part ? split_parts(M, K, V) : 1;
+  if (ks > 1) return launch_splitk<true>(M, K, V, ks, hidden, w_qkv, qa, sa, part, s);
+  return dispatch<true>(M, K, V, hidden, w_qkv, qa, sa, s);
 }
 
 hipError_t launch_linear(int32_t M, int32_t K, int32_t N, const void *x, const void *w, const void *residual, void *out,
-                         hipStream_t s) {
+                         float *part, hipStream_t s) {
   QkvArgs qa = {};
   StoreArgs sa = {(const bf16_t *)residual, (bf16_t *)out};
+  const int ks = part ? split_parts(M, K, N) : 1;
+  if (ks > 1) return launch_splitk<false>(M, K, N, ks, x, w, qa, sa, part, s);
   return dispatch<false>(M, K, N, x, w, qa, sa, s);
 }
 

@@ -151,6 +151,13 @@ class DraftTreeBuilder:
         return out
 
 
+def linear(x, w, residual, out):
+    """out = x w^T (+ residual); small token counts take the split-K path (its workspace is allocated here)."""
+    nbytes = hb.hb_proj_workspace_bytes(x.shape[0], x.shape[1], w.shape[0])
+    ws = alloc_workspace(nbytes, x.device) if nbytes else None
+    hb.hb_out_project_ws(x, w, residual, out, ws)
+
+
 class MetaQueryLayer:
     """The draft model's intermediate layer up to fc1: meta-query cross-attention over the layer
     features of every token, output projection with the skip connection, fc1.  Weights bf16 in
@@ -175,10 +182,10 @@ class MetaQueryLayer:
         hb.hb_out_project(feats.view(S * L, D), self.w_v, None, v_proj)
         hb.hb_meta_query_attn(self.H, Q, feats, v_proj.view(S, L, D), self.a_fold, self.residual_layers,
                               pre.view(S, Q, D), None if res is None else res.view(S, Q, D))
-        hb.hb_out_project(pre, self.w_o, res, f_c)
+        linear(pre, self.w_o, res, f_c)
         f_c = f_c.view(S, Q * D)
         out = bf(S, self.w_fc1.shape[0])
-        hb.hb_out_project(f_c, self.w_fc1, None, out)
+        linear(f_c, self.w_fc1, None, out)
         return f_c, out
 
 
@@ -188,8 +195,8 @@ def fc_concat(a, b, w_a, w_b):
     T = a.shape[0]
     tmp = torch.empty((T, w_a.shape[0]), dtype=torch.bfloat16, device=a.device)
     out = torch.empty_like(tmp)
-    hb.hb_out_project(a, w_a, None, tmp)
-    hb.hb_out_project(b, w_b, tmp, out)
+    linear(a, w_a, None, tmp)
+    linear(b, w_b, tmp, out)
     return out
 
 
@@ -265,6 +272,9 @@ class VerifyLayerStack:
         self.attn_out = torch.empty_like(dev.q)
         self.ws_attn = alloc_workspace(hb.hb_tree_verify_attn_workspace_bytes(desc), d)
         self.ws_lm = alloc_workspace(max(8, hb.hb_lmhead_argmax_workspace_bytes(T)), d)
+        K = hidden0.shape[1]
+        proj_bytes = max(hb.hb_proj_workspace_bytes(T, K, w_qkv[0].shape[0]), hb.hb_proj_workspace_bytes(T, K, w_o[0].shape[0]))
+        self.ws_proj = alloc_workspace(proj_bytes, d) if proj_bytes else None  # small token counts: split-K partials
         self.target_ids = torch.empty(T, dtype=torch.int32, device=d)
         self.accept_len = torch.empty(B, dtype=torch.int32, device=d)
         self.accept_path = torch.empty((B, max_path), dtype=torch.int32, device=d)
@@ -287,12 +297,13 @@ class VerifyLayerStack:
             y = self.hidden[1 + (l & 1)]
             kp, vp = self.pools[l]
             mark("qkv_rope_project")
-            hb.hb_qkv_rope_project(x, self.w_qkv[l], None, self.cos, self.sin, self.q, self.k_tree[l], self.v_tree[l])
+            hb.hb_qkv_rope_project_ws(x, self.w_qkv[l], None, self.cos, self.sin, self.q, self.k_tree[l],
+                                      self.v_tree[l], self.ws_proj)
             mark("tree_verify_attn")
             hb.hb_tree_verify_attn(desc, self.q, self.k_tree[l], self.v_tree[l], kp, vp, dev.block_table,
                                    dev.prefix_len, dev.node_offset, dev.parent, self.attn_out, None, self.ws_attn)
             mark("out_project")
-            hb.hb_out_project(self.attn_out.view(T, -1), self.w_o[l], x, y)
+            hb.hb_out_project_ws(self.attn_out.view(T, -1), self.w_o[l], x, y, self.ws_proj)
             x = y
         self.final_hidden = x
         mark("lmhead_argmax")

@@ -51,10 +51,22 @@ def test_positions_and_rope_table(hb):
 
 
 @pytest.mark.parametrize("T,K,Hq,Hkv,bias", [(960, 3584, 28, 4, True), (128, 3584, 28, 4, False), (77, 128, 2, 1, True),
-                                             (300, 320, 3, 3, False), (1, 64, 1, 1, True), (513, 192, 8, 2, True),
+                                             (300, 320, 3, 3, False), (300, 320, 3, 3, True), (1, 64, 1, 1, True), (513, 192, 8, 2, True),
                                              (100, 256, 2, 1, True), (1, 512, 1, 1, True), (16, 768, 3, 3, False),
                                              (128, 1024, 4, 2, True)])
 def test_qkv_projection_with_rotary_embedding(hb, T, K, Hq, Hkv, bias):
+    _qkv_case(hb, T, K, Hq, Hkv, bias, False)
+
+
+@pytest.mark.parametrize("T,K,Hq,Hkv,bias", [(128, 3584, 28, 4, True), (100, 256, 2, 1, True), (1, 512, 1, 1, False),
+                                             (64, 768, 3, 3, True), (65, 1024, 4, 2, False), (300, 320, 3, 3, True)])
+def test_qkv_projection_split_over_k(hb, T, K, Hq, Hkv, bias):
+    """The workspace variant: at most 128 tokens take the split-K path (also when K gives a single
+    part), more tokens the ordinary one."""
+    _qkv_case(hb, T, K, Hq, Hkv, bias, True)
+
+
+def _qkv_case(hb, T, K, Hq, Hkv, bias, with_workspace):
     g = torch.Generator().manual_seed(T * 7 + K)
     hidden = torch.randn((T, K), generator=g).to(torch.bfloat16)
     w = (torch.randn(((Hq + 2 * Hkv) * 128, K), generator=g) * (1.0 / np.sqrt(K))).to(torch.bfloat16)
@@ -67,7 +79,13 @@ def test_qkv_projection_with_rotary_embedding(hb, T, K, Hq, Hkv, bias):
     q = torch.full((T, Hq, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
     k = torch.full((T, Hkv, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
     v = torch.full((T, Hkv, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
-    hb.hb_qkv_rope_project(hidden.cuda(), w.cuda(), None if b is None else b.cuda(), cos, sin, q, k, v)
+    if with_workspace:
+        nbytes = hb.hb_proj_workspace_bytes(T, K, (Hq + 2 * Hkv) * 128)
+        assert (nbytes > 0) == (T <= 128 and K >= 1024)
+        ws = torch.full((max(nbytes, 16),), 0xFF, dtype=torch.uint8, device="cuda")  # NaN patterns: nothing may be read unwritten
+        hb.hb_qkv_rope_project_ws(hidden.cuda(), w.cuda(), None if b is None else b.cuda(), cos, sin, q, k, v, ws)
+    else:
+        hb.hb_qkv_rope_project(hidden.cuda(), w.cuda(), None if b is None else b.cuda(), cos, sin, q, k, v)
     torch.cuda.synchronize()
     rq, rk, rv = qkv_rope_project_ref(W.widen(hidden), W.widen(w), None if b is None else W.widen(b), pos.numpy(),
                                       Hq, Hkv, 128, theta)
@@ -79,12 +97,28 @@ def test_qkv_projection_with_rotary_embedding(hb, T, K, Hq, Hkv, bias):
                                        (128, 3584, 3584, True), (37, 256, 20, True), (5, 512, 1000, False),
                                        (96, 10752, 3584, False), (1, 256, 4, True)])
 def test_output_projection(hb, T, K, N, res):
+    _out_case(hb, T, K, N, res, False)
+
+
+@pytest.mark.parametrize("T,K,N,res", [(128, 3584, 3584, True), (96, 10752, 3584, False), (37, 256, 20, True),
+                                       (5, 512, 1000, False), (1, 1024, 4, True), (64, 2048, 260, True),
+                                       (129, 512, 512, True)])
+def test_output_projection_split_over_k(hb, T, K, N, res):
+    _out_case(hb, T, K, N, res, True)
+
+
+def _out_case(hb, T, K, N, res, with_workspace):
     g = torch.Generator().manual_seed(T + K + N)
     x = torch.randn((T, K), generator=g).to(torch.bfloat16)
     w = (torch.randn((N, K), generator=g) * (1.0 / np.sqrt(K))).to(torch.bfloat16)
     r = torch.randn((T, N), generator=g).to(torch.bfloat16) if res else None
     out = torch.full((T, N), float("nan"), dtype=torch.bfloat16, device="cuda")
-    hb.hb_out_project(x.cuda(), w.cuda(), None if r is None else r.cuda(), out)
+    if with_workspace:
+        nbytes = hb.hb_proj_workspace_bytes(T, K, N)
+        ws = torch.full((max(nbytes, 16),), 0xFF, dtype=torch.uint8, device="cuda")
+        hb.hb_out_project_ws(x.cuda(), w.cuda(), None if r is None else r.cuda(), out, ws)
+    else:
+        hb.hb_out_project(x.cuda(), w.cuda(), None if r is None else r.cuda(), out)
     torch.cuda.synchronize()
     _close(out, linear_ref(W.widen(x), W.widen(w), None if r is None else W.widen(r)), "out")
 
