@@ -100,6 +100,56 @@ int main(void) {
   CHECK(hb_kv_compact(&d, (char *)p + 2, p, p, p, p, p, p, p, p, 6, NULL, NULL, NULL) == HB_ERR_INVALID_ARG);
   d.batch = 0;
   CHECK(hb_kv_compact(&d, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 6, NULL, NULL, NULL) == HB_OK);
+
+  /* sampling acceptance, projections, draft tree, meta queries: every call below fails or is a
+   * no-op on host-visible arguments */
+  CHECK(hb_tree_accept_sample(2, 65, 100, p, p, p, p, p, p, p, 6, p, p, p, p, p, 1 << 20, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_tree_accept_sample(2, 60, 100, p, p, p, p, p, p, p, 6, p, p, p, p, p, 8, NULL) == HB_ERR_WORKSPACE);
+  CHECK(hb_tree_accept_sample(0, 60, 100, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 6, NULL, NULL, NULL, NULL, NULL, 0, NULL) == HB_OK);
+  CHECK(hb_tree_accept_sample_workspace_bytes(16, 152064) == (size_t)16 * 152064 * 4);
+  CHECK(hb_tree_positions(2, 65, 120, p, p, p, p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_rope_table(4, 127, 1e6, p, p, p, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_rope_table(0, 128, 1e6, NULL, NULL, NULL, NULL) == HB_OK);
+  CHECK(hb_qkv_rope_project(4, 3584, 28, 4, 64, p, p, NULL, p, p, p, p, p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_qkv_rope_project(4, 100, 28, 4, 128, p, p, NULL, p, p, p, p, p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_qkv_rope_project(4, 3584, 28, 4, 128, p, NULL, NULL, p, p, p, p, p, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_qkv_rope_project_ws(4, 3584, 28, 4, 128, (char *)p + 2, p, NULL, p, p, p, p, p, p, 64, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_out_project(4, 64, 6, p, p, NULL, p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_out_project_ws(4, 64, 8, p, p, NULL, NULL, p, 64, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_out_project_ws(0, 64, 8, NULL, NULL, NULL, NULL, NULL, 0, NULL) == HB_OK);
+  for (int t = 1; t <= 200; t += 33)
+    for (int k = 64; k <= 16384; k *= 2)
+      for (int n = 4; n <= 200000; n *= 7) {
+        size_t ws = hb_proj_workspace_bytes(t, k, n);
+        CHECK(t <= 128 || ws == 0);
+        CHECK(ws % 4 == 0 && ws <= (size_t)256 * 128 * 4 * (size_t)(n + 255));
+      }
+  CHECK(hb_topk_logprob(HB_F32, 4, 100, 0, p, p, (float *)p, p, 1 << 20, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_topk_logprob(HB_F32, 4, 100, 33, p, p, (float *)p, p, 1 << 20, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_topk_logprob(HB_F32, 4, 100, 5, p, p, (float *)p, p, 8, NULL) == HB_ERR_WORKSPACE);
+  CHECK(hb_topk_logprob(HB_BF16, 0, 100, 5, NULL, NULL, NULL, NULL, 0, NULL) == HB_OK);
+  for (int m = 1; m <= 3000; m = m * 5 + 1)
+    for (int v = 1; v <= 2000000; v = v * 11 + 3) {
+      size_t ws = hb_topk_logprob_workspace_bytes(m, v, 10);
+      CHECK(ws >= (size_t)m * 88 && ws <= (size_t)m * 88 * (size_t)(v / 2048 + 1));
+    }
+  CHECK(hb_draft_tree_candidates(10, 5) == 410 && hb_draft_tree_candidates(0, 5) == 0);
+  CHECK(hb_tree_grow(2, 10, 5, 5, p, (float *)p, (float *)p, p, p, p, p, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_tree_grow(2, 40, 5, 0, p, (float *)p, (float *)p, p, p, p, p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_tree_grow(0, 10, 5, 0, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) == HB_OK);
+  CHECK(hb_tree_finalize(2, 10, 5, 65, (float *)p, p, p, p, p, p, p, p, (uint64_t *)p, p, (float *)p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_tree_finalize(2, 2, 2, 8, (float *)p, p, p, p, p, p, p, p, (uint64_t *)p, p, (float *)p, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_tree_finalize(0, 10, 5, 60, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) == HB_OK);
+  CHECK(hb_meta_query_fold_bytes(3, 3584, 28) == (size_t)2 * 96 * 3584 * 2);
+  CHECK(hb_meta_query_fold(3, 3584, 27, p, p, p, p, p, 1 << 20, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_meta_query_fold(3, 3584, 28, p, p, p, p, p, 16, NULL) == HB_ERR_WORKSPACE);
+  {
+    int32_t layers_bad[3] = {0, 14, 28}, layers_ok[3] = {0, 14, 27};
+    CHECK(hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers_bad, p, p, NULL) == HB_ERR_INVALID_ARG);
+    CHECK(hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers_ok, p, NULL, NULL) == HB_ERR_INVALID_ARG);
+    CHECK(hb_meta_query_attn(4, 33, 3584, 28, 3, p, p, p, NULL, p, NULL, NULL) == HB_ERR_UNSUPPORTED);
+    CHECK(hb_meta_query_attn(0, 28, 3584, 28, 3, NULL, NULL, NULL, layers_ok, NULL, p, NULL) == HB_OK);
+  }
   printf("host shim checks passed\n");
   return 0;
 }
