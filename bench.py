@@ -355,15 +355,11 @@ def bench_draft_tree(steps, warmup, B=16, K=10, T=5, N=60, V=152064):
     outs = (i32(B + 1), i32(n), i32(n), i32(n), torch.empty(n, dtype=torch.int64, device="cuda"), i32(n),
             torch.empty(n, dtype=torch.float32, device="cuda"))
 
-    def build(i, ev=None):
+    def build(i):
         for level in range(T):
             x = roots[(i + level) % 3] if level == 0 else sets[(i + level) % 3]
             ids, lp = (ids0, lp0) if level == 0 else (ids1, lp1)
-            if ev is not None and level == 1:
-                ev[0].record()
             hb.hb_topk_logprob(x, K, ids, lp, ws)
-            if ev is not None and level == 1:
-                ev[1].record()
             hb.hb_tree_grow(B, K, T, level, ids, lp, builder.cand_score, builder.cand_token, builder.cand_parent,
                             builder.frontier, builder.frontier_slot)
         hb.hb_tree_finalize(B, K, T, N, builder.cand_score, builder.cand_token, builder.cand_parent, root_token, *outs)
@@ -376,11 +372,15 @@ def bench_draft_tree(steps, warmup, B=16, K=10, T=5, N=60, V=152064):
         build(i)
     torch.cuda.synchronize()
     ms_build = (time.perf_counter() - t0) * 1e3 / steps
-    ev = _events(steps)
-    for i, e in enumerate(ev):
-        build(i, e)
+    # the top-k pass of one level (160 rows) alone: back-to-back calls over the rotating logits,
+    # one event pair around all of them (an event pair per call would add its own 10-20 us)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for i in range(steps):
+        hb.hb_topk_logprob(sets[i % 3], K, ids1, lp1, ws)
+    b.record()
     torch.cuda.synchronize()
-    ms_topk = _mean_ms(ev)
+    ms_topk = a.elapsed_time(b) / steps
     level_bytes = B * K * V * 4
     return {
         "what": f"{B} trees of {N} nodes from {K} children per node over {T} levels, vocabulary {V}, float32 logits; "

@@ -101,9 +101,10 @@ __device__ __forceinline__ int pos_of(bool vec, int j, int n, int n_full) {
 
 // Pass 1 of the top-k: one workgroup per (chunk, row).  The chunk goes from memory straight into
 // registers (every load is in flight before the first value is used).  The k best entries are
-// found without sorting: the k-th largest of the 256 per-thread maxima is a lower bound T of the
-// chunk's k-th largest value, so only values >= T can be among the k best; those few are
-// collected in LDS (as order-preserving keys) and the k best picked there by counting ranks.
+// found without sorting: a threshold T that at least k values of the chunk reach (from the
+// per-thread maxima, see below) is a lower bound of the chunk's k-th largest value, so only values
+// >= T can be among the k best; those few are collected in LDS (as order-preserving keys) and
+// the k best picked there by counting ranks.
 // Many equal values can let more pass than the list holds; then k rounds of a workgroup-wide
 // maximum run over the registers instead (same result, slower).
 template <typename T>
@@ -114,9 +115,8 @@ __global__ __launch_bounds__(kThreads) void topk_chunk_kernel(int V, int k, int 
   __shared__ float fred[kThreads / 64];
   __shared__ unsigned long long win[kMaxTopK];
   __shared__ unsigned long long list[kListCap];
-  __shared__ unsigned long long tmax[kThreads];
   __shared__ int list_n;
-  __shared__ float thr_s;
+  __shared__ float thr_w[kThreads / 64];
   constexpr int PER = 16 / (int)sizeof(T);
   const int c = blockIdx.x, m = blockIdx.y;
   const int tid = threadIdx.x;
@@ -160,30 +160,48 @@ __global__ __launch_bounds__(kThreads) void topk_chunk_kernel(int V, int k, int 
 #pragma unroll
   for (int j = 0; j <= kPerThread; ++j) mt = fmaxf(mt, x[j]);
   const float mx = wg_max_f(mt, fred);
-  // T = the k-th largest of the threads' maxima (threads without a value do not take part):
-  // every thread counts the maxima above its own; the one that finds k - 1 holds T
+  // Threshold T with at least k values >= T in the chunk: every wavefront takes the k-th largest
+  // of its 64 lane maxima (a lane counts the maxima strictly above its own, lane by lane through
+  // readlane; the smallest maximum with fewer than k above it is the k-th largest), which k of its
+  // own values reach; T is the largest of the wavefronts' thresholds.  A wavefront with fewer
+  // than k lanes holding values sets no threshold; if none does, everything passes.
   const bool has = pos_of<PER>(vec, 0, n, n_full) < n || pos_of<PER>(vec, kPerThread, n, n_full) < n;
-  const unsigned long long mine = has ? sel_key(mt, (uint32_t)tid) : 0ull;
-  tmax[tid] = mine;
-  if (tid == 0) thr_s = ninf;  // fewer than k threads hold values: everything passes
-  __syncthreads();
-  {
-    int rank = 0;
-#pragma unroll 8
-    for (int j = 0; j < kThreads; ++j) rank += tmax[j] > mine ? 1 : 0;
-    if (has && rank == k - 1) thr_s = mt;
-  }
-  __syncthreads();
-  const float thr = thr_s;
-  float sum = 0.f;
-  const bool any = mx > ninf;
+  int above = 0;
 #pragma unroll
-  for (int j = 0; j <= kPerThread; ++j) {
-    const int p = pos_of<PER>(vec, j, n, n_full);
-    if (any) sum += __expf(x[j] - mx);  // values the thread does not own are -inf and add 0
-    if (p < n && x[j] >= thr) {
-      const int at = atomicAdd(&list_n, 1);
-      if (at < kListCap) list[at] = sel_key(x[j], (uint32_t)(v0 + p));
+  for (int l = 0; l < 64; ++l) {
+    const float other = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mt), l));
+    above += other > mt ? 1 : 0;
+  }
+  const int holders = __popcll(__ballot(has));
+  float tw = (has && above < k) ? mt : __builtin_huge_valf();
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) tw = fminf(tw, __shfl_xor(tw, off, 64));
+  if (holders < k) tw = ninf;
+  if ((tid & 63) == 0) thr_w[tid >> 6] = tw;
+  __syncthreads();
+  const float thr = fmaxf(fmaxf(thr_w[0], thr_w[1]), fmaxf(thr_w[2], thr_w[3]));
+  float sum = 0.f;
+  if (thr > ninf) {
+    // the common case: values the thread does not own are -inf, fail the test and add exp(-inf) = 0
+    const float c1 = 1.4426950408889634f, c0 = -mx * 1.4426950408889634f;
+#pragma unroll
+    for (int j = 0; j <= kPerThread; ++j) {
+      sum += __builtin_amdgcn_exp2f(fmaf(x[j], c1, c0));
+      if (x[j] >= thr) {
+        const int at = atomicAdd(&list_n, 1);
+        if (at < kListCap) list[at] = sel_key(x[j], (uint32_t)(v0 + pos_of<PER>(vec, j, n, n_full)));
+      }
+    }
+  } else {
+    const bool any = mx > ninf;
+#pragma unroll
+    for (int j = 0; j <= kPerThread; ++j) {
+      const int p = pos_of<PER>(vec, j, n, n_full);
+      if (any) sum += __expf(x[j] - mx);
+      if (p < n) {
+        const int at = atomicAdd(&list_n, 1);
+        if (at < kListCap) list[at] = sel_key(x[j], (uint32_t)(v0 + p));
+      }
     }
   }
   sum = wg_sum_f(sum, fred);  // its barriers also publish list and list_n
