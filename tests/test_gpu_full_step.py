@@ -145,6 +145,55 @@ def test_greedy_losslessness_with_the_matrix_core_kernels_in_the_loop(bf16_toy, 
         assert all(l == full for l in lens[:-1])
 
 
+@pytest.mark.parametrize("K,T,N", [(3, 4, 12), (4, 3, 20), (1, 5, 6)])
+def test_greedy_losslessness_with_trees_built_on_the_device(bf16_toy, K, T, N):
+    """Draft logits -> hb_topk_logprob -> hb_tree_grow per level -> hb_tree_finalize -> verification
+    -> acceptance -> compaction, in a loop: whatever the draft proposes, the emitted stream is the
+    plain greedy stream.  The 'draft model' is a seeded table of logits per token path that
+    favours the true next token along the committed stream with a margin that shrinks with depth
+    (so deeper levels branch and miss more), and anything otherwise."""
+    import paper_2509_18824_amd.step as St
+    from toy_gpu import ToyDecoderGpu
+    w, prompt, stream = bf16_toy
+    n_new = len(stream)
+    full = list(prompt) + list(stream)
+    V = w.vocab
+
+    def draft_logits(paths):
+        out = np.empty((len(paths), V), dtype=np.float32)
+        for i, path in enumerate(paths):
+            rng = np.random.default_rng([77, len(path)] + [int(t) for t in path[-6:]])
+            row = rng.normal(0, 1.5, size=V).astype(np.float32)
+            if len(path) < len(full) and list(path) == full[:len(path)]:
+                row[full[len(path)]] += np.float32(6.0 - 1.2 * (len(path) - len(prompt)) % 5)
+            out[i] = row
+        return torch.from_numpy(out).cuda()
+
+    lens_seen = []
+
+    def tree_builder(step, toks):
+        builder = St.DraftTreeBuilder(1, K, T)
+        paths = [list(toks)]
+        for level in range(T):
+            ids, logp = St.topk_logprob(draft_logits(paths), K)
+            frontier, slot = builder.grow(ids, logp)
+            torch.cuda.synchronize()
+            cand_tok = builder.cand_token[0].cpu().numpy()
+            paths = [paths[s] + [int(cand_tok[c])] for c, s in zip(frontier[0].tolist(), slot[0].tolist())]
+        out = builder.finalize(N, torch.tensor([toks[-1]], dtype=torch.int32, device="cuda"))
+        torch.cuda.synchronize()
+        parent = out["parent"].cpu().numpy()
+        ids = out["draft_ids"].cpu().numpy()
+        assert len(parent) == min(N, 1 + K + (T - 1) * K * K) and parent[0] == -1 and ids[0] == toks[-1]
+        return parent, ids
+
+    table = np.random.default_rng(5).permutation(16)
+    gpu = ToyDecoderGpu(w, n_blocks=16, dtype="bf16")
+    out, lens = gpu.spec_decode(prompt, n_new, None, None, table, tree_builder=tree_builder)
+    assert out == stream
+    assert max(lens) >= 2  # the draft was right often enough to accept something
+
+
 def test_full_step_replays_from_a_hip_graph(S):
     """The four calls only enqueue kernels on the caller's stream (no allocation, no memset, no
     host synchronisation), so a step can be captured into a HIP graph.  The graph is replayed

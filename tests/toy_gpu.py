@@ -55,7 +55,9 @@ class ToyDecoderGpu:
         h = self._rms(x, lw["n2"])
         return x + (torch.nn.functional.silu(h @ lw["wg"]) * (h @ lw["wu"])) @ lw["wd"]
 
-    def spec_decode(self, prompt, n_new, drafter, tree_for_step, block_table, algo=0):
+    def spec_decode(self, prompt, n_new, drafter, tree_for_step, block_table, algo=0, tree_builder=None):
+        """tree_builder(step, tokens) -> (parent, draft_ids), when given, replaces the pair
+        (tree_for_step, drafter): the tree's shape then comes with its tokens."""
         w, dev, page = self.w, self.dev, self.page
         bt = torch.tensor(np.asarray(block_table).reshape(1, -1), dtype=torch.int32, device=dev)
         pools = [(torch.zeros((self.n_blocks, w.Hkv, page, w.Dh), device=dev, dtype=self.tdt),
@@ -90,13 +92,14 @@ class ToyDecoderGpu:
             L += n
             prefix_len.fill_(L)
         while len(out) < n_new:
-            par_np = np.asarray(tree_for_step(step), dtype=np.int32)
+            built = tree_builder(step, list(toks)) if tree_builder is not None else None
+            par_np = np.asarray(built[0] if built is not None else tree_for_step(step), dtype=np.int32)
             n = len(par_np)
             depth = np.zeros(n, dtype=np.int64)
             for i in range(1, n):
                 depth[i] = depth[par_np[i]] + 1
             max_path = int(depth.max()) + 1
-            draft = np.asarray(drafter(list(toks), par_np), dtype=np.int32).copy()
+            draft = np.asarray(built[1] if built is not None else drafter(list(toks), par_np), dtype=np.int32).copy()
             draft[0] = toks[-1]
             parent = torch.from_numpy(par_np).to(dev)
             node_offset = torch.tensor([0, n], dtype=torch.int32, device=dev)
