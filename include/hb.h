@@ -292,6 +292,20 @@ int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *
                       int32_t *out_slots, int32_t *new_len, void *stream);
 
 /*
+ * hb_kv_compact for every layer of the model in one launch (the same accepted path goes into
+ * each layer's cache; Section 4.1: committed context lives in the KV cache).  k_tree, v_tree,
+ * k_pool, v_pool are DEVICE arrays of n_layers device pointers (8-byte aligned tables; every
+ * tensor as in hb_kv_compact, 16-byte aligned, which the call cannot check on the host).  The
+ * page table, lengths and path are shared by the layers; out_slots and new_len (optional) are
+ * written once.  Errors: INVALID_ARG, UNSUPPORTED, DEVICE.  n_layers == 0 is a no-op.
+ */
+int32_t hb_kv_compact_layers(const hb_attn_desc *desc, int32_t n_layers, const void *const *k_tree,
+                             const void *const *v_tree, void *const *k_pool, void *const *v_pool,
+                             const int32_t *block_table, const int32_t *prefix_len, const int32_t *node_offset,
+                             const int32_t *accept_len, const int32_t *accept_path, int32_t max_path,
+                             int32_t *out_slots, int32_t *new_len, void *stream);
+
+/*
  * Construction of the draft tree from the draft model's outputs: the step before the
  * verification (the paper drafts in the EAGLE-3 manner, Section 3.1, and leaves the arrangement of
  * the drafted tokens open; its measurements use chains, Section 4.2).  This is the dynamic tree of

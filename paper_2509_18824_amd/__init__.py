@@ -29,6 +29,7 @@ from .binding import (
     hb_tree_accept_sample,
     hb_tree_accept_sample_workspace_bytes,
     hb_kv_compact,
+    hb_kv_compact_layers,
     hb_topk_logprob,
     hb_topk_logprob_workspace_bytes,
     hb_draft_tree_candidates,

@@ -102,6 +102,8 @@ def _load():
     lib.hb_meta_query_attn.argtypes = [i32] * 5 + [p, p, p, C.POINTER(i32), p, p, p]
     lib.hb_kv_compact.restype = i32
     lib.hb_kv_compact.argtypes = [C.POINTER(AttnDesc)] + [p] * 9 + [i32, p, p, p]
+    lib.hb_kv_compact_layers.restype = i32
+    lib.hb_kv_compact_layers.argtypes = [C.POINTER(AttnDesc), i32] + [p] * 9 + [i32, p, p, p]
     return lib
 
 
@@ -332,3 +334,16 @@ def hb_kv_compact(desc: AttnDesc, k_tree, v_tree, k_pool, v_pool, block_table, p
     _check(lib.hb_kv_compact(C.byref(desc), _ptr(k_tree), _ptr(v_tree), _ptr(k_pool), _ptr(v_pool),
                              _ptr(block_table), _ptr(prefix_len), _ptr(node_offset), _ptr(accept_len),
                              _ptr(accept_path), max_path, _ptr(out_slots), _ptr(new_len), _stream(stream)))
+
+
+def hb_kv_compact_layers(desc: AttnDesc, n_layers: int, k_tree_ptrs, v_tree_ptrs, k_pool_ptrs, v_pool_ptrs,
+                         block_table, prefix_len, node_offset, accept_len, accept_path, max_path: int,
+                         out_slots=None, new_len=None, stream=None) -> None:
+    """*_ptrs: int64 device tensors holding the data pointers of every layer's tensor."""
+    for t in (k_tree_ptrs, v_tree_ptrs, k_pool_ptrs, v_pool_ptrs):
+        if t.dtype != torch.int64 or t.numel() < n_layers:
+            raise ValueError("pointer tables must be int64 tensors with one entry per layer")
+    _check(lib.hb_kv_compact_layers(C.byref(desc), n_layers, _ptr(k_tree_ptrs), _ptr(v_tree_ptrs), _ptr(k_pool_ptrs),
+                                    _ptr(v_pool_ptrs), _ptr(block_table), _ptr(prefix_len), _ptr(node_offset),
+                                    _ptr(accept_len), _ptr(accept_path), max_path, _ptr(out_slots), _ptr(new_len),
+                                    _stream(stream)))

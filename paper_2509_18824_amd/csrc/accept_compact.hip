@@ -90,8 +90,9 @@ __global__ __launch_bounds__(64) void tree_accept_kernel(
   }
 }
 
-__global__ __launch_bounds__(256) void kv_compact_kernel(
-    hb_attn_desc d, int row_bytes, const uint4 *__restrict__ k_tree, const uint4 *__restrict__ v_tree,
+// one (path slot j, sequence b) of one layer; out_slots / new_len are written when given
+__device__ __forceinline__ void compact_one(
+    const hb_attn_desc &d, int row_bytes, const uint4 *__restrict__ k_tree, const uint4 *__restrict__ v_tree,
     uint4 *__restrict__ k_pool, uint4 *__restrict__ v_pool, const int32_t *__restrict__ block_table,
     const int32_t *__restrict__ prefix_len, const int32_t *__restrict__ node_offset,
     const int32_t *__restrict__ accept_len, const int32_t *__restrict__ accept_path, int max_path,
@@ -129,6 +130,28 @@ __global__ __launch_bounds__(256) void kv_compact_kernel(
   }
 }
 
+__global__ __launch_bounds__(256) void kv_compact_kernel(
+    hb_attn_desc d, int row_bytes, const uint4 *__restrict__ k_tree, const uint4 *__restrict__ v_tree,
+    uint4 *__restrict__ k_pool, uint4 *__restrict__ v_pool, const int32_t *__restrict__ block_table,
+    const int32_t *__restrict__ prefix_len, const int32_t *__restrict__ node_offset,
+    const int32_t *__restrict__ accept_len, const int32_t *__restrict__ accept_path, int max_path,
+    int32_t *__restrict__ out_slots, int32_t *__restrict__ new_len) {
+  compact_one(d, row_bytes, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset, accept_len,
+              accept_path, max_path, out_slots, new_len);
+}
+
+// all layers in one launch: blockIdx.z = layer, its tensors from tables of device pointers
+__global__ __launch_bounds__(256) void kv_compact_layers_kernel(
+    hb_attn_desc d, int row_bytes, const uint4 *const *__restrict__ k_tree, const uint4 *const *__restrict__ v_tree,
+    uint4 *const *__restrict__ k_pool, uint4 *const *__restrict__ v_pool, const int32_t *__restrict__ block_table,
+    const int32_t *__restrict__ prefix_len, const int32_t *__restrict__ node_offset,
+    const int32_t *__restrict__ accept_len, const int32_t *__restrict__ accept_path, int max_path,
+    int32_t *__restrict__ out_slots, int32_t *__restrict__ new_len) {
+  const int l = blockIdx.z;
+  compact_one(d, row_bytes, k_tree[l], v_tree[l], k_pool[l], v_pool[l], block_table, prefix_len, node_offset,
+              accept_len, accept_path, max_path, l == 0 ? out_slots : nullptr, l == 0 ? new_len : nullptr);
+}
+
 }  // namespace
 
 hipError_t launch_tree_accept(int32_t B, int32_t max_nodes, const int32_t *node_offset,
@@ -151,6 +174,21 @@ hipError_t launch_kv_compact(const hb_attn_desc &d, const void *k_tree, const vo
   kv_compact_kernel<<<grid, 256, 0, s>>>(d, row_bytes, (const uint4 *)k_tree, (const uint4 *)v_tree,
                                          (uint4 *)k_pool, (uint4 *)v_pool, block_table, prefix_len,
                                          node_offset, accept_len, accept_path, max_path, out_slots, new_len);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_compact_layers(const hb_attn_desc &d, int32_t n_layers, const void *const *k_tree,
+                                    const void *const *v_tree, void *const *k_pool, void *const *v_pool,
+                                    const int32_t *block_table, const int32_t *prefix_len,
+                                    const int32_t *node_offset, const int32_t *accept_len,
+                                    const int32_t *accept_path, int32_t max_path, int32_t *out_slots,
+                                    int32_t *new_len, hipStream_t s) {
+  int row_bytes = d.head_dim * (d.dtype == HB_F32 ? 4 : 2);
+  dim3 grid((unsigned)max_path, (unsigned)d.batch, (unsigned)n_layers);
+  kv_compact_layers_kernel<<<grid, 256, 0, s>>>(d, row_bytes, (const uint4 *const *)k_tree, (const uint4 *const *)v_tree,
+                                                (uint4 *const *)k_pool, (uint4 *const *)v_pool, block_table,
+                                                prefix_len, node_offset, accept_len, accept_path, max_path,
+                                                out_slots, new_len);
   return hipGetLastError();
 }
 

@@ -555,4 +555,25 @@ int32_t hb_kv_compact(const hb_attn_desc *desc, const void *k_tree, const void *
   return HB_OK;
 }
 
+int32_t hb_kv_compact_layers(const hb_attn_desc *desc, int32_t n_layers, const void *const *k_tree,
+                             const void *const *v_tree, void *const *k_pool, void *const *v_pool,
+                             const int32_t *block_table, const int32_t *prefix_len, const int32_t *node_offset,
+                             const int32_t *accept_len, const int32_t *accept_path, int32_t max_path,
+                             int32_t *out_slots, int32_t *new_len, void *stream) {
+  int32_t rc = check_shape(desc);
+  if (rc) return rc;
+  if (max_path <= 0 || n_layers < 0) return fail(HB_ERR_INVALID_ARG, "need max_path > 0 and n_layers >= 0");
+  if (n_layers > 65535) return fail(HB_ERR_UNSUPPORTED, "n_layers %d: at most 65535 layers per call", n_layers);
+  if (desc->batch == 0 || n_layers == 0) return HB_OK;
+  if (!k_tree || !v_tree || !k_pool || !v_pool || !block_table || !prefix_len || !node_offset || !accept_len ||
+      !accept_path)
+    return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (((uintptr_t)k_tree | (uintptr_t)v_tree | (uintptr_t)k_pool | (uintptr_t)v_pool) & 7)
+    return fail(HB_ERR_INVALID_ARG, "the pointer tables must be 8-byte aligned");
+  HB_HIP_TRY(launch_kv_compact_layers(*desc, n_layers, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len,
+                                      node_offset, accept_len, accept_path, max_path, out_slots, new_len,
+                                      (hipStream_t)stream));
+  return HB_OK;
+}
+
 }  // extern "C"

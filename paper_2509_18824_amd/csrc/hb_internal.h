@@ -132,6 +132,13 @@ hipError_t launch_kv_compact(const hb_attn_desc &d, const void *k_tree, const vo
                              const int32_t *accept_len, const int32_t *accept_path,
                              int32_t max_path, int32_t *out_slots, int32_t *new_len, hipStream_t s);
 
+hipError_t launch_kv_compact_layers(const hb_attn_desc &d, int32_t n_layers, const void *const *k_tree,
+                                    const void *const *v_tree, void *const *k_pool, void *const *v_pool,
+                                    const int32_t *block_table, const int32_t *prefix_len,
+                                    const int32_t *node_offset, const int32_t *accept_len,
+                                    const int32_t *accept_path, int32_t max_path, int32_t *out_slots,
+                                    int32_t *new_len, hipStream_t s);
+
 // ---- argmax key: (order-preserving float bits << 32) | (0xffffffff - index) ---------------
 // max over keys = largest value, lowest index among equal values.  NaN is mapped to -inf.
 __device__ inline unsigned long long argmax_key(float v, uint32_t idx) {

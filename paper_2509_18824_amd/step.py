@@ -282,6 +282,10 @@ class VerifyLayerStack:
         self.bonus = torch.empty(B, dtype=torch.int32, device=d)
         self.out_slots = torch.empty((B, max_path), dtype=torch.int32, device=d)
         self.new_len = torch.empty(B, dtype=torch.int32, device=d)
+        # tables of every layer's tensor addresses, for the compaction of all layers in one launch
+        table = lambda ts: torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=d)
+        self.ptr_tables = (table(self.k_tree), table(self.v_tree), table([p[0] for p in pools]),
+                           table([p[1] for p in pools]))
 
     def run(self, compact=True, on_call=None):
         """``on_call(name)`` (optional) is invoked before every library call, e.g. to record events."""
@@ -314,9 +318,7 @@ class VerifyLayerStack:
                           self.bonus)
         if compact:
             mark("kv_compact")
-            for l in range(self.n_layers):
-                kp, vp = self.pools[l]
-                hb.hb_kv_compact(desc, self.k_tree[l], self.v_tree[l], kp, vp, dev.block_table, dev.prefix_len,
-                                 dev.node_offset, self.accept_len, self.accept_path, self.max_path, self.out_slots,
-                                 self.new_len)
+            hb.hb_kv_compact_layers(desc, self.n_layers, *self.ptr_tables, dev.block_table, dev.prefix_len,
+                                    dev.node_offset, self.accept_len, self.accept_path, self.max_path,
+                                    self.out_slots, self.new_len)
         mark("end")

@@ -112,6 +112,17 @@ def test_lmhead_accept_compact_argument_errors():
     assert "aligned" in hb.hb_last_error()
 
 
+def test_all_layer_compaction_argument_errors():
+    L, p = hb.lib, C.c_void_p(0x1000)
+    d = _desc()
+    assert L.hb_kv_compact_layers(C.byref(d), 28, p, p, p, p, p, p, p, p, p, 0, None, None, None) == 1
+    assert L.hb_kv_compact_layers(C.byref(d), -1, p, p, p, p, p, p, p, p, p, 6, None, None, None) == 1
+    assert L.hb_kv_compact_layers(C.byref(d), 28, None, p, p, p, p, p, p, p, p, 6, None, None, None) == 1
+    assert L.hb_kv_compact_layers(C.byref(d), 28, C.c_void_p(0x1004), p, p, p, p, p, p, p, p, 6, None, None, None) == 1
+    assert L.hb_kv_compact_layers(C.byref(d), 0, None, None, None, None, None, None, None, None, None, 6, None, None, None) == 0
+    assert L.hb_kv_compact_layers(None, 28, p, p, p, p, p, p, p, p, p, 6, None, None, None) == 1
+
+
 def test_draft_tree_argument_errors():
     L, p = hb.lib, C.c_void_p(0x1000)
     assert L.hb_draft_tree_candidates(10, 5) == 410 and L.hb_draft_tree_candidates(1, 5) == 5

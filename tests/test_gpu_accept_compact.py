@@ -126,3 +126,33 @@ def test_compaction_is_a_bit_exact_scatter(step, dtype, Hkv, D):
     assert np.array_equal(slots.cpu().numpy(), ref_slots)
     assert np.array_equal(new_len.cpu().numpy(), ref_len)
     assert np.array_equal(bits(dev.k_pool), ref_k) and np.array_equal(bits(dev.v_pool), ref_v)
+
+
+def test_compaction_of_all_layers_in_one_launch(step):
+    """hb_kv_compact_layers: three layers with their own tree K/V and pools, one launch; every
+    layer's pools must equal the oracle's scatter of that layer's tensors, bit for bit."""
+    import paper_2509_18824_amd as hb
+    trees = [W.seeded_tree(b) for b in range(5)]
+    lens = [11, 30, 13, 47, 15]
+    layers = [W.make_verify_inputs(40 + l, "bf16", 8, 4, 128, lens, trees, poison=False) for l in range(3)]
+    inp = layers[0]
+    target = np.random.default_rng(3).integers(0, 500, size=inp.total_nodes)
+    draft, _ = W.plant_draft_ids(3, trees, target, 500, want_depth=[0, 5, 2, 3, 1])
+    alen, apath, _, _ = tree_accept_ref(inp.node_offset.numpy(), inp.parent.numpy(), draft, target, inp.max_path)
+    devs = [step.to_device(x) for x in layers]
+    # the page table and lengths are shared by the layers (those of layer 0)
+    refs = [kv_compact_ref(bits(x.k_tree), bits(x.v_tree), bits(x.k_pool), bits(x.v_pool), inp.block_table.numpy(),
+                           inp.prefix_len.numpy(), inp.node_offset.numpy(), alen, apath) for x in layers]
+    table = lambda ts: torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device="cuda")
+    B, max_path = apath.shape
+    slots = torch.full((B, max_path), -7, dtype=torch.int32, device="cuda")
+    new_len = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    d0 = devs[0]
+    hb.hb_kv_compact_layers(step.desc_for(inp), 3, table([d.k_tree for d in devs]), table([d.v_tree for d in devs]),
+                            table([d.k_pool for d in devs]), table([d.v_pool for d in devs]), d0.block_table,
+                            d0.prefix_len, d0.node_offset, torch.from_numpy(alen).cuda(), torch.from_numpy(apath).cuda(),
+                            max_path, slots, new_len)
+    torch.cuda.synchronize()
+    assert np.array_equal(slots.cpu().numpy(), refs[0][2]) and np.array_equal(new_len.cpu().numpy(), refs[0][3])
+    for d, (ref_k, ref_v, _, _) in zip(devs, refs):
+        assert np.array_equal(bits(d.k_pool), ref_k) and np.array_equal(bits(d.v_pool), ref_v)
