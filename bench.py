@@ -326,6 +326,32 @@ def achievable_peaks():
     out["bf16_gemm_lmhead_shape_ms"] = ms
     del h, w
     torch.cuda.empty_cache()
+    # the library's fused attention on the dense problem of the long-context workload's shape (per
+    # (sequence, kv head): 420 query rows against 32768 keys, head size 128, bf16, no mask, contiguous
+    # K/V): what a tuned library kernel reaches on this few-rows-many-keys shape, without paging,
+    # tree mask or split-K merge
+    try:
+        q = torch.randn(8, 1, 420, 128, device="cuda", dtype=torch.bfloat16)
+        kk = torch.randn(8, 1, 32768, 128, device="cuda", dtype=torch.bfloat16)
+        vv = torch.randn(8, 1, 32768, 128, device="cuda", dtype=torch.bfloat16)
+        ms = timed(lambda: torch.nn.functional.scaled_dot_product_attention(q, kk, vv))
+        out["sdpa_long_context_shape_ms"] = ms
+        out["sdpa_long_context_shape_TFLOPs"] = 4.0 * 8 * 420 * 32768 * 128 / (ms * 1e-3) / 1e12
+        del q, kk, vv
+        # the same flops with the keys cut into 32 chunks handed over as batch entries (the
+        # parallelism a split-K plan gives, without the merge): the library kernel's own rate on
+        # 420-row query tiles
+        q = torch.randn(256, 1, 420, 128, device="cuda", dtype=torch.bfloat16)
+        kk = torch.randn(256, 1, 1024, 128, device="cuda", dtype=torch.bfloat16)
+        vv = torch.randn(256, 1, 1024, 128, device="cuda", dtype=torch.bfloat16)
+        ms = timed(lambda: torch.nn.functional.scaled_dot_product_attention(q, kk, vv))
+        out["sdpa_presplit_ms"] = ms
+        out["sdpa_presplit_TFLOPs"] = 4.0 * 256 * 420 * 1024 * 128 / (ms * 1e-3) / 1e12
+        del q, kk, vv
+    except Exception as e:  # a build without a fused attention kernel for this shape
+        out["sdpa_long_context_shape_TFLOPs"] = None
+        out["sdpa_error"] = str(e)[:200]
+    torch.cuda.empty_cache()
     out["note"] = "library kernels through torch on this box in this run; fractions of the published peaks: " \
                   f"copy {out['hbm_copy_GBps'] / PEAK_HBM_GBS:.2f}, read {out['hbm_read_GBps'] / PEAK_HBM_GBS:.2f}, " \
                   f"GEMM {out['bf16_gemm_8192_TFLOPs'] / PEAK_BF16_TFLOPS:.2f}"
