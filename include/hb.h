@@ -4,11 +4,14 @@
  * The step (paper, Section 1): a draft model proposes several tokens, here arranged as a token
  * tree, and the target model validates all of them in one batched pass.  Because the target
  * decides, its outputs are unchanged (Section 4.1 "Setup"): under greedy decoding the emitted
- * stream equals plain autoregressive decoding.  This library is the target-side pass after the
- * projections: attention of every tree node over the paged prefix KV cache plus its own
- * ancestors, LM head with a fused argmax, greedy longest-accepted-path selection, and the
- * append of the accepted nodes' K/V to the cache (the paper keeps committed context in the KV
- * cache, Section 4.1).
+ * stream equals plain autoregressive decoding.  The core of this library is that target-side
+ * pass: attention of every tree node over the paged prefix KV cache plus its own ancestors, LM
+ * head with a fused argmax, greedy longest-accepted-path selection (or sampling acceptance), and
+ * the append of the accepted nodes' K/V to the cache (the paper keeps committed context in the
+ * KV cache, Section 4.1).  Around it: the target's projections on both sides of the attention
+ * (positions, rotary table, fused QKV projection, output projection), the construction of the
+ * draft tree from the draft model's logits, and the draft model's intermediate layer
+ * (aggregation of the target's layer features with meta queries, Section 3.1.1).
  *
  * Conventions for every entry point
  *   - Returns an hb_status; on failure hb_last_error() gives a thread-local message.
