@@ -120,3 +120,58 @@ def test_tree_shapes_and_edges(S, B, K, T, N):
 def test_tree_with_equal_scores(S):
     _grow_both(S, 2, 3, 3, 9, 0, seed=0, uniform=True)
     _grow_both(S, 4, 6, 4, 48, 3000, seed=9, ties=True)
+
+
+def test_tree_build_replays_from_a_hip_graph(S):
+    """Top-k, growth of every level and finalisation only enqueue kernels (no allocation, no
+    memset): captured once, replayed on changing logits with eager builds in between, every replay
+    equals the eager build bit for bit."""
+    import paper_2509_18824_amd as hb
+    B, K, T, N, V = 4, 5, 3, 24, 6000
+    levels = [torch.empty((B * (1 if l == 0 else K), V), dtype=torch.float32, device="cuda") for l in range(T)]
+    ids = [torch.empty((x.shape[0], K), dtype=torch.int32, device="cuda") for x in levels]
+    lps = [torch.empty((x.shape[0], K), dtype=torch.float32, device="cuda") for x in levels]
+    ws = S.alloc_workspace(hb.hb_topk_logprob_workspace_bytes(B * K, V, K))
+    builder = S.DraftTreeBuilder(B, K, T)
+    root = torch.arange(B, dtype=torch.int32, device="cuda")
+    n = B * N
+    i32 = lambda m: torch.empty(m, dtype=torch.int32, device="cuda")
+    outs = [i32(B + 1), i32(n), i32(n), i32(n), torch.empty(n, dtype=torch.int64, device="cuda"), i32(n),
+            torch.empty(n, dtype=torch.float32, device="cuda")]
+
+    def build():
+        for l in range(T):
+            hb.hb_topk_logprob(levels[l], K, ids[l], lps[l], ws)
+            hb.hb_tree_grow(B, K, T, l, ids[l], lps[l], builder.cand_score, builder.cand_token, builder.cand_parent,
+                            builder.frontier, builder.frontier_slot)
+        hb.hb_tree_finalize(B, K, T, N, builder.cand_score, builder.cand_token, builder.cand_parent, root, *outs)
+
+    def fill(seed):
+        for l, x in enumerate(levels):
+            x.copy_(torch.from_numpy(W.make_draft_logits(seed * 10 + l, x.shape[0], V)))
+
+    fill(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        build()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        build()
+    seen = set()
+    for seed in (1, 2, 3):
+        fill(seed)
+        build()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in outs]
+        for t in outs:
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, outs):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+        hb.hb_tree_validate_host(outs[1][:N].cpu().tolist())
+        seen.add(tuple(outs[2].cpu().tolist()))
+    assert len(seen) == 3  # the logits, and with them the trees, did change between replays

@@ -239,3 +239,70 @@ def test_full_step_replays_from_a_hip_graph(S):
         replayed = snapshot()
         for a, b in zip(eager, replayed):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+@pytest.mark.parametrize("tree", ["tree", "chain8"])
+def test_layer_stack_replays_from_a_hip_graph(S, tree):
+    """Three decoder layers (QKV projection + rotary embedding, attention over each layer's own
+    pools, output projection; with 8-node chains the projections take the split-K path), LM head,
+    acceptance and the compaction of all layers in one launch, captured once and replayed with
+    eager steps in between on changing draft ids: every replay equals the eager step, bit for bit,
+    pools of every layer included."""
+    inp = W.make_config(4, scale_down=8, tree=tree)
+    V, n_layers = 4096, 3
+    T, Hq, Hkv, D = inp.total_nodes, inp.Hq, inp.Hkv, inp.D
+    K = Hq * D
+    dev = S.to_device(inp)
+    desc = S.desc_for(inp)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    mk = lambda *shape, std: (torch.randn(shape, generator=g, device="cuda") * std).to(torch.bfloat16)
+    w_qkv = [mk((Hq + 2 * Hkv) * D, K, std=K ** -0.5) for _ in range(n_layers)]
+    w_o = [mk(K, K, std=0.3 * K ** -0.5) for _ in range(n_layers)]
+    lm = mk(V, K, std=0.02)
+    hidden0 = mk(T, K, std=1.0)
+    pools = [(dev.k_pool, dev.v_pool)] + [(dev.k_pool.clone(), dev.v_pool.clone()) for _ in range(n_layers - 1)]
+    pristine = [(k.clone(), v.clone()) for k, v in pools]
+    draft = torch.zeros(T, dtype=torch.int32, device="cuda")
+    stack = S.VerifyLayerStack(desc, dev, pools, w_qkv, w_o, lm, draft, inp.max_path, hidden0)
+    assert (stack.ws_proj is not None) == (T <= 128)
+    stack.run(compact=False)
+    torch.cuda.synchronize()
+    target = stack.target_ids.cpu().numpy()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        stack.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        stack.run()
+
+    def restore():
+        for (k, v), (k0, v0) in zip(pools, pristine):
+            k.copy_(k0); v.copy_(v0)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        outs = [stack.final_hidden, stack.target_ids, stack.accept_len, stack.accept_path, stack.out_tokens,
+                stack.bonus, stack.out_slots, stack.new_len]
+        return [t.clone() for t in outs] + [t.clone() for kv in pools for t in kv]
+
+    for seed in (4, 5, 6):
+        ids, planted = W.plant_draft_ids(seed, inp.trees(), target, V)
+        stack.draft_ids.copy_(torch.from_numpy(ids))
+        restore()
+        stack.run()
+        eager = snapshot()
+        assert list(stack.accept_len.cpu().numpy()) == [d + 1 for d in planted]
+        # the compaction wrote the accepted nodes into every layer's pools
+        assert all(not torch.equal(k.view(torch.int16), k0.view(torch.int16)) for (k, _), (k0, _) in zip(pools, pristine))
+        restore()
+        for t in (stack.target_ids, stack.accept_len, stack.accept_path, stack.out_tokens, stack.bonus,
+                  stack.out_slots, stack.new_len):
+            t.fill_(0)
+        graph.replay()
+        replayed = snapshot()
+        for a, b in zip(eager, replayed):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
