@@ -422,7 +422,7 @@ def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
     """The draft model's intermediate layer (meta-query cross-attention over the target's layer
     features, output projection with skip connection, fc1) on the tokens one step commits at most
     (16 sequences x 6), random weights.  Per call: value projection GEMM [n_tok * L, D] x [D, D],
-    the fused scores / softmax / mixing kernel, output projection, fc1."""
+    the score and softmax / mixing kernels, output projection, fc1."""
     import torch
     import workloads as W
     import paper_2509_18824_amd as hb
@@ -435,6 +435,7 @@ def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
     v_proj, pre, res, f_c, out = bf(n_tok * L, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok, D)
     names = ("value_projection", "meta_query_attn", "output_projection", "fc1")
     ws_fc1 = S.alloc_workspace(hb.hb_proj_workspace_bytes(n_tok, Q * D, D))  # split-K partials (few tokens only)
+    ws_attn = S.alloc_workspace(hb.hb_meta_query_attn_workspace_bytes(n_tok, D, H, Q))  # partial scores
 
     def call(ev=None):
         marks = []
@@ -447,7 +448,7 @@ def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
         hb.hb_out_project(feats.view(n_tok * L, D), layer.w_v, None, v_proj)
         mark()
         hb.hb_meta_query_attn(H, Q, feats, v_proj.view(n_tok, L, D), layer.a_fold, layer.residual_layers,
-                              pre.view(n_tok, Q, D), res.view(n_tok, Q, D))
+                              pre.view(n_tok, Q, D), res.view(n_tok, Q, D), ws_attn)
         mark()
         hb.hb_out_project(pre, layer.w_o, res, f_c)
         mark()

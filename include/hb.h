@@ -406,6 +406,10 @@ int32_t hb_tree_finalize(int32_t B, int32_t K, int32_t T, int32_t n_nodes, const
  *   feats, v_proj [S, L, D] device;  a_fold from hb_meta_query_fold
  *   residual_layers_or_null   HOST int32 [Q]: the layer whose feature is each query's residual
  *   pre [S, Q, D] device;  residual_out_or_null [S, Q, D] device (written iff residual layers given)
+ *   workspace   device, hb_meta_query_attn_workspace_bytes(S, D, H, Q) bytes (0 for an unsupported
+ *               shape), 4-byte aligned, overwritten: partial scores of the tokens, about 12 KB per
+ *               token and per share of D that a workgroup column takes (14 shares of D = 3584
+ *               for up to about 300 tokens, one from 4096 tokens on)
  * Errors: INVALID_ARG (sizes < 1, H not dividing D, residual layer outside [0, L), NULL or
  * misaligned pointers), UNSUPPORTED (D % 256 != 0, (D / H) % 8 != 0, H * Q > 96, Q > 4, L > 32),
  * WORKSPACE, DEVICE.  S == 0 is a no-op.
@@ -415,9 +419,12 @@ size_t hb_meta_query_fold_bytes(int32_t Q, int32_t D, int32_t H);
 int32_t hb_meta_query_fold(int32_t Q, int32_t D, int32_t H, const void *f_q, const void *w_q, const void *w_k,
                            void *a_fold, void *workspace, size_t workspace_bytes, void *stream);
 
+size_t hb_meta_query_attn_workspace_bytes(int32_t S, int32_t D, int32_t H, int32_t Q);
+
 int32_t hb_meta_query_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q, const void *feats,
                            const void *v_proj, const void *a_fold, const int32_t *residual_layers_or_null,
-                           void *pre, void *residual_out_or_null, void *stream);
+                           void *pre, void *residual_out_or_null, void *workspace, size_t workspace_bytes,
+                           void *stream);
 
 #ifdef __cplusplus
 }

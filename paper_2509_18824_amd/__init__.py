@@ -37,6 +37,7 @@ from .binding import (
     hb_tree_finalize,
     hb_meta_query_fold_bytes,
     hb_meta_query_fold,
+    hb_meta_query_attn_workspace_bytes,
     hb_meta_query_attn,
     HB_F32,
     HB_BF16,

@@ -99,7 +99,9 @@ def _load():
     lib.hb_meta_query_fold.restype = i32
     lib.hb_meta_query_fold.argtypes = [i32, i32, i32, p, p, p, p, p, sz, p]
     lib.hb_meta_query_attn.restype = i32
-    lib.hb_meta_query_attn.argtypes = [i32] * 5 + [p, p, p, C.POINTER(i32), p, p, p]
+    lib.hb_meta_query_attn.argtypes = [i32] * 5 + [p, p, p, C.POINTER(i32), p, p, p, sz, p]
+    lib.hb_meta_query_attn_workspace_bytes.restype = sz
+    lib.hb_meta_query_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.hb_kv_compact.restype = i32
     lib.hb_kv_compact.argtypes = [C.POINTER(AttnDesc)] + [p] * 9 + [i32, p, p, p]
     lib.hb_kv_compact_layers.restype = i32
@@ -318,15 +320,20 @@ def hb_meta_query_fold(H: int, f_q, w_q, w_k, a_fold, workspace, stream=None) ->
                                   _stream(stream)))
 
 
-def hb_meta_query_attn(H: int, Q: int, feats, v_proj, a_fold, residual_layers, pre, residual_out=None,
+def hb_meta_query_attn_workspace_bytes(S: int, D: int, H: int, Q: int) -> int:
+    return int(lib.hb_meta_query_attn_workspace_bytes(S, D, H, Q))
+
+
+def hb_meta_query_attn(H: int, Q: int, feats, v_proj, a_fold, residual_layers, pre, residual_out, workspace,
                        stream=None) -> None:
     S, L, D = feats.shape
     for t in (feats, v_proj, a_fold, pre):
         if t.dtype != torch.bfloat16 or not t.is_contiguous():
             raise ValueError("bf16 contiguous tensors expected")
     layers = (C.c_int32 * Q)(*[int(x) for x in residual_layers]) if residual_layers is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.hb_meta_query_attn(S, L, D, H, Q, _ptr(feats), _ptr(v_proj), _ptr(a_fold), layers, _ptr(pre),
-                                  _ptr(residual_out), _stream(stream)))
+                                  _ptr(residual_out), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def hb_kv_compact(desc: AttnDesc, k_tree, v_tree, k_pool, v_pool, block_table, prefix_len, node_offset,

@@ -514,9 +514,15 @@ int32_t hb_meta_query_fold(int32_t Q, int32_t D, int32_t H, const void *f_q, con
   return HB_OK;
 }
 
+size_t hb_meta_query_attn_workspace_bytes(int32_t S, int32_t D, int32_t H, int32_t Q) {
+  if (S < 1 || check_meta_shape(1, D, H, Q)) return 0;
+  return meta_attn_workspace_bytes(S, D, H, Q);
+}
+
 int32_t hb_meta_query_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q, const void *feats,
                            const void *v_proj, const void *a_fold, const int32_t *residual_layers_or_null,
-                           void *pre, void *residual_out_or_null, void *stream) {
+                           void *pre, void *residual_out_or_null, void *workspace, size_t workspace_bytes,
+                           void *stream) {
   if (S < 0) return fail(HB_ERR_INVALID_ARG, "S must be >= 0");
   int32_t rc = check_meta_shape(L, D, H, Q);
   if (rc) return rc;
@@ -531,8 +537,14 @@ int32_t hb_meta_query_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q
   if (misaligned(feats) || misaligned(v_proj) || misaligned(a_fold) || misaligned(pre) ||
       (residual_out_or_null && misaligned(residual_out_or_null)))
     return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  const size_t need = meta_attn_workspace_bytes(S, D, H, Q);
+  if (!workspace || workspace_bytes < need)
+    return fail(HB_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  if ((uintptr_t)workspace % 4) return fail(HB_ERR_WORKSPACE, "workspace must be 4-byte aligned");
   HB_HIP_TRY(launch_meta_attn(S, L, D, H, Q, feats, v_proj, a_fold, residual_layers_or_null, pre,
-                              residual_layers_or_null ? residual_out_or_null : nullptr, (hipStream_t)stream));
+                              residual_layers_or_null ? residual_out_or_null : nullptr, (float *)workspace,
+                              (hipStream_t)stream));
   return HB_OK;
 }
 

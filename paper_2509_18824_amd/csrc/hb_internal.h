@@ -125,7 +125,8 @@ hipError_t launch_meta_fold(int32_t Q, int32_t D, int32_t H, const void *f_q, co
                             void *a_fold, float *qproj, hipStream_t s);
 hipError_t launch_meta_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q, const void *feats, const void *v_proj,
                             const void *a_fold, const int32_t *residual_layers, void *pre, void *res_out,
-                            hipStream_t s);
+                            float *part, hipStream_t s);
+size_t meta_attn_workspace_bytes(int32_t S, int32_t D, int32_t H, int32_t Q);
 hipError_t launch_kv_compact(const hb_attn_desc &d, const void *k_tree, const void *v_tree,
                              void *k_pool, void *v_pool, const int32_t *block_table,
                              const int32_t *prefix_len, const int32_t *node_offset,

@@ -10,14 +10,18 @@
 // (value rounded to bf16 plus the rounded remainder), so that folding costs the scores no
 // accuracy against projecting keys in fp32.
 //
-// meta_attn_kernel, one workgroup per token: the eight wavefronts split D, each accumulates its
-// share of the [H Q, L] scores with MFMA 16x16x32 (operands straight from memory in fragment
-// layout: the A rows come from L2, the token's features from HBM), the partial scores meet in
-// LDS, one thread per (head, query) row does the softmax over the L layers, and every thread then
-// mixes the token's projected values (v_proj = f_i W_v^T, a plain linear layer run beforehand)
-// for eight feature columns of all Q queries:  pre[q, c] = sum_l P[head(c) Q + q, l] v_proj[l, c].
+// meta_scores_kernel: the scores of all tokens are one dense product A [H Q, D] x feats^T
+// [D, S L].  A workgroup takes eight tokens and a range of 256-feature slices of D; it stages the
+// slice of A (both halves) in LDS once and its four wavefronts, two tokens each, run MFMA
+// 16x16x32 with the A fragments from LDS and the tokens' features straight from memory in
+// fragment layout, so A crosses the vector memory path once per eight tokens.  With few tokens
+// the slices are spread over several workgroups, which write partial scores (fp32) to a workspace.
+// meta_mix_kernel, one workgroup per token (and per 4096 features): sums the partial scores, one thread per (head, query)
+// row does the softmax over the L layers, and every thread then mixes the token's projected values
+// (v_proj = f_i W_v^T, a plain linear layer run beforehand) for eight feature columns of all Q
+// queries:  pre[q, c] = sum_l P[head(c) Q + q, l] v_proj[l, c].
 // The output projection and the skip connection (Section 3.1.2) are a linear layer with residual
-// run afterwards on pre; this kernel also copies the residual rows f_i[residual_layers[q]].
+// run afterwards on pre; the mixing kernel also copies the residual rows f_i[residual_layers[q]].
 #include "hb_internal.h"
 
 namespace hb {
@@ -30,9 +34,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;       // the two set-up kernels
 constexpr int kWaves = 4;
-constexpr int kAttnWaves = 8;       // wavefronts of meta_attn_kernel: each takes an eighth of D
-constexpr int kAttnThreads = 64 * kAttnWaves;
-constexpr int kBRing = 4;           // steps that the token's feature fragments are loaded ahead
+constexpr int kScoreWaves = 4;      // wavefronts of meta_scores_kernel
+constexpr int kScoreThreads = 64 * kScoreWaves;
+constexpr int kTokPerWave = 2;      // tokens whose scores one wavefront accumulates
+constexpr int kTokPerGroup = kScoreWaves * kTokPerWave;
+constexpr int kSlice = 256;         // features of A staged in LDS at a time
+constexpr int kSlicePieces = kSlice / 8;       // 16-byte pieces per row of a slice
+constexpr int kSliceSteps = kSlice / 32;       // MFMA steps per slice
+constexpr int kRowPieces = kSlicePieces + 1;   // LDS row stride in pieces: fragment reads of 16 rows hit distinct banks
+constexpr int kMixThreads = 512;      // meta_mix_kernel: one thread per eight feature columns
+constexpr int kMaxParts = 16;         // workgroup columns of the score kernel
 constexpr int kMaxRowTiles = 6;   // H * Q <= 96
 constexpr int kMaxRows = 16 * kMaxRowTiles;
 constexpr int kMaxL = 32;
@@ -79,96 +90,165 @@ struct ResidualLayers {
   int32_t on;
 };
 
-__global__ __launch_bounds__(kAttnThreads) void meta_attn_kernel(int L, int D, int H, int Q, int row_tiles,
-                                                                 const u32x4 *__restrict__ feats,
-                                                                 const u32x4 *__restrict__ v_proj,
-                                                                 const u32x4 *__restrict__ a_hi,
-                                                                 const u32x4 *__restrict__ a_lo, ResidualLayers res,
-                                                                 u32x4 *__restrict__ pre, u32x4 *__restrict__ res_out) {
-  extern __shared__ float meta_lds[];
-  float (*part)[kMaxRows][kLdsL] = reinterpret_cast<float (*)[kMaxRows][kLdsL]>(meta_lds);  // [kAttnWaves]
-  float (*prob)[kLdsL] = reinterpret_cast<float (*)[kLdsL]>(meta_lds + kAttnWaves * kMaxRows * kLdsL);
-  const int s = blockIdx.x;
+// part[p][s][row][l] (row stride 32): the scores of token s summed over the slices that
+// workgroup column p covers
+__global__ __launch_bounds__(kScoreThreads) void meta_scores_kernel(int S, int L, int D, int row_tiles,
+                                                                    int slices_per_wg,
+                                                                    const u32x4 *__restrict__ feats,
+                                                                    const u32x4 *__restrict__ a_hi,
+                                                                    const u32x4 *__restrict__ a_lo,
+                                                                    float *__restrict__ part) {
+  extern __shared__ u32x4 meta_a_lds[];  // [2][rows_pad][kRowPieces]
+  const int rows_pad = 16 * row_tiles;
+  u32x4 *lds_hi = meta_a_lds, *lds_lo = meta_a_lds + rows_pad * kRowPieces;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j16 = lane & 15, kq = lane >> 4;
+  const int dp = D / 8;                       // 16-byte pieces per feature row
+  const int tok0 = blockIdx.x * kTokPerGroup + wave * kTokPerWave;
+  const int slices = D / kSlice;
+  const int sl_begin = blockIdx.y * slices_per_wg;
+  const int sl_end = sl_begin + slices_per_wg < slices ? sl_begin + slices_per_wg : slices;
+
+  // B operand: lane (j16, kq) feeds layer 16 ct + j16, features 8 kq .. 8 kq + 7 of the step.
+  // Tokens past the end and layers past L read a valid row and are zeroed or dropped later.
+  const u32x4 *bp[kTokPerWave][2];
+  bool live[2];
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) live[ct] = 16 * ct + j16 < L;
+#pragma unroll
+  for (int t = 0; t < kTokPerWave; ++t) {
+    const int tk = tok0 + t < S ? tok0 + t : S - 1;
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) bp[t][ct] = feats + ((size_t)tk * L + (live[ct] ? 16 * ct + j16 : 0)) * dp + kq;
+  }
+  f32x4 acc[kMaxRowTiles][kTokPerWave][2];
+#pragma unroll
+  for (int mt = 0; mt < kMaxRowTiles; ++mt)
+#pragma unroll
+    for (int t = 0; t < kTokPerWave; ++t)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) acc[mt][t][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+
+  for (int sl = sl_begin; sl < sl_end; ++sl) {
+    const int piece0 = sl * kSlicePieces;
+    // the tokens' fragments of the whole slice are requested before A is staged
+    u32x4 fb[kSliceSteps][kTokPerWave][2];
+#pragma unroll
+    for (int st = 0; st < kSliceSteps; ++st)
+#pragma unroll
+      for (int t = 0; t < kTokPerWave; ++t)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) fb[st][t][ct] = bp[t][ct][piece0 + 4 * st];
+    __syncthreads();  // the previous slice's fragment reads are done
+    // all of the slice's loads are issued before the first LDS write
+    constexpr int kStage = kMaxRows * kSlicePieces / kScoreThreads;
+    u32x4 sh[kStage], sl_[kStage];
+#pragma unroll
+    for (int i = 0; i < kStage; ++i) {
+      const int idx = tid + i * kScoreThreads;
+      if (idx < rows_pad * kSlicePieces) {
+        const int row = idx / kSlicePieces, pc = idx % kSlicePieces;
+        sh[i] = a_hi[(size_t)row * dp + piece0 + pc];
+        sl_[i] = a_lo[(size_t)row * dp + piece0 + pc];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kStage; ++i) {
+      const int idx = tid + i * kScoreThreads;
+      if (idx < rows_pad * kSlicePieces) {
+        const int row = idx / kSlicePieces, pc = idx % kSlicePieces;
+        lds_hi[row * kRowPieces + pc] = sh[i];
+        lds_lo[row * kRowPieces + pc] = sl_[i];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int st = 0; st < kSliceSteps; ++st) {
+      bf16x8 x[kTokPerWave][2];
+#pragma unroll
+      for (int t = 0; t < kTokPerWave; ++t)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) x[t][ct] = __builtin_bit_cast(bf16x8, live[ct] ? fb[st][t][ct] : zero);
+#pragma unroll
+      for (int mt = 0; mt < kMaxRowTiles; ++mt) {
+        if (mt < row_tiles) {
+          const int at = (16 * mt + j16) * kRowPieces + 4 * st + kq;
+          const bf16x8 h8 = __builtin_bit_cast(bf16x8, lds_hi[at]);
+          const bf16x8 l8 = __builtin_bit_cast(bf16x8, lds_lo[at]);
+#pragma unroll
+          for (int t = 0; t < kTokPerWave; ++t)
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
+              acc[mt][t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(h8, x[t][ct], acc[mt][t][ct], 0, 0, 0);
+              acc[mt][t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(l8, x[t][ct], acc[mt][t][ct], 0, 0, 0);
+            }
+        }
+      }
+    }
+  }
+  // lane (j16, kq) holds rows 16 mt + 4 kq + r of layer 16 ct + j16
+#pragma unroll
+  for (int t = 0; t < kTokPerWave; ++t) {
+    if (tok0 + t < S) {
+      float *dst = part + ((size_t)blockIdx.y * S + tok0 + t) * rows_pad * kMaxL;
+#pragma unroll
+      for (int mt = 0; mt < kMaxRowTiles; ++mt) {
+        if (mt < row_tiles) {
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dst[(16 * mt + 4 * kq + r) * kMaxL + 16 * ct + j16] = acc[mt][t][ct][r];
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kMixThreads) void meta_mix_kernel(int S, int L, int D, int H, int Q, int rows_pad,
+                                                               int parts, const float *__restrict__ part,
+                                                               const u32x4 *__restrict__ feats,
+                                                               const u32x4 *__restrict__ v_proj, ResidualLayers res,
+                                                               u32x4 *__restrict__ pre, u32x4 *__restrict__ res_out) {
+  __shared__ float prob[kMaxRows][kLdsL];
+  const int s = blockIdx.x;
+  const int tid = threadIdx.x;
   const int dp = D / 8;                       // 16-byte pieces per feature row
   const u32x4 *f_tok = feats + (size_t)s * L * dp;
   const u32x4 *g_tok = v_proj + (size_t)s * L * dp;
   const int rows = H * Q;
 
-  // ---- scores: this wavefront's eighth of D ------------------------------------------------
-  // The A rows come from L2 (every token re-reads them), one step ahead; the token's own
-  // features come from HBM and are requested kBRing - 1 steps ahead.
-  f32x4 acc[kMaxRowTiles][2];
+  // Everything the token needs from memory is requested up front, in one round: the projected
+  // values of this thread's eight columns for all layers, the residual rows, the partial scores.
+  const int d8 = (D / H) / 8;  // 16-byte pieces per head
+  const int cg = blockIdx.y * kMixThreads + tid;  // this thread's 16-byte column group
+  const bool mixer = cg < dp;
+  u32x4 g[kMaxL], rr[kMaxQ];
 #pragma unroll
-  for (int mt = 0; mt < kMaxRowTiles; ++mt) {
-    acc[mt][0] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    acc[mt][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  }
-  const int steps = D / (32 * kAttnWaves);    // 32 features per MFMA step
-  const int piece0 = wave * steps * 4 + kq;   // 16-byte piece of the lane's fragment at step 0
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-  const int l0 = j16, l1 = 16 + j16;          // the lane's layers (B operand columns)
-  const u32x4 *b0 = f_tok + (size_t)(l0 < L ? l0 : 0) * dp + piece0;
-  const u32x4 *b1 = f_tok + (size_t)(l1 < L ? l1 : 0) * dp + piece0;
-  const u32x4 *ah = a_hi + (size_t)j16 * dp + piece0;
-  const u32x4 *al = a_lo + (size_t)j16 * dp + piece0;
-  u32x4 fb[kBRing][2], fh[2][kMaxRowTiles], fl[2][kMaxRowTiles];
-#define HB_META_LOAD_B(buf_, step_)                                            \
-  {                                                                            \
-    fb[buf_][0] = b0[(step_) * 4];                                             \
-    fb[buf_][1] = b1[(step_) * 4];                                             \
-  }
-#define HB_META_LOAD_A(buf_, step_)                                            \
-  {                                                                            \
-    _Pragma("unroll") for (int mt = 0; mt < kMaxRowTiles; ++mt) {               \
-      if (mt < row_tiles) {                                                    \
-        fh[buf_][mt] = ah[(size_t)mt * 16 * dp + (step_) * 4];                 \
-        fl[buf_][mt] = al[(size_t)mt * 16 * dp + (step_) * 4];                 \
-      }                                                                        \
-    }                                                                          \
-  }
-#define HB_META_MMA(abuf_, bbuf_)                                                                                \
-  {                                                                                                              \
-    const bf16x8 x0 = __builtin_bit_cast(bf16x8, l0 < L ? fb[bbuf_][0] : zero);                                  \
-    const bf16x8 x1 = __builtin_bit_cast(bf16x8, l1 < L ? fb[bbuf_][1] : zero);                                  \
-    _Pragma("unroll") for (int mt = 0; mt < kMaxRowTiles; ++mt) {                                                 \
-      if (mt < row_tiles) {                                                                                      \
-        const bf16x8 h8 = __builtin_bit_cast(bf16x8, fh[abuf_][mt]);                                             \
-        const bf16x8 l8 = __builtin_bit_cast(bf16x8, fl[abuf_][mt]);                                             \
-        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(h8, x0, acc[mt][0], 0, 0, 0);                       \
-        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(h8, x1, acc[mt][1], 0, 0, 0);                       \
-        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(l8, x0, acc[mt][0], 0, 0, 0);                       \
-        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(l8, x1, acc[mt][1], 0, 0, 0);                       \
-      }                                                                                                          \
-    }                                                                                                            \
-  }
+  for (int l = 0; l < kMaxL; ++l)
+    if (mixer && l < L) g[l] = g_tok[(size_t)l * dp + cg];
 #pragma unroll
-  for (int u = 0; u < kBRing - 1; ++u)
-    if (u < steps) HB_META_LOAD_B(u, u);
-  HB_META_LOAD_A(0, 0);
-  for (int st = 0; st < steps; st += kBRing) {
+  for (int q = 0; q < kMaxQ; ++q)
+    if (mixer && res.on && q < Q) rr[q] = f_tok[(size_t)res.layer[q] * dp + cg];
+
+  // ---- the token's scores: sum over the workgroup columns of the score kernel ----------------
+  const int n4 = rows_pad * kMaxL / 4;  // float4 pieces of one partial table
+  const f32x4 *part4 = reinterpret_cast<const f32x4 *>(part);
 #pragma unroll
-    for (int u = 0; u < kBRing; ++u) {
-      const int cur = st + u;
-      if (cur < steps) {
-        if (cur + kBRing - 1 < steps) HB_META_LOAD_B((u + kBRing - 1) % kBRing, cur + kBRing - 1);
-        if (cur + 1 < steps) HB_META_LOAD_A((u + 1) & 1, cur + 1);
-        HB_META_MMA(u & 1, u);
-      }
-    }
-  }
-#undef HB_META_LOAD_A
-#undef HB_META_LOAD_B
-#undef HB_META_MMA
-  // lane (j16, kq) holds rows 16 mt + 4 kq + r of layer 16 ct + j16
+  for (int it = 0; it < (kMaxRows * kMaxL / 4 + kMixThreads - 1) / kMixThreads; ++it) {
+    const int i = tid + it * kMixThreads;
+    if (i < n4) {
+      f32x4 v[kMaxParts];
 #pragma unroll
-  for (int mt = 0; mt < kMaxRowTiles; ++mt) {
-    if (mt < row_tiles) {
+      for (int p = 0; p < kMaxParts; ++p)
+        if (p < parts) v[p] = part4[((size_t)p * S + s) * n4 + i];
+      f32x4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
+      for (int p = 0; p < kMaxParts; ++p)
+        if (p < parts) t += v[p];
+      const int row = i / (kMaxL / 4), c4 = i % (kMaxL / 4);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) part[wave][16 * mt + 4 * kq + r][16 * ct + j16] = acc[mt][ct][r];
+      for (int e = 0; e < 4; ++e) prob[row][4 * c4 + e] = t[e];
     }
   }
   __syncthreads();
@@ -179,10 +259,7 @@ __global__ __launch_bounds__(kAttnThreads) void meta_attn_kernel(int L, int D, i
     float mx = -__builtin_huge_valf();
 #pragma unroll
     for (int l = 0; l < kMaxL; ++l) {
-      float t = 0.f;
-#pragma unroll
-      for (int w = 0; w < kAttnWaves; ++w) t += part[w][tid][l];
-      sc[l] = t;
+      sc[l] = prob[tid][l];
       if (l < L) mx = fmaxf(mx, sc[l]);
     }
     float sum = 0.f;
@@ -198,22 +275,21 @@ __global__ __launch_bounds__(kAttnThreads) void meta_attn_kernel(int L, int D, i
   __syncthreads();
 
   // ---- mix the projected values: eight feature columns per thread, all queries ---------------
-  const int d8 = (D / H) / 8;  // 16-byte pieces per head
-  for (int cg = tid; cg < dp; cg += kAttnThreads) {
-    const int h = cg / d8;
-    float o[kMaxQ][8];
+  if (!mixer) return;
+  const int h = cg / d8;
+  float o[kMaxQ][8];
 #pragma unroll
-    for (int q = 0; q < kMaxQ; ++q)
+  for (int q = 0; q < kMaxQ; ++q)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[q][e] = 0.f;
-#pragma unroll 8
-    for (int l = 0; l < L; ++l) {
-      const u32x4 g = g_tok[(size_t)l * dp + cg];
+    for (int e = 0; e < 8; ++e) o[q][e] = 0.f;
+#pragma unroll
+  for (int l = 0; l < kMaxL; ++l) {
+    if (l < L) {
       float gv[8];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        gv[2 * e] = __uint_as_float(g[e] << 16);
-        gv[2 * e + 1] = __uint_as_float(g[e] & 0xffff0000u);
+        gv[2 * e] = __uint_as_float(g[l][e] << 16);
+        gv[2 * e + 1] = __uint_as_float(g[l][e] & 0xffff0000u);
       }
 #pragma unroll
       for (int q = 0; q < kMaxQ; ++q) {
@@ -224,16 +300,16 @@ __global__ __launch_bounds__(kAttnThreads) void meta_attn_kernel(int L, int D, i
         }
       }
     }
+  }
 #pragma unroll
-    for (int q = 0; q < kMaxQ; ++q) {
-      if (q < Q) {
-        u32x4 w;
+  for (int q = 0; q < kMaxQ; ++q) {
+    if (q < Q) {
+      u32x4 w;
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          w[e] = (uint32_t)f32_to_bf16(o[q][2 * e]) | ((uint32_t)f32_to_bf16(o[q][2 * e + 1]) << 16);
-        pre[((size_t)s * Q + q) * dp + cg] = w;
-        if (res.on) res_out[((size_t)s * Q + q) * dp + cg] = f_tok[(size_t)res.layer[q] * dp + cg];
-      }
+      for (int e = 0; e < 4; ++e)
+        w[e] = (uint32_t)f32_to_bf16(o[q][2 * e]) | ((uint32_t)f32_to_bf16(o[q][2 * e + 1]) << 16);
+      pre[((size_t)s * Q + q) * dp + cg] = w;
+      if (res.on) res_out[((size_t)s * Q + q) * dp + cg] = rr[q];
     }
   }
 }
@@ -256,9 +332,27 @@ hipError_t launch_meta_fold(int32_t Q, int32_t D, int32_t H, const void *f_q, co
   return hipGetLastError();
 }
 
+// Workgroup columns of the score kernel: enough of them that a few tokens still fill the chip
+static void score_split(int32_t S, int32_t D, int *slices_per_wg, int *parts) {
+  const int slices = D / kSlice;
+  const int groups = (S + kTokPerGroup - 1) / kTokPerGroup;
+  int p = (512 + groups - 1) / groups;
+  if (p > slices) p = slices;
+  if (p > kMaxParts) p = kMaxParts;
+  if (p < 1) p = 1;
+  *slices_per_wg = (slices + p - 1) / p;
+  *parts = (slices + *slices_per_wg - 1) / *slices_per_wg;
+}
+
+size_t meta_attn_workspace_bytes(int32_t S, int32_t D, int32_t H, int32_t Q) {
+  int spw, parts;
+  score_split(S, D, &spw, &parts);
+  return (size_t)parts * S * meta_rows_pad(H, Q) * kMaxL * sizeof(float);
+}
+
 hipError_t launch_meta_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t Q, const void *feats, const void *v_proj,
                             const void *a_fold, const int32_t *residual_layers, void *pre, void *res_out,
-                            hipStream_t s) {
+                            float *part, hipStream_t s) {
   const int rows_pad = meta_rows_pad(H, Q);
   ResidualLayers res = {};
   if (residual_layers && res_out) {
@@ -266,11 +360,18 @@ hipError_t launch_meta_attn(int32_t S, int32_t L, int32_t D, int32_t H, int32_t 
     for (int q = 0; q < Q; ++q) res.layer[q] = residual_layers[q];
   }
   const bf16_t *a_hi = (const bf16_t *)a_fold, *a_lo = a_hi + (size_t)rows_pad * D;
-  constexpr size_t kLds = (size_t)(kAttnWaves + 1) * kMaxRows * kLdsL * sizeof(float);
-  hipError_t e = hipFuncSetAttribute((const void *)meta_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+  int spw, parts;
+  score_split(S, D, &spw, &parts);
+  const size_t lds = (size_t)2 * rows_pad * kRowPieces * sizeof(u32x4);
+  hipError_t e = hipFuncSetAttribute((const void *)meta_scores_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)((size_t)2 * kMaxRows * kRowPieces * sizeof(u32x4)));
   if (e != hipSuccess) return e;
-  meta_attn_kernel<<<S, kAttnThreads, kLds, s>>>(L, D, H, Q, rows_pad / 16, (const u32x4 *)feats, (const u32x4 *)v_proj,
-                                          (const u32x4 *)a_hi, (const u32x4 *)a_lo, res, (u32x4 *)pre, (u32x4 *)res_out);
+  meta_scores_kernel<<<dim3((S + kTokPerGroup - 1) / kTokPerGroup, parts), kScoreThreads, lds, s>>>(
+      S, L, D, rows_pad / 16, spw, (const u32x4 *)feats, (const u32x4 *)a_hi, (const u32x4 *)a_lo, part);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  meta_mix_kernel<<<dim3(S, (D / 8 + kMixThreads - 1) / kMixThreads), kMixThreads, 0, s>>>(S, L, D, H, Q, rows_pad, parts, part, (const u32x4 *)feats,
+                                            (const u32x4 *)v_proj, res, (u32x4 *)pre, (u32x4 *)res_out);
   return hipGetLastError();
 }
 

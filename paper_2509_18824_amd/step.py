@@ -180,8 +180,9 @@ class MetaQueryLayer:
         v_proj, pre, f_c = bf(S * L, D), bf(S * Q, D), bf(S * Q, D)
         res = bf(S * Q, D) if self.residual_layers is not None else None
         hb.hb_out_project(feats.view(S * L, D), self.w_v, None, v_proj)
+        ws = torch.empty(hb.hb_meta_query_attn_workspace_bytes(S, D, self.H, Q) // 4, dtype=torch.float32, device=dev)
         hb.hb_meta_query_attn(self.H, Q, feats, v_proj.view(S, L, D), self.a_fold, self.residual_layers,
-                              pre.view(S, Q, D), None if res is None else res.view(S, Q, D))
+                              pre.view(S, Q, D), None if res is None else res.view(S, Q, D), ws)
         linear(pre, self.w_o, res, f_c)
         f_c = f_c.view(S, Q * D)
         out = bf(S, self.w_fc1.shape[0])

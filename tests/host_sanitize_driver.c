@@ -145,10 +145,15 @@ int main(void) {
   CHECK(hb_meta_query_fold(3, 3584, 28, p, p, p, p, p, 16, NULL) == HB_ERR_WORKSPACE);
   {
     int32_t layers_bad[3] = {0, 14, 28}, layers_ok[3] = {0, 14, 27};
-    CHECK(hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers_bad, p, p, NULL) == HB_ERR_INVALID_ARG);
-    CHECK(hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers_ok, p, NULL, NULL) == HB_ERR_INVALID_ARG);
-    CHECK(hb_meta_query_attn(4, 33, 3584, 28, 3, p, p, p, NULL, p, NULL, NULL) == HB_ERR_UNSUPPORTED);
-    CHECK(hb_meta_query_attn(0, 28, 3584, 28, 3, NULL, NULL, NULL, layers_ok, NULL, p, NULL) == HB_OK);
+    CHECK(hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers_bad, p, p, p, (size_t)1 << 30, NULL) == HB_ERR_INVALID_ARG);
+    CHECK(hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers_ok, p, NULL, p, (size_t)1 << 30, NULL) == HB_ERR_INVALID_ARG);
+    CHECK(hb_meta_query_attn(4, 33, 3584, 28, 3, p, p, p, NULL, p, NULL, p, (size_t)1 << 30, NULL) == HB_ERR_UNSUPPORTED);
+    CHECK(hb_meta_query_attn(0, 28, 3584, 28, 3, NULL, NULL, NULL, layers_ok, NULL, p, NULL, 0, NULL) == HB_OK);
+    CHECK(hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, NULL, p, NULL, p, 16, NULL) == HB_ERR_WORKSPACE);
+    for (int32_t S = 1; S <= 20000; S = S * 3 + 1) {
+      size_t nb = hb_meta_query_attn_workspace_bytes(S, 3584, 28, 3);
+      CHECK(nb >= (size_t)S * 96 * 32 * 4 && nb <= (size_t)14 * S * 96 * 32 * 4);
+    }
   }
   printf("host shim checks passed\n");
   return 0;

@@ -155,11 +155,17 @@ def test_meta_query_argument_errors():
     assert L.hb_meta_query_fold(3, 3584, 28, None, p, p, p, p, 1 << 20, None) == 1
     assert L.hb_meta_query_fold(3, 3584, 28, C.c_void_p(0x1002), p, p, p, p, 1 << 20, None) == 1
     layers = (C.c_int32 * 3)(0, 14, 28)
-    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers, p, p, None) == 1  # layer 28 of 28
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, layers, p, p, p, 1 << 30, None) == 1  # layer 28 of 28
     ok_layers = (C.c_int32 * 3)(0, 14, 27)
-    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, ok_layers, p, None, None) == 1  # no residual_out
-    assert L.hb_meta_query_attn(4, 33, 3584, 28, 3, p, p, p, None, p, None, None) == 2       # L > 32
-    assert L.hb_meta_query_attn(4, 28, 3584, 56, 3, p, p, p, None, p, None, None) == 2       # 168 rows
-    assert L.hb_meta_query_attn(-1, 28, 3584, 28, 3, p, p, p, None, p, None, None) == 1
-    assert L.hb_meta_query_attn(0, 28, 3584, 28, 3, None, None, None, None, None, None, None) == 0
-    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, None, p, p, None, p, None, None) == 1
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, ok_layers, p, None, p, 1 << 30, None) == 1  # no residual_out
+    assert L.hb_meta_query_attn(4, 33, 3584, 28, 3, p, p, p, None, p, None, p, 1 << 30, None) == 2       # L > 32
+    assert L.hb_meta_query_attn(4, 28, 3584, 56, 3, p, p, p, None, p, None, p, 1 << 30, None) == 2       # 168 rows
+    assert L.hb_meta_query_attn(-1, 28, 3584, 28, 3, p, p, p, None, p, None, p, 1 << 30, None) == 1
+    assert L.hb_meta_query_attn(0, 28, 3584, 28, 3, None, None, None, None, None, None, None, 0, None) == 0
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, None, p, p, None, p, None, p, 1 << 30, None) == 1
+    need = hb.hb_meta_query_attn_workspace_bytes(4, 3584, 28, 3)
+    assert need == 14 * 4 * 96 * 32 * 4                      # 14 slices of 256 features, one workgroup column each
+    assert hb.hb_meta_query_attn_workspace_bytes(8192, 3584, 28, 3) == 8192 * 96 * 32 * 4
+    assert hb.hb_meta_query_attn_workspace_bytes(4, 3584, 56, 3) == 0
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, None, p, None, p, need - 1, None) == 3
+    assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, None, p, None, None, need, None) == 3

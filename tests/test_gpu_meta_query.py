@@ -50,6 +50,9 @@ def _run(S, seed, n_tok, L, D, H, Q, layers, peaked=False, zero_wo=False):
     (7, 32, 768, 3, 4, None),            # 32 layers, four queries, no skip connection
     (2, 17, 1024, 32, 3, [0, 8, 16]),    # 96 (head, query) rows: every row tile
     (1, 1, 256, 2, 1, [0]),              # one layer, one head, one query
+    (9, 5, 4352, 34, 2, [0, 4]),         # 17 slices of D over 9 workgroup columns (two slices each, the last one), a ragged
+                                         # second token group, more than 4096 features (two column blocks in the mixing)
+    (150, 4, 256, 2, 2, None),           # many tokens, a single slice
 ])
 def test_small_shapes(S, n_tok, L, D, H, Q, layers):
     _run(S, 3 + n_tok, n_tok, L, D, H, Q, layers)
