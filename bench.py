@@ -435,6 +435,7 @@ def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
     v_proj, pre, res, f_c, out = bf(n_tok * L, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok * Q, D), bf(n_tok, D)
     names = ("value_projection", "meta_query_attn", "output_projection", "fc1")
     ws_fc1 = S.alloc_workspace(hb.hb_proj_workspace_bytes(n_tok, Q * D, D))  # split-K partials (few tokens only)
+    ws_out = S.alloc_workspace(hb.hb_proj_workspace_bytes(n_tok * Q, D, D))
     ws_attn = S.alloc_workspace(hb.hb_meta_query_attn_workspace_bytes(n_tok, D, H, Q))  # partial scores
 
     def call(ev=None):
@@ -450,7 +451,7 @@ def bench_meta_query(steps, warmup, n_tok=96, L=28, D=3584, H=28, Q=3):
         hb.hb_meta_query_attn(H, Q, feats, v_proj.view(n_tok, L, D), layer.a_fold, layer.residual_layers,
                               pre.view(n_tok, Q, D), res.view(n_tok, Q, D), ws_attn)
         mark()
-        hb.hb_out_project(pre, layer.w_o, res, f_c)
+        hb.hb_out_project_ws(pre, layer.w_o, res, f_c, ws_out)
         mark()
         hb.hb_out_project_ws(f_c.view(n_tok, Q * D), layer.w_fc1, None, out, ws_fc1)
         mark()

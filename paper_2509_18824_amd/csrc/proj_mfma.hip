@@ -159,23 +159,24 @@ hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, c
   return hipGetLastError();
 }
 
-// ---- at most 128 tokens: split K ------------------------------------------------------------
-// With so few tokens a projection is a stream of its weight matrix from HBM, and one workgroup
-// per 256-row weight tile would give work to a dozen CUs only.  Here the K range of every tile is
-// cut into `ks` parts, one workgroup each (ids round-robin over the XCDs put the workgroups of
-// one K part, which read the same slice of the hidden rows, on one XCD); a workgroup runs the
-// same tile loop over its part and stores its fp32 accumulators to the caller's workspace as
-// part[kpart][weight row][token] (tokens contiguous: a lane's 32 neighbours hold consecutive
-// tokens of one weight row).  proj_reduce_kernel then sums the parts in order and applies the
-// epilogue (bias, rotary embedding, residual), one thread per token and group of four features
-// (for the rotary variant: four (d, d + 64) pairs).
+// ---- few tokens: split K ---------------------------------------------------------------------
+// With few tokens a projection is a stream of its weight matrix from HBM, and one workgroup per
+// 256-row weight tile and hidden tile would give work to a few dozen CUs only.  Here the K range
+// of every tile is cut into `ks` parts, one workgroup per (weight tile, K part, hidden tile); the
+// workgroups that differ in the hidden tile only, which read the same weights, get neighbouring
+// slots of one XCD.  A workgroup runs the same tile loop over its part and stores its fp32
+// accumulators to the caller's workspace as part[kpart][weight row][token] (tokens contiguous: a
+// lane's 32 neighbours hold consecutive tokens of one weight row).  proj_reduce_kernel then sums
+// the parts in order and applies the epilogue (bias, rotary embedding, residual), one thread per
+// token and group of four features (for the rotary variant: four (d, d + 64) pairs).
 template <int MT>
-__global__ __launch_bounds__(512) void proj_splitk_kernel(int M, int Kfull, int V, int ks, int v_pad,
+__global__ __launch_bounds__(512) void proj_splitk_kernel(int M, int Kfull, int V, int ks, int v_pad, int m_tiles,
+                                                          int m_pad, int units,
                                                           const u32x4 *__restrict__ hidden_full,
                                                           const u32x4 *__restrict__ weight_full,
                                                           float *__restrict__ part) {
   constexpr int WV = 4;
-  constexpr bool WNT = true;  // nobody shares a weight tile: stream it past the hidden rows in L2
+  constexpr bool WNT = false;  // measured: the non-temporal hint costs 10-25 % here, also with a single hidden tile
   constexpr int TM = 64 * MT;
   constexpr int VT = 8 / WV;
   extern __shared__ u32x4 lds[];
@@ -186,8 +187,11 @@ __global__ __launch_bounds__(512) void proj_splitk_kernel(int M, int Kfull, int 
   const int wave = tid >> 6;
   const int wv = wave >> 1;
   const int wm = wave & 1;
-  const int v_tile = blockIdx.x / ks, kpart = blockIdx.x % ks;
-  const int m0 = 0;
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int unit = (slot / m_tiles) * kXcds + xcd;  // (weight tile, K part)
+  if (unit >= units) return;
+  const int v_tile = unit / ks, kpart = unit % ks;
+  const int m0 = (slot % m_tiles) * TM;
   const int v0 = v_tile * TV;
   const int K = Kfull / ks;          // this workgroup's share
   const int kp = Kfull / 8;          // row stride in 16-byte pieces
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(512) void proj_splitk_kernel(int M, int Kfull, int 
 #define HB_GEMM_W_ROW(t_) (v0 + (t_))
 #include "mfma_gemm_tile.inc"
 #undef HB_GEMM_W_ROW
-  float *dst = part + ((size_t)kpart * v_pad + v0) * TM;
+  float *dst = part + ((size_t)kpart * v_pad + v0) * m_pad + m0;
 #pragma unroll
   for (int i = 0; i < VT; ++i)
 #pragma unroll
@@ -204,7 +208,7 @@ __global__ __launch_bounds__(512) void proj_splitk_kernel(int M, int Kfull, int 
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = wv * 32 * VT + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-        dst[(size_t)row * TM + wm * 32 * MT + j * 32 + frag_row] = acc[i][j][r];
+        dst[(size_t)row * m_pad + wm * 32 * MT + j * 32 + frag_row] = acc[i][j][r];
       }
 }
 
@@ -269,45 +273,66 @@ __global__ __launch_bounds__(256) void proj_reduce_kernel(int M, int V, int ks, 
   }
 }
 
-// K parts for the split: a divisor of the K steps that leaves every part at least kMinSteps steps
-// and gives as many workgroups as there are CUs, or as close to that as it gets from below.
-constexpr int kSplitMaxM = 128;
-constexpr int kMinSteps = 8;
-int split_parts(int M, int K, int V) {
-  if (M > kSplitMaxM || K % BK) return 1;
+// The split for at most kSplitMaxM tokens: hidden tile height (64 mt rows) and K parts (a divisor
+// of the K steps, at least kMinSteps steps per part, all workgroups resident at once), by a cost
+// model fitted to measurements on weights too many to stay in the last-level cache (microseconds):
+//   split:  6 + steps / ks * (0.70 | 0.86 for mt = 1 | 2) + partial bytes written and read / 4 TB/s
+//   plain:  3 + steps * 0.75 per round of 256 workgroups
+// ks = 1 means: do not split.
+constexpr int kSplitMaxM = 512;
+constexpr int kMinSteps = 4;
+struct SplitPlan {
+  int ks, mt;
+};
+SplitPlan split_plan(int M, int K, int V) {
+  SplitPlan best = {1, 1};
+  if (M > kSplitMaxM || K % BK) return best;
   const int steps = K / BK, v_tiles = (V + TV - 1) / TV;
-  int best = 1;
-  for (int d = 1; d <= steps; ++d) {
-    if (steps % d || steps / d < kMinSteps) continue;
-    if (v_tiles * d <= 256 && d > best) best = d;
+  const long plain_units = (long)v_tiles * ((M + 63) / 64);
+  double best_cost = 3.0 + steps * 0.75 * (double)((plain_units + 255) / 256);
+  for (int mt = 1; mt <= 2; ++mt) {
+    const int m_tiles = (M + 64 * mt - 1) / (64 * mt);
+    for (int d = 2; d <= steps; ++d) {
+      if (steps % d || steps / d < kMinSteps || (long)v_tiles * m_tiles * d > 256) continue;
+      const double bytes = 8.0 * d * v_tiles * TV * m_tiles * 64 * mt;
+      const double cost = 6.0 + (double)(steps / d) * (mt == 1 ? 0.70 : 0.86) + bytes / 4e6;
+      if (cost < best_cost - 1e-9) {
+        best_cost = cost;
+        best = {d, mt};
+      }
+    }
   }
   return best;
 }
 
 template <bool ROPE>
-hipError_t launch_splitk(int M, int K, int V, int ks, const void *hidden, const void *weight, const QkvArgs &qa,
+hipError_t launch_splitk(int M, int K, int V, SplitPlan plan, const void *hidden, const void *weight, const QkvArgs &qa,
                          const StoreArgs &sa, float *part, hipStream_t s) {
-  const int mt = M <= 64 ? 1 : 2;
-  const int tm = 64 * mt;
+  const int ks = plan.ks, tm = 64 * plan.mt;
+  const int m_tiles = (M + tm - 1) / tm, m_pad = m_tiles * tm;
   const int v_tiles = (V + TV - 1) / TV, v_pad = v_tiles * TV;
+  const int units = v_tiles * ks;
+  const unsigned grid = (unsigned)((units + kXcds - 1) / kXcds * kXcds * m_tiles);
   const size_t lds_bytes = (size_t)(3 * TV + 2 * tm) * CH * sizeof(u32x4);
   hipError_t e;
-  if (mt == 1) {
+  if (plan.mt == 1) {
     auto kern = proj_splitk_kernel<1>;
     e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
-    kern<<<v_tiles * ks, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, (const u32x4 *)hidden, (const u32x4 *)weight, part);
+    kern<<<grid, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, m_tiles, m_pad, units, (const u32x4 *)hidden,
+                                      (const u32x4 *)weight, part);
   } else {
     auto kern = proj_splitk_kernel<2>;
     e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
-    kern<<<v_tiles * ks, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, (const u32x4 *)hidden, (const u32x4 *)weight, part);
+    kern<<<grid, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, m_tiles, m_pad, units, (const u32x4 *)hidden,
+                                      (const u32x4 *)weight, part);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long groups = ROPE ? (long)(V / kHeadDim) * 16 : (V + 3) / 4;
-  const long threads = groups * tm;
-  proj_reduce_kernel<ROPE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(M, V, ks, v_pad, tm, part, qa, sa);
+  const long threads = groups * m_pad;
+  proj_reduce_kernel<ROPE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(M, V, ks, v_pad, m_pad, part, qa, sa);
   return hipGetLastError();
 }
 
@@ -383,10 +408,11 @@ __global__ __launch_bounds__(256) void rope_table_kernel(int T, int half, double
 bool proj_mfma_supports(int32_t M, int32_t K, int32_t N) { return M >= 1 && K >= BK && K % BK == 0 && N >= 4 && N % 4 == 0; }
 
 size_t proj_workspace_bytes(int32_t M, int32_t K, int32_t N) {
-  const int ks = split_parts(M, K, N);
-  if (ks <= 1) return 0;
+  const SplitPlan plan = split_plan(M, K, N);
+  if (plan.ks <= 1) return 0;
   const size_t v_pad = (size_t)((N + TV - 1) / TV) * TV;
-  return (size_t)ks * v_pad * (M <= 64 ? 64 : 128) * sizeof(float);
+  const size_t tm = 64 * plan.mt, m_pad = (M + tm - 1) / tm * tm;
+  return (size_t)plan.ks * v_pad * m_pad * sizeof(float);
 }
 
 hipError_t launch_qkv_rope(int32_t M, int32_t K, int32_t Hq, int32_t Hkv, const void *hidden, const void *w_qkv,
@@ -395,8 +421,8 @@ hipError_t launch_qkv_rope(int32_t M, int32_t K, int32_t Hq, int32_t Hkv, const 
   QkvArgs qa = {(const bf16_t *)bias, cos, sin, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, Hq, Hkv};
   StoreArgs sa = {nullptr, nullptr};
   const int V = (Hq + 2 * Hkv) * kHeadDim;
-  const int ks = part ? split_parts(M, K, V) : 1;
-  if (ks > 1) return launch_splitk<true>(M, K, V, ks, hidden, w_qkv, qa, sa, part, s);
+  const SplitPlan plan = part ? split_plan(M, K, V) : SplitPlan{1, 1};
+  if (plan.ks > 1) return launch_splitk<true>(M, K, V, plan, hidden, w_qkv, qa, sa, part, s);
   return dispatch<true>(M, K, V, hidden, w_qkv, qa, sa, s);
 }
 
@@ -404,8 +430,8 @@ hipError_t launch_linear(int32_t M, int32_t K, int32_t N, const void *x, const v
                          float *part, hipStream_t s) {
   QkvArgs qa = {};
   StoreArgs sa = {(const bf16_t *)residual, (bf16_t *)out};
-  const int ks = part ? split_parts(M, K, N) : 1;
-  if (ks > 1) return launch_splitk<false>(M, K, N, ks, x, w, qa, sa, part, s);
+  const SplitPlan plan = part ? split_plan(M, K, N) : SplitPlan{1, 1};
+  if (plan.ks > 1) return launch_splitk<false>(M, K, N, plan, x, w, qa, sa, part, s);
   return dispatch<false>(M, K, N, x, w, qa, sa, s);
 }
 

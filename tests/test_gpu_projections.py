@@ -59,10 +59,12 @@ def test_qkv_projection_with_rotary_embedding(hb, T, K, Hq, Hkv, bias):
 
 
 @pytest.mark.parametrize("T,K,Hq,Hkv,bias", [(128, 3584, 28, 4, True), (100, 256, 2, 1, True), (1, 512, 1, 1, False),
-                                             (64, 768, 3, 3, True), (65, 1024, 4, 2, False), (300, 320, 3, 3, True)])
+                                             (64, 768, 3, 3, True), (65, 1024, 4, 2, False), (300, 320, 3, 3, True),
+                                             (288, 3584, 28, 4, True), (200, 1024, 3, 1, False), (512, 2048, 2, 2, True),
+                                             (513, 2048, 2, 1, True)])
 def test_qkv_projection_split_over_k(hb, T, K, Hq, Hkv, bias):
-    """The workspace variant: at most 128 tokens take the split-K path (also when K gives a single
-    part), more tokens the ordinary one."""
+    """The workspace variant: at most 512 tokens take the split-K path when K has enough steps
+    (one or several hidden tiles per weight tile and K part), anything else the ordinary one."""
     _qkv_case(hb, T, K, Hq, Hkv, bias, True)
 
 
@@ -81,7 +83,7 @@ def _qkv_case(hb, T, K, Hq, Hkv, bias, with_workspace):
     v = torch.full((T, Hkv, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
     if with_workspace:
         nbytes = hb.hb_proj_workspace_bytes(T, K, (Hq + 2 * Hkv) * 128)
-        assert (nbytes > 0) == (T <= 128 and K >= 1024)
+        assert (nbytes > 0) == (T <= 512 and K >= 512)
         ws = torch.full((max(nbytes, 16),), 0xFF, dtype=torch.uint8, device="cuda")  # NaN patterns: nothing may be read unwritten
         hb.hb_qkv_rope_project_ws(hidden.cuda(), w.cuda(), None if b is None else b.cuda(), cos, sin, q, k, v, ws)
     else:
@@ -102,7 +104,8 @@ def test_output_projection(hb, T, K, N, res):
 
 @pytest.mark.parametrize("T,K,N,res", [(128, 3584, 3584, True), (96, 10752, 3584, False), (37, 256, 20, True),
                                        (5, 512, 1000, False), (1, 1024, 4, True), (64, 2048, 260, True),
-                                       (129, 512, 512, True)])
+                                       (129, 512, 512, True), (288, 3584, 3584, True), (300, 1024, 520, False),
+                                       (512, 2048, 260, True), (450, 768, 2052, True)])
 def test_output_projection_split_over_k(hb, T, K, N, res):
     _out_case(hb, T, K, N, res, True)
 
