@@ -53,6 +53,16 @@ def test_topk_equal_logits_go_to_the_lower_token_id(S, M, V, k):
     assert np.allclose(logp.cpu().numpy()[0, :2], -np.log(2.0), atol=1e-6) and np.isneginf(logp.cpu().numpy()[0, 2:]).all()
 
 
+@pytest.mark.parametrize("M,V,k,bf16,ties", [(3, 16388, 10, False, False),   # last chunk: a single 16-byte vector
+                                              (70, 32768, 12, True, True),     # bf16, more than a thousand chunks
+                                              (600, 4096, 10, False, False),   # one chunk per row, two rounds of rows
+                                              (33, 40008, 32, True, False)])   # bf16, last chunk of one vector, k = 32
+def test_topk_rows_of_whole_vectors(S, M, V, k, bf16, ties):
+    """Rows that consist of whole 16-byte vectors (vector loads all the way, no ragged end), with
+    a last chunk of a single vector, many more chunks than resident workgroups, bf16 and ties."""
+    _topk_case(S, W.make_draft_logits(41 + M, M, V, ties=ties), k, bf16=bf16)
+
+
 def test_topk_full_vocabulary_every_row_of_a_level(S):
     """The shape of one level of the batch-16 workload: 160 rows (16 sequences x 10 frontier
     nodes) over the vocabulary of 152064, float32; and the root level's 16 rows in bf16."""
