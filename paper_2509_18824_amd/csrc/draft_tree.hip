@@ -328,7 +328,9 @@ __global__ __launch_bounds__(kThreads) void tree_grow_kernel(int K, int level, i
   }
 }
 
-__global__ __launch_bounds__(kThreads) void tree_finalize_kernel(
+constexpr int kFinalThreads = 1024;  // one workgroup per sequence: sixteen wavefronts share the C^2 / 2 comparisons
+
+__global__ __launch_bounds__(kFinalThreads) void tree_finalize_kernel(
     int B, int C, int n, const float *__restrict__ cand_score, const int32_t *__restrict__ cand_token,
     const int32_t *__restrict__ cand_parent, const int32_t *__restrict__ root_token, int32_t *__restrict__ node_offset,
     int32_t *__restrict__ parent, int32_t *__restrict__ draft_ids, int32_t *__restrict__ depth,
@@ -336,33 +338,51 @@ __global__ __launch_bounds__(kThreads) void tree_finalize_kernel(
   extern __shared__ unsigned char dyn[];
   float *s = (float *)dyn;                 // C scores
   int16_t *node_of = (int16_t *)(s + C);   // C: node index of a kept candidate, 0 otherwise
-  __shared__ int counts[kThreads];
+  unsigned char *kept = (unsigned char *)(node_of + C);  // C: the candidate is among the n - 1 best
+  __shared__ int wave_kept[kFinalThreads / 64];
   __shared__ int spar[64];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int keep = n - 1;
-  for (int c = tid; c < C; c += kThreads) {
+  for (int c = tid; c < C; c += kFinalThreads) {
     float x = cand_score[(size_t)b * C + c];
     s[c] = (x == x) ? x : -__builtin_huge_valf();
   }
   __syncthreads();
-  // each thread owns a contiguous run of candidates, so that kept candidates are counted in order
-  const int per = (C + kThreads - 1) / kThreads;
-  const int c0 = min(C, tid * per), c1 = min(C, c0 + per);
-  unsigned long long kept_bits = 0ull;  // per <= 64 is checked by the launcher
-  int cnt = 0;
-  for (int c = c0; c < c1; ++c) {
-    const float sc = s[c];
+  // ranks: four neighbouring lanes share a candidate, each counts a quarter of the others
+  const int sub = tid & 3;
+  constexpr int kPerPass = kFinalThreads / 4;
+  const int c_end = (C + kPerPass - 1) / kPerPass * kPerPass;  // the same trip count for every lane
+  for (int c = tid >> 2; c < c_end; c += kPerPass) {
+    const bool live = c < C;
+    const float sc = live ? s[c] : 0.f;
     int rank = 0;
+    if (live) {
 #pragma unroll 8
-    for (int u = 0; u < C; ++u) rank += beats(s[u], u, sc, c) ? 1 : 0;
-    if (rank < keep) { kept_bits |= 1ull << (c - c0); ++cnt; }
+      for (int u = sub; u < C; u += 4) rank += beats(s[u], u, sc, c) ? 1 : 0;
+    }
+    rank += __shfl_xor(rank, 1, 64);
+    rank += __shfl_xor(rank, 2, 64);
+    if (live && sub == 0) kept[c] = rank < keep ? 1 : 0;
   }
-  counts[tid] = cnt;
   __syncthreads();
-  int before = 0;
-  for (int t = 0; t < tid; ++t) before += counts[t];
+  // each thread owns a contiguous run of candidates, so that kept candidates are counted in order
+  const int per = (C + kFinalThreads - 1) / kFinalThreads;
+  const int c0 = min(C, tid * per), c1 = min(C, c0 + per);
+  int cnt = 0;
+  for (int c = c0; c < c1; ++c) cnt += kept[c];
+  // exclusive prefix count over the threads: inside the wavefront by shifts, then the wavefronts before
+  int incl = cnt;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int y = __shfl_up(incl, off, 64);
+    if ((tid & 63) >= off) incl += y;
+  }
+  if ((tid & 63) == 63) wave_kept[tid >> 6] = incl;
+  __syncthreads();
+  int before = incl - cnt;
+  for (int w = 0; w < (tid >> 6); ++w) before += wave_kept[w];
   for (int c = c0; c < c1; ++c) {
-    const bool k = (kept_bits >> (c - c0)) & 1ull;
+    const bool k = kept[c] != 0;
     node_of[c] = k ? (int16_t)(1 + before) : (int16_t)0;
     before += k ? 1 : 0;
   }
@@ -453,8 +473,8 @@ hipError_t launch_tree_finalize(int32_t B, int32_t C, int32_t n, const float *ca
                                 const int32_t *cand_parent, const int32_t *root_token, int32_t *node_offset,
                                 int32_t *parent, int32_t *draft_ids, int32_t *depth, unsigned long long *anc,
                                 int32_t *node_cand, float *node_score, hipStream_t s) {
-  const size_t lds = (size_t)C * (sizeof(float) + sizeof(int16_t)) + 16;
-  tree_finalize_kernel<<<B, kThreads, lds, s>>>(B, C, n, cand_score, cand_token, cand_parent, root_token, node_offset,
+  const size_t lds = (size_t)C * (sizeof(float) + sizeof(int16_t) + 1) + 16;
+  tree_finalize_kernel<<<B, kFinalThreads, lds, s>>>(B, C, n, cand_score, cand_token, cand_parent, root_token, node_offset,
                                                 parent, draft_ids, depth, anc, node_cand, node_score);
   return hipGetLastError();
 }
