@@ -66,6 +66,25 @@ def test_target_model_shape(S):
     _run(S, 41, 24, 28, 3584, 28, 3, [2, 14, 27], peaked=True)
 
 
+def test_prefill_scale_on_sampled_tokens(S):
+    """1024 tokens of the target model's shape (one workgroup column per two slices of D in the
+    score kernel, 128 token groups); every token is independent of the others, so the oracle
+    checks 24 sampled ones."""
+    n_tok, L, D, H, Q, layers = 1024, 28, 3584, 28, 3, [2, 14, 27]
+    x = W.make_meta_inputs(77, n_tok, L, D, H, Q)
+    g = {k: v.cuda() for k, v in x.items()}
+    layer = S.MetaQueryLayer(g["f_q"], g["w_q"], g["w_k"], g["w_v"], g["w_o"], g["w_fc1"], H, residual_layers=layers)
+    f_c, out = layer.run(g["feats"])
+    torch.cuda.synchronize()
+    pick = np.sort(np.random.default_rng(5).choice(n_tok, 24, replace=False))
+    pick[0], pick[-1] = 0, n_tok - 1
+    w = {k: v.float().numpy().astype(np.float64) for k, v in x.items() if k != "feats"}
+    feats = x["feats"][torch.from_numpy(pick)].float().numpy().astype(np.float64)
+    ref_c = meta_query_attn_ref(w["f_q"], feats, w["w_q"], w["w_k"], w["w_v"], w["w_o"], H, residual_layers=layers)
+    _close(f_c[torch.from_numpy(pick).cuda()], ref_c, "f_c")
+    _close(out[torch.from_numpy(pick).cuda()], linear_ref(ref_c, w["w_fc1"]), "fc1")
+
+
 def test_zero_initialised_output_projection_passes_the_feature_levels_through(S):
     """Section 3.1.2: with W_o at zero the layer's output is the three residual features, bit for bit."""
     f_c, ref_c, x = _run(S, 50, 9, 28, 512, 4, 3, [0, 13, 27], zero_wo=True)

@@ -126,13 +126,16 @@ def _out_case(hb, T, K, N, res, with_workspace):
     _close(out, linear_ref(W.widen(x), W.widen(w), None if r is None else W.widen(r)), "out")
 
 
-def test_projected_qkv_feed_the_attention(hb):
+@pytest.mark.parametrize("scale_down,K,tree", [(16, 512, "tree"), (1, 3584, "tree"), (1, 3584, "chain8")])
+def test_projected_qkv_feed_the_attention(hb, scale_down, K, tree):
     """hidden -> QKV + rotary -> tree-verify attention -> output projection, against the oracle
-    chained the same way on the bf16 tensors the GPU hands from step to step."""
+    chained the same way on the bf16 tensors the GPU hands from step to step; also one whole layer
+    of the batch-16 workload at full size (960 tree tokens, and 128 tokens of 8-node chains, which
+    take the split-K projections; hidden size 3584, prefixes of 1024-4096 tokens)."""
     import paper_2509_18824_amd.step as S
     from oracle import tree_attn_ref
-    inp = W.make_config(4, scale_down=16)
-    T, Hq, Hkv, D, K = inp.total_nodes, inp.Hq, inp.Hkv, inp.D, 512
+    inp = W.make_config(4, scale_down=scale_down, tree=tree)
+    T, Hq, Hkv, D = inp.total_nodes, inp.Hq, inp.Hkv, inp.D
     g = torch.Generator().manual_seed(5)
     hidden = torch.randn((T, K), generator=g).to(torch.bfloat16)
     wqkv = (torch.randn(((Hq + 2 * Hkv) * D, K), generator=g) / np.sqrt(K)).to(torch.bfloat16)
@@ -142,11 +145,13 @@ def test_projected_qkv_feed_the_attention(hb):
     hb.hb_tree_positions(inp.B, 64, dev.node_offset, dev.parent, dev.prefix_len, pos)
     cos = torch.empty((T, 64), dtype=torch.float32, device="cuda"); sin = torch.empty_like(cos)
     hb.hb_rope_table(D, 1e6, pos, cos, sin)
-    hb.hb_qkv_rope_project(hidden.cuda(), wqkv.cuda(), None, cos, sin, dev.q, dev.k_tree, dev.v_tree)
+    ws = S.alloc_workspace(max(hb.hb_proj_workspace_bytes(T, K, (Hq + 2 * Hkv) * D), hb.hb_proj_workspace_bytes(T, Hq * D, K)))
+    assert (ws is not None) == (T <= 512)
+    hb.hb_qkv_rope_project_ws(hidden.cuda(), wqkv.cuda(), None, cos, sin, dev.q, dev.k_tree, dev.v_tree, ws)
     desc = S.desc_for(inp)
     out, _ = S.tree_verify_attn(desc, dev, want_lse=False)
     y = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
-    hb.hb_out_project(out.view(T, -1), wo.cuda(), hidden.cuda(), y)
+    hb.hb_out_project_ws(out.view(T, -1), wo.cuda(), hidden.cuda(), y, ws)
     torch.cuda.synchronize()
     ref_pos = tree_positions_ref(inp.node_offset.numpy(), inp.parent.numpy(), inp.prefix_len.numpy())
     rq, rk, rv = qkv_rope_project_ref(W.widen(hidden), W.widen(wqkv), None, ref_pos, Hq, Hkv, D, 1e6)
