@@ -16,6 +16,7 @@ target's own greedy stream):
   kv_compaction.kv_compact_ref     append the accepted nodes' K/V to the paged cache
   stochastic_acceptance.tree_accept_sample_ref   sampling acceptance (speculative sampling over a tree)
   projections.qkv_rope_project_ref / linear_ref / tree_positions_ref   the projections around the attention
+  projections.rmsnorm_ref / swiglu_ref                                 the layer's normalisations and feed-forward gate
   draft_tree.topk_logprob_ref / DraftTreeRef / build_draft_tree_ref   the draft tree's construction
   meta_query.meta_query_attn_ref / fc_concat_ref   the draft's intermediate layer (Section 3.1.1, Eq. 1)
   toy_decoder.ToyDecoderRef        small random-weight decoder: greedy autoregressive stream and
@@ -35,7 +36,7 @@ from .toy_decoder import ToyDecoderRef
 from .stochastic_acceptance import tree_accept_sample_ref
 from .draft_tree import topk_logprob_ref, DraftTreeRef, build_draft_tree_ref
 from .meta_query import meta_query_attn_ref, fc_concat_ref
-from .projections import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref
+from .projections import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref, rmsnorm_ref, swiglu_ref
 
 __all__ = [
     "tree_attn_ref",
@@ -50,6 +51,8 @@ __all__ = [
     "rope_ref",
     "qkv_rope_project_ref",
     "linear_ref",
+    "rmsnorm_ref",
+    "swiglu_ref",
     "topk_logprob_ref",
     "DraftTreeRef",
     "build_draft_tree_ref",

@@ -6,8 +6,9 @@ The paper's verification step is one parallel pass of the target model over the 
 (Section 1); in a decoder layer that pass is, around the attention: the query/key/value
 projection of the nodes' hidden states, the rotary position embedding of queries and keys at
 each node's position (a node at depth t below the pending token sits at position L + t, the
-position it would have in sequential decoding), and the output projection.  The paper gives no
-model dimensions; shapes and the rotate-half rotary convention are those of the toy decoder here
+position it would have in sequential decoding), and the output projection; the rest of the
+layer is the root-mean-square normalisation in front of the attention and of the feed-forward
+block, and the gated-SiLU feed-forward block itself.  The paper gives no model dimensions; shapes and the rotate-half rotary convention are those of the toy decoder here
 (and of the decoder family BAGEL builds on).
 """
 from __future__ import annotations
@@ -58,3 +59,24 @@ def linear_ref(x, w, residual=None):
     """out[t, n] = sum_k x[t, k] w[n, k] (+ residual[t, n])."""
     y = np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
     return y if residual is None else y + np.asarray(residual, dtype=np.float64)
+
+
+def rmsnorm_ref(x, weight, eps):
+    """Root-mean-square normalisation of every row: out[t, :] = x[t, :] / sqrt(mean_k x[t, k]^2 +
+    eps) * weight.  x [T, K], weight [K]."""
+    x = np.asarray(x, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + float(eps)) * np.asarray(weight, dtype=np.float64)[None, :]
+
+
+def swiglu_ref(x, w_gate_up):
+    """The gated-SiLU half of the feed-forward block: w_gate_up [2 F, K] holds the gate
+    projection's F rows, then the up projection's F rows (nn.Linear layout);
+    out[t, f] = silu(x[t] . w_gate[f]) * (x[t] . w_up[f]),  silu(z) = z / (1 + exp(-z)).  The down
+    projection with the residual is linear_ref."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w_gate_up, dtype=np.float64)
+    F = w.shape[0] // 2
+    g = x @ w[:F].T
+    u = x @ w[F:].T
+    return g / (1.0 + np.exp(-g)) * u

@@ -66,3 +66,47 @@ def test_positions():
     assert list(tree_positions_ref([0, 6, 6, 7], par, [10, 99, 0])) == [10, 11, 11, 12, 12, 13, 0]
     t = W.seeded_tree(3)
     assert np.array_equal(tree_positions_ref([0, len(t)], t, [7]), 7 + W.tree_depths(t))
+
+
+def test_rmsnorm_pins():
+    """Unit mean square for eps = 0 and unit weight; scale invariance; a constant row maps to
+    +-weight; a hand-worked row; eps as an added variance; torch's rms_norm in float64; the toy
+    decoder's own normalisation (pinned separately by the losslessness tests)."""
+    from oracle import rmsnorm_ref
+    rng = np.random.default_rng(3)
+    x, w = rng.standard_normal((6, 40)), rng.standard_normal(40)
+    y = rmsnorm_ref(x, np.ones(40), 0.0)
+    assert np.allclose((y * y).mean(-1), 1.0)
+    assert np.allclose(rmsnorm_ref(7.5 * x, w, 0.0), rmsnorm_ref(x, w, 0.0))
+    assert np.allclose(rmsnorm_ref(np.full((1, 40), -3.0), w, 0.0), -w[None, :])
+    # x = (3, 4): mean square 12.5; with eps = 3.5 the divisor is 4
+    assert np.allclose(rmsnorm_ref([[3.0, 4.0]], [2.0, -1.0], 3.5), [[1.5, -1.0]])
+    t = torch.nn.functional.rms_norm(torch.from_numpy(x), (40,), torch.from_numpy(w), eps=1e-6)
+    assert np.allclose(rmsnorm_ref(x, w, 1e-6), t.numpy(), atol=1e-14)
+    from oracle.toy_decoder import _rms_norm
+    assert np.allclose(_rms_norm(x, w), rmsnorm_ref(x, w, 1e-6))
+
+
+def test_swiglu_pins():
+    """silu's closed forms (silu(0) = 0, silu(z) - silu(-z) = z, silu(z) -> z for large z), a
+    hand-worked entry, gate and up are not interchangeable, torch's silu in float64, the toy
+    decoder's feed-forward block."""
+    from oracle import swiglu_ref
+    # one token, K = 1, F = 2: gate pre-activations (0, ln 3), up pre-activations (5, 2)
+    out = swiglu_ref([[1.0]], [[0.0], [np.log(3.0)], [5.0], [2.0]])
+    assert np.allclose(out, [[0.0, np.log(3.0) / (1.0 + 1.0 / 3.0) * 2.0]])
+    z = np.linspace(-6, 6, 25)
+    s_pos = swiglu_ref(np.ones((25, 1)), np.concatenate([z[:, None], np.ones((25, 1))]))[0]      # silu(z) * 1
+    s_neg = swiglu_ref(np.ones((25, 1)), np.concatenate([-z[:, None], np.ones((25, 1))]))[0]
+    assert np.allclose(s_pos - s_neg, z)
+    assert abs(swiglu_ref([[1.0]], [[40.0], [1.0]])[0, 0] - 40.0) < 1e-12
+    rng = np.random.default_rng(4)
+    x, w = rng.standard_normal((5, 16)), rng.standard_normal((2 * 12, 16))
+    got = swiglu_ref(x, w)
+    tx, tw = torch.from_numpy(x), torch.from_numpy(w)
+    ref = torch.nn.functional.silu(tx @ tw[:12].T) * (tx @ tw[12:].T)
+    assert np.allclose(got, ref.numpy(), atol=1e-13)
+    swapped = swiglu_ref(x, np.concatenate([w[12:], w[:12]]))
+    assert not np.allclose(got, swapped)
+    from oracle.toy_decoder import _silu
+    assert np.allclose(_silu(x @ w[:12].T) * (x @ w[12:].T), got)
