@@ -217,6 +217,30 @@ int32_t hb_out_project_ws(int32_t T, int32_t K, int32_t N, const void *x, const 
                           void *stream);
 
 /*
+ * The rest of a decoder layer of the target around the attention block (Section 1: the target
+ * validates the drafted tokens in one parallel pass over whole layers; pre-norm layers with
+ * root-mean-square normalisation and a gated-SiLU feed-forward block, the decoder family that the
+ * paper's base model builds on).  All tensors bf16, device, 16-byte aligned, row-major; fp32
+ * accumulation, one rounding to bf16 at the end.
+ *
+ * hb_rmsnorm:  out[t, :] = x[t, :] / sqrt(mean_k x[t, k]^2 + eps) * weight.
+ *   x, out [T, K] (out may be x);  weight [K];  eps >= 0.
+ * hb_swiglu_project:  out[t, f] = silu(x[t] . w_gate[f]) * (x[t] . w_up[f]),  silu(z) = z / (1 + exp(-z)),
+ *   both projections in one pass over x.
+ *   x [T, K];  w_gate_up [2 F, K]: the gate projection's F rows, then the up projection's F rows
+ *   (y = x W^T layout);  out [T, F].
+ *   workspace_or_null   device, hb_proj_workspace_bytes(T, K, 2 * F) bytes, 16-byte aligned: with
+ *               it, few tokens take the split over K of hb_out_project_ws; NULL, short or
+ *               misaligned: the unsplit kernel.
+ * The block's down projection with its residual is hb_out_project(T, F, K, act, w_down, residual, out).
+ * Errors: INVALID_ARG (T < 0, sizes < 1, eps < 0, NULL or misaligned pointers), UNSUPPORTED
+ * (hb_rmsnorm: K % 8 != 0; hb_swiglu_project: K % 64 != 0, F % 4 != 0), DEVICE.  T == 0 is a no-op.
+ */
+int32_t hb_rmsnorm(int32_t T, int32_t K, const void *x, const void *weight, float eps, void *out, void *stream);
+int32_t hb_swiglu_project(int32_t T, int32_t K, int32_t F, const void *x, const void *w_gate_up, void *out,
+                          void *workspace_or_null, size_t workspace_bytes, void *stream);
+
+/*
  * Greedy longest accepted path per sequence.  Node 0 is always accepted; node i > 0 matches
  * when draft_ids[i] == target_ids[parent[i]] and is accepted when it and all its ancestors
  * match.  The deepest accepted node wins (lowest id among equals).  accept_len is the number

@@ -35,6 +35,8 @@ from .binding import (
     hb_draft_tree_candidates,
     hb_tree_grow,
     hb_tree_finalize,
+    hb_rmsnorm,
+    hb_swiglu_project,
     hb_meta_query_fold_bytes,
     hb_meta_query_fold,
     hb_meta_query_attn_workspace_bytes,

@@ -94,6 +94,10 @@ def _load():
     lib.hb_tree_grow.argtypes = [i32, i32, i32, i32] + [p] * 7 + [p]
     lib.hb_tree_finalize.restype = i32
     lib.hb_tree_finalize.argtypes = [i32, i32, i32, i32] + [p] * 11 + [p]
+    lib.hb_rmsnorm.restype = i32
+    lib.hb_rmsnorm.argtypes = [i32, i32, p, p, C.c_float, p, p]
+    lib.hb_swiglu_project.restype = i32
+    lib.hb_swiglu_project.argtypes = [i32, i32, i32, p, p, p, p, sz, p]
     lib.hb_meta_query_fold_bytes.restype = sz
     lib.hb_meta_query_fold_bytes.argtypes = [i32, i32, i32]
     lib.hb_meta_query_fold.restype = i32
@@ -248,6 +252,24 @@ def hb_out_project_ws(x, w, residual, out, workspace, stream=None) -> None:
         raise ValueError("need bf16 x [T, K], w [N, K], out [T, N]")
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.hb_out_project_ws(T, K, N, _ptr(x), _ptr(w), _ptr(residual), _ptr(out), _ptr(workspace), ws_bytes,
+                                 _stream(stream)))
+
+
+def hb_rmsnorm(x, weight, eps: float, out, stream=None) -> None:
+    T, K = x.shape
+    if x.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16 or weight.shape != (K,) or out.shape != (T, K):
+        raise ValueError("need bf16 x [T, K], weight [K], out [T, K]")
+    _check(lib.hb_rmsnorm(T, K, _ptr(x), _ptr(weight), eps, _ptr(out), _stream(stream)))
+
+
+def hb_swiglu_project(x, w_gate_up, out, workspace=None, stream=None) -> None:
+    T, K = x.shape
+    F = w_gate_up.shape[0] // 2
+    if (w_gate_up.shape != (2 * F, K) or x.dtype != torch.bfloat16 or w_gate_up.dtype != torch.bfloat16
+            or out.shape != (T, F)):
+        raise ValueError("need bf16 x [T, K], w_gate_up [2 F, K], out [T, F]")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.hb_swiglu_project(T, K, F, _ptr(x), _ptr(w_gate_up), _ptr(out), _ptr(workspace), ws_bytes,
                                  _stream(stream)))
 
 

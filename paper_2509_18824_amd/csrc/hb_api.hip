@@ -372,6 +372,32 @@ int32_t hb_out_project_ws(int32_t T, int32_t K, int32_t N, const void *x, const 
   return out_project(T, K, N, x, w, residual_or_null, out, workspace, workspace_bytes, stream);
 }
 
+int32_t hb_swiglu_project(int32_t T, int32_t K, int32_t F, const void *x, const void *w_gate_up, void *out,
+                          void *workspace_or_null, size_t workspace_bytes, void *stream) {
+  if (T < 0 || K <= 0 || F <= 0) return fail(HB_ERR_INVALID_ARG, "need T >= 0 and K, F > 0");
+  if (K % 64 || F % 4) return fail(HB_ERR_UNSUPPORTED, "K %d must be a multiple of 64 and F %d of 4", K, F);
+  if ((int64_t)F > (int64_t)1 << 24) return fail(HB_ERR_UNSUPPORTED, "F %d: too many features", F);
+  if (T == 0) return HB_OK;
+  if (!x || !w_gate_up || !out) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(x) || misaligned(w_gate_up) || misaligned(out))
+    return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  HB_HIP_TRY(launch_swiglu(T, K, F, x, w_gate_up, out, proj_part(T, K, 2 * F, workspace_or_null, workspace_bytes),
+                           (hipStream_t)stream));
+  return HB_OK;
+}
+
+int32_t hb_rmsnorm(int32_t T, int32_t K, const void *x, const void *weight, float eps, void *out, void *stream) {
+  if (T < 0 || K <= 0) return fail(HB_ERR_INVALID_ARG, "need T >= 0 and K > 0");
+  if (!(eps >= 0.f)) return fail(HB_ERR_INVALID_ARG, "eps must be >= 0");
+  if (K % 8) return fail(HB_ERR_UNSUPPORTED, "K %d must be a multiple of 8", K);
+  if (T == 0) return HB_OK;
+  if (!x || !weight || !out) return fail(HB_ERR_INVALID_ARG, "a required device pointer is NULL");
+  if (misaligned(x) || misaligned(weight) || misaligned(out))
+    return fail(HB_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  HB_HIP_TRY(launch_rmsnorm(T, K, x, weight, eps, out, (hipStream_t)stream));
+  return HB_OK;
+}
+
 int32_t hb_tree_accept(int32_t B, int32_t max_nodes_per_tree, const int32_t *node_offset,
                        const int32_t *parent, const int32_t *draft_ids, const int32_t *target_ids,
                        const int32_t *prev_target_or_null, int32_t max_path, int32_t *accept_len,

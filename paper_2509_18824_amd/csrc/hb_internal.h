@@ -95,6 +95,9 @@ hipError_t launch_qkv_rope(int32_t M, int32_t K, int32_t Hq, int32_t Hkv, const 
                            float *part, hipStream_t s);
 hipError_t launch_linear(int32_t M, int32_t K, int32_t N, const void *x, const void *w, const void *residual,
                          void *out, float *part, hipStream_t s);
+hipError_t launch_swiglu(int32_t M, int32_t K, int32_t F, const void *x, const void *w_gate_up, void *out, float *part,
+                         hipStream_t s);
+hipError_t launch_rmsnorm(int32_t T, int32_t K, const void *x, const void *weight, float eps, void *out, hipStream_t s);
 hipError_t launch_tree_positions(int32_t B, int32_t max_nodes, int32_t total_nodes, const int32_t *node_offset,
                                  const int32_t *parent, const int32_t *prefix_len, int32_t *positions, hipStream_t s);
 hipError_t launch_rope_table(int32_t T, int32_t half, double theta, const int32_t *positions, float *cos, float *sin,

@@ -2,6 +2,9 @@
 //   * fused query/key/value projection + bias + rotary embedding, written straight into the
 //     layouts hb_tree_verify_attn reads (q [T, Hq, D], k_tree / v_tree [T, Hkv, D]);
 //   * output projection (a plain  out = x W^T (+ residual)  in bf16 with fp32 accumulation);
+//   * the gated-SiLU half of the feed-forward block, out = silu(x Wg^T) * (x Wu^T), gate and up
+//     projection in one pass (the down projection is the plain one with the residual);
+//   * root-mean-square normalisation of the rows;
 //   * the two small kernels that give every tree node its position (prefix length + depth) and
 //     the cosine / sine table of those positions.
 // The matrix work is the tile loop of the LM head (mfma_gemm_tile.inc: C^T = W H^T, weight rows
@@ -9,7 +12,10 @@
 // token).  For the rotary embedding the 256 weight rows of a tile are not taken in memory order:
 // a tile holds two heads, and the rows are arranged so that the two accumulators a lane holds at
 // the same position of its two 32-row sub-tiles are the pair (d, d + 64) of one head, which is
-// what the rotate-half convention rotates together: the rotation costs no exchange at all.
+// what the rotate-half convention rotates together: the rotation costs no exchange at all.  The
+// gated projection uses the same device: a tile holds 128 features, the gate rows in the first
+// 32-row sub-tile of every wavefront row and the matching up rows in the second, so silu(gate) * up
+// is one lane's own two accumulators.
 #include "hb_internal.h"
 
 namespace hb {
@@ -46,7 +52,7 @@ struct StoreArgs {
 // ROPE: query/key/value projection with rotary embedding (V = (Hq + 2 Hkv) * 128 weight rows),
 // else plain projection.  One workgroup per (weight tile, hidden tile); the workgroups that share
 // a weight tile get neighbouring slots of one XCD (ids 8 apart) and find it in that XCD's L2.
-template <int MT, bool ROPE>
+template <int MT, bool ROPE, bool GLU>
 __global__ __launch_bounds__(512) void proj_mfma_kernel(int M, int K, int V, int m_tiles, int v_tiles,
                                                         const u32x4 *__restrict__ hidden,
                                                         const u32x4 *__restrict__ weight, QkvArgs qa, StoreArgs sa) {
@@ -73,8 +79,11 @@ __global__ __launch_bounds__(512) void proj_mfma_kernel(int M, int K, int V, int
 
   // Tile row t (wavefront row wv = t / 64, sub-tile i = (t % 64) / 32, rr = t % 32) holds, for the
   // rotary variant, feature  (wv / 2) * 128 + (wv % 2) * 32 + 64 i + rr  of the tile's two heads.
+  // ... and for the gated projection (V = 2 F weight rows: F gate rows, then F up rows) feature
+  // v0 / 2 + 32 wv + rr of the gate (i = 0) or of the up projection (i = 1).
 #define HB_GEMM_W_ROW(t_) (ROPE ? v0 + (((t_) >> 7) << 7) + ((((t_) >> 6) & 1) << 5) + ((((t_) >> 5) & 1) << 6) + ((t_) & 31) \
-                                : v0 + (t_))
+                           : GLU ? (((t_) >> 5) & 1) * (V >> 1) + (v0 >> 1) + (((t_) >> 6) << 5) + ((t_) & 31)                  \
+                                 : v0 + (t_))
 #include "mfma_gemm_tile.inc"
 #undef HB_GEMM_W_ROW
 
@@ -123,6 +132,20 @@ __global__ __launch_bounds__(512) void proj_mfma_kernel(int M, int K, int V, int
         *(u32x2 *)(dst + d) = (u32x2){pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
         *(u32x2 *)(dst + d + 64) = (u32x2){pack_bf16(x2[0], x2[1]), pack_bf16(x2[2], x2[3])};
       }
+    } else if (GLU) {
+      const int F = V >> 1;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int f = (v0 >> 1) + wv * 32 + 8 * c + 4 * frag_half;  // f .. f + 3, F % 4 == 0
+        if (f >= F) continue;
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float g = acc[0][j][4 * c + e];
+          y[e] = g / (1.f + __expf(-g)) * acc[1][j][4 * c + e];
+        }
+        *(u32x2 *)(sa.out + (size_t)m * F + f) = (u32x2){pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
+      }
     } else {
 #pragma unroll
       for (int i = 0; i < VT; ++i)
@@ -144,14 +167,14 @@ __global__ __launch_bounds__(512) void proj_mfma_kernel(int M, int K, int V, int
   }
 }
 
-template <int MT, bool ROPE>
+template <int MT, bool ROPE, bool GLU>
 hipError_t launch(int M, int K, int V, const void *hidden, const void *weight, const QkvArgs &qa, const StoreArgs &sa,
                   hipStream_t s) {
   constexpr int TM = 64 * MT;
   const int m_tiles = (M + TM - 1) / TM;
   const int v_tiles = (V + TV - 1) / TV;
   const size_t lds_bytes = (size_t)(3 * TV + 2 * TM) * CH * sizeof(u32x4);
-  auto kern = proj_mfma_kernel<MT, ROPE>;
+  auto kern = proj_mfma_kernel<MT, ROPE, GLU>;
   hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)((v_tiles + kXcds - 1) / kXcds * kXcds * m_tiles));
@@ -212,7 +235,7 @@ __global__ __launch_bounds__(512) void proj_splitk_kernel(int M, int Kfull, int 
       }
 }
 
-template <bool ROPE>
+template <bool ROPE, bool GLU>
 __global__ __launch_bounds__(256) void proj_reduce_kernel(int M, int V, int ks, int v_pad, int tm,
                                                           const float *__restrict__ part, QkvArgs qa, StoreArgs sa) {
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -255,6 +278,22 @@ __global__ __launch_bounds__(256) void proj_reduce_kernel(int M, int V, int ks, 
     }
     *(u32x2 *)(dst + d) = (u32x2){pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
     *(u32x2 *)(dst + d + 64) = (u32x2){pack_bf16(x2[0], x2[1]), pack_bf16(x2[2], x2[3])};
+  } else if (GLU) {
+    const int F = V >> 1, f = g * 4;
+    if (f >= F) return;
+    float xg[4] = {0.f, 0.f, 0.f, 0.f}, xu[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int kpart = 0; kpart < ks; ++kpart) {
+      const float *src = part + ((size_t)kpart * v_pad + f) * tm + m;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        xg[e] += src[(size_t)e * tm];
+        xu[e] += src[(size_t)(F + e) * tm];
+      }
+    }
+    float y[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = xg[e] / (1.f + __expf(-xg[e])) * xu[e];
+    *(u32x2 *)(sa.out + (size_t)m * F + f) = (u32x2){pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
   } else {
     const int n = g * 4;
     if (n >= V) return;
@@ -305,7 +344,7 @@ SplitPlan split_plan(int M, int K, int V) {
   return best;
 }
 
-template <bool ROPE>
+template <bool ROPE, bool GLU>
 hipError_t launch_splitk(int M, int K, int V, SplitPlan plan, const void *hidden, const void *weight, const QkvArgs &qa,
                          const StoreArgs &sa, float *part, hipStream_t s) {
   const int ks = plan.ks, tm = 64 * plan.mt;
@@ -330,9 +369,9 @@ hipError_t launch_splitk(int M, int K, int V, SplitPlan plan, const void *hidden
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const long groups = ROPE ? (long)(V / kHeadDim) * 16 : (V + 3) / 4;
+  const long groups = ROPE ? (long)(V / kHeadDim) * 16 : GLU ? (V / 2 + 3) / 4 : (V + 3) / 4;
   const long threads = groups * m_pad;
-  proj_reduce_kernel<ROPE><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(M, V, ks, v_pad, m_pad, part, qa, sa);
+  proj_reduce_kernel<ROPE, GLU><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(M, V, ks, v_pad, m_pad, part, qa, sa);
   return hipGetLastError();
 }
 
@@ -341,7 +380,7 @@ hipError_t launch_splitk(int M, int K, int V, SplitPlan plan, const void *hidden
 // the LM head's measured 2100 clocks at MT = 3); one workgroup per CU at a time, so the launch
 // takes ceil(units / 256) rounds of that.  960 x 4608: MT = 2 (144 units, one round) beats MT = 1
 // (270 units: a second round for 14 of them) and MT = 3 (90 units).
-template <bool ROPE>
+template <bool ROPE, bool GLU>
 hipError_t dispatch(int M, int K, int V, const void *hidden, const void *weight, const QkvArgs &qa, const StoreArgs &sa,
                     hipStream_t s) {
   const int v_tiles = (V + TV - 1) / TV;
@@ -353,10 +392,10 @@ hipError_t dispatch(int M, int K, int V, const void *hidden, const void *weight,
     if (cost < best - 1e-9) { best = cost; mt = t; }
   }
   switch (mt) {
-    case 4: return launch<4, ROPE>(M, K, V, hidden, weight, qa, sa, s);
-    case 3: return launch<3, ROPE>(M, K, V, hidden, weight, qa, sa, s);
-    case 2: return launch<2, ROPE>(M, K, V, hidden, weight, qa, sa, s);
-    default: return launch<1, ROPE>(M, K, V, hidden, weight, qa, sa, s);
+    case 4: return launch<4, ROPE, GLU>(M, K, V, hidden, weight, qa, sa, s);
+    case 3: return launch<3, ROPE, GLU>(M, K, V, hidden, weight, qa, sa, s);
+    case 2: return launch<2, ROPE, GLU>(M, K, V, hidden, weight, qa, sa, s);
+    default: return launch<1, ROPE, GLU>(M, K, V, hidden, weight, qa, sa, s);
   }
 }
 
@@ -403,6 +442,66 @@ __global__ __launch_bounds__(256) void rope_table_kernel(int T, int half, double
   sin_out[idx] = (float)sv;
 }
 
+// out[t, :] = x[t, :] / sqrt(mean(x[t, :]^2) + eps) * weight: one workgroup per row, the row is
+// read once (16-byte loads, K % 8 == 0) and kept in registers between the two passes when it
+// fits (K <= 8192), otherwise read again
+__global__ __launch_bounds__(256) void rmsnorm_kernel(int K, const bf16_t *__restrict__ x,
+                                                      const bf16_t *__restrict__ weight, float eps,
+                                                      bf16_t *__restrict__ out) {
+  __shared__ float red[4];
+  constexpr int kKeep = 4;  // 16-byte pieces a thread keeps: 4 * 256 * 8 = 8192 values
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const int pieces = K / 8;
+  const u32x4 *row = (const u32x4 *)(x + (size_t)t * K);
+  const u32x4 *wv = (const u32x4 *)weight;
+  u32x4 *dst = (u32x4 *)(out + (size_t)t * K);
+  u32x4 keep[kKeep];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < kKeep; ++i) {
+    const int p = tid + i * 256;
+    keep[i] = row[p < pieces ? p : pieces - 1];
+  }
+#pragma unroll
+  for (int i = 0; i < kKeep; ++i) {
+    if (tid + i * 256 < pieces) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a = __uint_as_float(keep[i][e] << 16), b = __uint_as_float(keep[i][e] & 0xffff0000u);
+        ss += a * a + b * b;
+      }
+    }
+  }
+  for (int p = tid + kKeep * 256; p < pieces; p += 256) {
+    const u32x4 v = row[p];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a = __uint_as_float(v[e] << 16), b = __uint_as_float(v[e] & 0xffff0000u);
+      ss += a * a + b * b;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  const float scale = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)K + eps);
+  auto emit = [&](int p, u32x4 v) {
+    const u32x4 w = wv[p];
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a = __uint_as_float(v[e] << 16) * scale * __uint_as_float(w[e] << 16);
+      const float b = __uint_as_float(v[e] & 0xffff0000u) * scale * __uint_as_float(w[e] & 0xffff0000u);
+      o[e] = pack_bf16(a, b);
+    }
+    dst[p] = o;
+  };
+#pragma unroll
+  for (int i = 0; i < kKeep; ++i)
+    if (tid + i * 256 < pieces) emit(tid + i * 256, keep[i]);
+  for (int p = tid + kKeep * 256; p < pieces; p += 256) emit(p, row[p]);
+}
+
 }  // namespace
 
 bool proj_mfma_supports(int32_t M, int32_t K, int32_t N) { return M >= 1 && K >= BK && K % BK == 0 && N >= 4 && N % 4 == 0; }
@@ -422,8 +521,8 @@ hipError_t launch_qkv_rope(int32_t M, int32_t K, int32_t Hq, int32_t Hkv, const 
   StoreArgs sa = {nullptr, nullptr};
   const int V = (Hq + 2 * Hkv) * kHeadDim;
   const SplitPlan plan = part ? split_plan(M, K, V) : SplitPlan{1, 1};
-  if (plan.ks > 1) return launch_splitk<true>(M, K, V, plan, hidden, w_qkv, qa, sa, part, s);
-  return dispatch<true>(M, K, V, hidden, w_qkv, qa, sa, s);
+  if (plan.ks > 1) return launch_splitk<true, false>(M, K, V, plan, hidden, w_qkv, qa, sa, part, s);
+  return dispatch<true, false>(M, K, V, hidden, w_qkv, qa, sa, s);
 }
 
 hipError_t launch_linear(int32_t M, int32_t K, int32_t N, const void *x, const void *w, const void *residual, void *out,
@@ -431,8 +530,22 @@ hipError_t launch_linear(int32_t M, int32_t K, int32_t N, const void *x, const v
   QkvArgs qa = {};
   StoreArgs sa = {(const bf16_t *)residual, (bf16_t *)out};
   const SplitPlan plan = part ? split_plan(M, K, N) : SplitPlan{1, 1};
-  if (plan.ks > 1) return launch_splitk<false>(M, K, N, plan, x, w, qa, sa, part, s);
-  return dispatch<false>(M, K, N, x, w, qa, sa, s);
+  if (plan.ks > 1) return launch_splitk<false, false>(M, K, N, plan, x, w, qa, sa, part, s);
+  return dispatch<false, false>(M, K, N, x, w, qa, sa, s);
+}
+
+hipError_t launch_swiglu(int32_t M, int32_t K, int32_t F, const void *x, const void *w_gate_up, void *out, float *part,
+                         hipStream_t s) {
+  QkvArgs qa = {};
+  StoreArgs sa = {nullptr, (bf16_t *)out};
+  const SplitPlan plan = part ? split_plan(M, K, 2 * F) : SplitPlan{1, 1};
+  if (plan.ks > 1) return launch_splitk<false, true>(M, K, 2 * F, plan, x, w_gate_up, qa, sa, part, s);
+  return dispatch<false, true>(M, K, 2 * F, x, w_gate_up, qa, sa, s);
+}
+
+hipError_t launch_rmsnorm(int32_t T, int32_t K, const void *x, const void *weight, float eps, void *out, hipStream_t s) {
+  rmsnorm_kernel<<<T, 256, 0, s>>>(K, (const bf16_t *)x, (const bf16_t *)weight, eps, (bf16_t *)out);
+  return hipGetLastError();
 }
 
 hipError_t launch_tree_positions(int32_t B, int32_t max_nodes, int32_t total_nodes, const int32_t *node_offset,

@@ -125,6 +125,12 @@ int main(void) {
         /* at most 256 workgroups, each with a 256 x 128 tile of fp32 partials */
         CHECK(ws % 4 == 0 && ws <= (size_t)256 * 256 * 128 * 4);
       }
+  CHECK(hb_rmsnorm(4, 3580, p, p, 1e-6f, p, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_rmsnorm(4, 3584, p, p, -1.f, p, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_rmsnorm(0, 3584, NULL, NULL, 1e-6f, NULL, NULL) == HB_OK);
+  CHECK(hb_swiglu_project(4, 3584, 18942, p, p, p, NULL, 0, NULL) == HB_ERR_UNSUPPORTED);
+  CHECK(hb_swiglu_project(4, 3584, 18944, p, NULL, p, NULL, 0, NULL) == HB_ERR_INVALID_ARG);
+  CHECK(hb_swiglu_project(0, 3584, 18944, NULL, NULL, NULL, NULL, 0, NULL) == HB_OK);
   CHECK(hb_topk_logprob(HB_F32, 4, 100, 0, p, p, (float *)p, p, 1 << 20, NULL) == HB_ERR_INVALID_ARG);
   CHECK(hb_topk_logprob(HB_F32, 4, 100, 33, p, p, (float *)p, p, 1 << 20, NULL) == HB_ERR_UNSUPPORTED);
   CHECK(hb_topk_logprob(HB_F32, 4, 100, 5, p, p, (float *)p, p, 8, NULL) == HB_ERR_WORKSPACE);

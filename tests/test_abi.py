@@ -169,3 +169,18 @@ def test_meta_query_argument_errors():
     assert hb.hb_meta_query_attn_workspace_bytes(4, 3584, 56, 3) == 0
     assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, None, p, None, p, need - 1, None) == 3
     assert L.hb_meta_query_attn(4, 28, 3584, 28, 3, p, p, p, None, p, None, None, need, None) == 3
+
+
+def test_layer_rest_argument_errors():
+    L, p = hb.lib, C.c_void_p(0x1000)
+    assert L.hb_rmsnorm(4, 3584, p, p, 1e-6, None, None) == 1
+    assert L.hb_rmsnorm(4, 3580, p, p, 1e-6, p, None) == 2            # K % 8
+    assert L.hb_rmsnorm(4, 3584, p, p, -1.0, p, None) == 1            # eps < 0
+    assert L.hb_rmsnorm(4, 3584, p, p, float("nan"), p, None) == 1
+    assert L.hb_rmsnorm(4, 3584, C.c_void_p(0x1004), p, 1e-6, p, None) == 1
+    assert L.hb_rmsnorm(0, 3584, None, None, 1e-6, None, None) == 0
+    assert L.hb_swiglu_project(4, 3584, 18944, p, p, None, None, 0, None) == 1
+    assert L.hb_swiglu_project(4, 3580, 18944, p, p, p, None, 0, None) == 2   # K % 64
+    assert L.hb_swiglu_project(4, 3584, 18942, p, p, p, None, 0, None) == 2   # F % 4
+    assert L.hb_swiglu_project(-1, 3584, 18944, p, p, p, None, 0, None) == 1
+    assert L.hb_swiglu_project(0, 3584, 18944, None, None, None, None, 0, None) == 0

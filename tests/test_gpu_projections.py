@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import workloads as W
-from oracle import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref
+from oracle import tree_positions_ref, rope_ref, qkv_rope_project_ref, linear_ref, rmsnorm_ref, swiglu_ref
 
 pytestmark = pytest.mark.gpu
 
@@ -124,6 +124,43 @@ def _out_case(hb, T, K, N, res, with_workspace):
         hb.hb_out_project(x.cuda(), w.cuda(), None if r is None else r.cuda(), out)
     torch.cuda.synchronize()
     _close(out, linear_ref(W.widen(x), W.widen(w), None if r is None else W.widen(r)), "out")
+
+
+@pytest.mark.parametrize("T,K,eps", [(960, 3584, 1e-6), (128, 3584, 1e-6), (1, 8, 0.0), (7, 8200, 1e-5), (33, 72, 1e-2),
+                                     (5, 16384, 1e-6)])
+def test_rmsnorm(hb, T, K, eps):
+    """Rows that fit the registers a thread keeps (K <= 8192), longer ones, the shortest."""
+    g = torch.Generator().manual_seed(T + K)
+    x = (torch.randn((T, K), generator=g) * 3.0 + 0.5).to(torch.bfloat16)
+    w = (1.0 + 0.3 * torch.randn(K, generator=g)).to(torch.bfloat16)
+    out = torch.full((T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    hb.hb_rmsnorm(x.cuda(), w.cuda(), eps, out)
+    torch.cuda.synchronize()
+    _close(out, rmsnorm_ref(W.widen(x), W.widen(w), eps), "rmsnorm")
+    xin = x.cuda()
+    hb.hb_rmsnorm(xin, w.cuda(), eps, xin)   # in place
+    torch.cuda.synchronize()
+    assert torch.equal(xin, out)
+
+
+@pytest.mark.parametrize("T,K,F,ws", [(960, 3584, 18944, False), (128, 3584, 18944, True), (128, 3584, 18944, False),
+                                      (77, 128, 132, True), (300, 320, 100, False), (1, 64, 4, True),
+                                      (513, 192, 520, True), (40, 1024, 260, True), (288, 2048, 1000, True)])
+def test_gated_silu_projection(hb, T, K, F, ws):
+    """Gate and up projection in one pass with silu(gate) * up in the epilogue: the feed-forward
+    width of the target model's shape for trees (960 tokens) and chains (128 tokens, split over K),
+    ragged feature counts (the last tile holds fewer than 128 features), a single token."""
+    g = torch.Generator().manual_seed(T * 3 + K + F)
+    x = torch.randn((T, K), generator=g).to(torch.bfloat16)
+    w = (torch.randn((2 * F, K), generator=g) * (1.5 / np.sqrt(K))).to(torch.bfloat16)
+    out = torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda")
+    wsp = None
+    if ws:
+        nbytes = hb.hb_proj_workspace_bytes(T, K, 2 * F)
+        wsp = torch.full((max(nbytes, 16),), 0xFF, dtype=torch.uint8, device="cuda")
+    hb.hb_swiglu_project(x.cuda(), w.cuda(), out, wsp)
+    torch.cuda.synchronize()
+    _close(out, swiglu_ref(W.widen(x), W.widen(w)), "swiglu")
 
 
 @pytest.mark.parametrize("scale_down,K,tree", [(16, 512, "tree"), (1, 3584, "tree"), (1, 3584, "chain8")])
