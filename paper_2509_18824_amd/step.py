@@ -247,15 +247,18 @@ class VerifyStep:
 
 
 class VerifyLayerStack:
-    """Buffers and call chain of one verification step through ``n_layers`` decoder layers reduced
-    to their attention half (QKV projection + rotary embedding -> tree-verify attention over that
-    layer's KV pools -> output projection with residual), then LM head with argmax, acceptance,
-    and the append of the accepted nodes' K/V to every layer's pools.  ``run`` only enqueues
-    kernels on the current stream (no allocation, no host synchronisation), so a step can be
-    captured into a HIP graph once and replayed."""
+    """Buffers and call chain of one verification step through ``n_layers`` decoder layers, then
+    LM head with argmax, acceptance, and the append of the accepted nodes' K/V to every layer's
+    pools.  Without ``mlp`` a layer is its attention half (QKV projection + rotary embedding ->
+    tree-verify attention over that layer's KV pools -> output projection with residual).  With
+    ``mlp = dict(norm1=[..], norm2=[..], w_gate_up=[..], w_down=[..], norm_f=.., eps=..)`` it is the
+    whole pre-norm layer: RMSNorm in front of the attention half, then RMSNorm -> gated-SiLU
+    projection -> down projection with residual, and a final RMSNorm in front of the LM head.
+    ``run`` only enqueues kernels on the current stream (no allocation, no host synchronisation),
+    so a step can be captured into a HIP graph once and replayed."""
 
     def __init__(self, desc: hb.AttnDesc, dev: DeviceInputs, pools, w_qkv, w_o, lm_weight, draft_ids, max_path: int,
-                 hidden0: torch.Tensor, theta: float = 1e6):
+                 hidden0: torch.Tensor, theta: float = 1e6, mlp=None):
         self.desc, self.dev, self.pools, self.w_qkv, self.w_o = desc, dev, pools, w_qkv, w_o
         self.lm_weight, self.draft_ids, self.max_path, self.theta = lm_weight, draft_ids, max_path, theta
         d = hidden0.device
@@ -264,6 +267,7 @@ class VerifyLayerStack:
         B = desc.batch
         self.n_layers = len(pools)
         self.hidden = [hidden0] + [torch.empty_like(hidden0) for _ in range(2)]  # input, ping, pong
+        self.mlp = mlp
         self.positions = torch.empty(T, dtype=torch.int32, device=d)
         self.cos = torch.empty((T, D // 2), dtype=torch.float32, device=d)
         self.sin = torch.empty_like(self.cos)
@@ -275,6 +279,12 @@ class VerifyLayerStack:
         self.ws_lm = alloc_workspace(max(8, hb.hb_lmhead_argmax_workspace_bytes(T)), d)
         K = hidden0.shape[1]
         proj_bytes = max(hb.hb_proj_workspace_bytes(T, K, w_qkv[0].shape[0]), hb.hb_proj_workspace_bytes(T, K, w_o[0].shape[0]))
+        if mlp is not None:
+            F = mlp["w_down"][0].shape[1]
+            proj_bytes = max(proj_bytes, hb.hb_proj_workspace_bytes(T, K, 2 * F), hb.hb_proj_workspace_bytes(T, F, K))
+            self.normed = torch.empty_like(hidden0)
+            self.mid = torch.empty_like(hidden0)      # the layer's hidden state between its two halves
+            self.act = torch.empty((T, F), dtype=hidden0.dtype, device=d)
         self.ws_proj = alloc_workspace(proj_bytes, d) if proj_bytes else None  # small token counts: split-K partials
         self.target_ids = torch.empty(T, dtype=torch.int32, device=d)
         self.accept_len = torch.empty(B, dtype=torch.int32, device=d)
@@ -298,18 +308,36 @@ class VerifyLayerStack:
                              self.positions)
         hb.hb_rope_table(self.q.shape[2], self.theta, self.positions, self.cos, self.sin)
         x = self.hidden[0]
+        mlp = self.mlp
         for l in range(self.n_layers):
-            y = self.hidden[1 + (l & 1)]
+            nxt = self.hidden[1 + (l & 1)]
+            y = nxt if mlp is None else self.mid
             kp, vp = self.pools[l]
+            a = x
+            if mlp is not None:
+                mark("rmsnorm")
+                hb.hb_rmsnorm(x, mlp["norm1"][l], mlp["eps"], self.normed)
+                a = self.normed
             mark("qkv_rope_project")
-            hb.hb_qkv_rope_project_ws(x, self.w_qkv[l], None, self.cos, self.sin, self.q, self.k_tree[l],
+            hb.hb_qkv_rope_project_ws(a, self.w_qkv[l], None, self.cos, self.sin, self.q, self.k_tree[l],
                                       self.v_tree[l], self.ws_proj)
             mark("tree_verify_attn")
             hb.hb_tree_verify_attn(desc, self.q, self.k_tree[l], self.v_tree[l], kp, vp, dev.block_table,
                                    dev.prefix_len, dev.node_offset, dev.parent, self.attn_out, None, self.ws_attn)
             mark("out_project")
             hb.hb_out_project_ws(self.attn_out.view(T, -1), self.w_o[l], x, y, self.ws_proj)
-            x = y
+            if mlp is not None:
+                mark("rmsnorm")
+                hb.hb_rmsnorm(y, mlp["norm2"][l], mlp["eps"], self.normed)
+                mark("swiglu_project")
+                hb.hb_swiglu_project(self.normed, mlp["w_gate_up"][l], self.act, self.ws_proj)
+                mark("down_project")
+                hb.hb_out_project_ws(self.act, mlp["w_down"][l], y, nxt, self.ws_proj)
+            x = nxt
+        if mlp is not None and mlp.get("norm_f") is not None:
+            mark("rmsnorm")
+            hb.hb_rmsnorm(x, mlp["norm_f"], mlp["eps"], self.normed)
+            x = self.normed
         self.final_hidden = x
         mark("lmhead_argmax")
         hb.hb_lmhead_argmax(x, self.lm_weight, self.target_ids, None, self.ws_lm)

@@ -241,10 +241,62 @@ def test_full_step_replays_from_a_hip_graph(S):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
 
 
+def _mlp_weights(mk, n_layers, K, F):
+    return dict(norm1=[mk(K, std=0.2) + 1 for _ in range(n_layers)], norm2=[mk(K, std=0.2) + 1 for _ in range(n_layers)],
+                w_gate_up=[mk(2 * F, K, std=K ** -0.5) for _ in range(n_layers)],
+                w_down=[mk(K, F, std=0.3 * F ** -0.5) for _ in range(n_layers)], norm_f=mk(K, std=0.2) + 1, eps=1e-6)
+
+
 @pytest.mark.parametrize("tree", ["tree", "chain8"])
-def test_layer_stack_replays_from_a_hip_graph(S, tree):
+def test_whole_decoder_layers_against_the_oracle(S, tree):
+    """Two whole pre-norm layers (RMSNorm, QKV projection + rotary embedding, attention, output
+    projection with residual, RMSNorm, gated-SiLU projection, down projection with residual) and
+    the final RMSNorm, against the float64 oracle chained the same way and rounded to bf16 where
+    the kernels hand a bf16 tensor on."""
+    from oracle import (tree_positions_ref, qkv_rope_project_ref, tree_attn_ref, linear_ref, rmsnorm_ref, swiglu_ref)
+    from oracle.toy_decoder import round_bf16
+    inp = W.make_config(4, scale_down=8, tree=tree)
+    n_layers, F = 2, 1024
+    T, Hq, Hkv, D = inp.total_nodes, inp.Hq, inp.Hkv, inp.D
+    K = Hq * D
+    dev = S.to_device(inp)
+    desc = S.desc_for(inp)
+    g = torch.Generator(device="cuda").manual_seed(17)
+    mk = lambda *shape, std: (torch.randn(shape, generator=g, device="cuda") * std).to(torch.bfloat16)
+    w_qkv = [mk((Hq + 2 * Hkv) * D, K, std=K ** -0.5) for _ in range(n_layers)]
+    w_o = [mk(K, K, std=0.3 * K ** -0.5) for _ in range(n_layers)]
+    mlp = _mlp_weights(mk, n_layers, K, F)
+    lm = mk(4096, K, std=0.02)
+    hidden0 = mk(T, K, std=1.0)
+    pools = [(dev.k_pool, dev.v_pool), (dev.k_pool.clone(), dev.v_pool.clone())]
+    draft = torch.zeros(T, dtype=torch.int32, device="cuda")
+    stack = S.VerifyLayerStack(desc, dev, pools, w_qkv, w_o, lm, draft, inp.max_path, hidden0, mlp=mlp)
+    stack.run(compact=False)
+    torch.cuda.synchronize()
+    wd = W.widen
+    pos = tree_positions_ref(inp.node_offset.numpy(), inp.parent.numpy(), inp.prefix_len.numpy())
+    x = wd(hidden0.cpu())
+    for l in range(n_layers):
+        a = round_bf16(rmsnorm_ref(x, wd(mlp["norm1"][l].cpu()), 1e-6))
+        q, k, v = (round_bf16(t) for t in qkv_rope_project_ref(a, wd(w_qkv[l].cpu()), None, pos, Hq, Hkv, D, 1e6))
+        attn, _ = tree_attn_ref(q, k, v, wd(pools[l][0].cpu()), wd(pools[l][1].cpu()), inp.block_table.numpy(),
+                                inp.prefix_len.numpy(), inp.node_offset.numpy(), inp.parent.numpy(), inp.softmax_scale)
+        y = round_bf16(linear_ref(round_bf16(attn).reshape(T, -1), wd(w_o[l].cpu()), x))
+        m = round_bf16(rmsnorm_ref(y, wd(mlp["norm2"][l].cpu()), 1e-6))
+        act = round_bf16(swiglu_ref(m, wd(mlp["w_gate_up"][l].cpu())))
+        x = round_bf16(linear_ref(act, wd(mlp["w_down"][l].cpu()), y))
+    ref = rmsnorm_ref(x, wd(mlp["norm_f"].cpu()), 1e-6)
+    got = wd(stack.final_hidden.cpu())
+    rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert rel <= 1e-2, rel                      # two layers of bf16 hand-overs
+    assert np.abs(got - ref).max() <= 0.1 * (1 + np.abs(ref).max())
+
+
+@pytest.mark.parametrize("tree,whole", [("tree", False), ("chain8", False), ("tree", True), ("chain8", True)])
+def test_layer_stack_replays_from_a_hip_graph(S, tree, whole):
     """Three decoder layers (QKV projection + rotary embedding, attention over each layer's own
-    pools, output projection; with 8-node chains the projections take the split-K path), LM head,
+    pools, output projection; with 8-node chains the projections take the split-K path; with
+    ``whole`` also the normalisations and the feed-forward block), LM head,
     acceptance and the compaction of all layers in one launch, captured once and replayed with
     eager steps in between on changing draft ids: every replay equals the eager step, bit for bit,
     pools of every layer included."""
@@ -263,7 +315,8 @@ def test_layer_stack_replays_from_a_hip_graph(S, tree):
     pools = [(dev.k_pool, dev.v_pool)] + [(dev.k_pool.clone(), dev.v_pool.clone()) for _ in range(n_layers - 1)]
     pristine = [(k.clone(), v.clone()) for k, v in pools]
     draft = torch.zeros(T, dtype=torch.int32, device="cuda")
-    stack = S.VerifyLayerStack(desc, dev, pools, w_qkv, w_o, lm, draft, inp.max_path, hidden0)
+    mlp = _mlp_weights(mk, n_layers, K, 1536) if whole else None
+    stack = S.VerifyLayerStack(desc, dev, pools, w_qkv, w_o, lm, draft, inp.max_path, hidden0, mlp=mlp)
     assert (stack.ws_proj is not None) == (T <= 512)
     stack.run(compact=False)
     torch.cuda.synchronize()
