@@ -196,16 +196,17 @@ int32_t hb_out_project(int32_t T, int32_t K, int32_t N, const void *x, const voi
 /*
  * The same two projections for small token counts (chain drafts, the draft model's batches), the
  * setting of the paper's own measurements (Section 4.2: chain decoding).  With a few hundred tokens
- * or fewer a projection is a stream of its weight matrix from HBM, and one workgroup per 256-row
- * weight tile and tile of tokens leaves most of the chip idle; given a workspace these calls cut
- * K into parts, one workgroup per (weight tile, K part, tile of tokens), keep the parts' fp32
+ * or fewer (and with up to a thousand when K is long) a projection is a stream of its weight
+ * matrix from HBM, and one workgroup per 256-row weight tile and tile of tokens leaves most of
+ * the chip idle; given a workspace these calls cut K into parts, one workgroup per (weight tile, K part, tile of tokens), keep the parts' fp32
  * partial results in the workspace and finish (sum in fixed order, bias, rotary embedding,
  * residual) in a second kernel.  Results are deterministic; they differ from the calls above in
  * fp32 summation order only.
  *   workspace   device, hb_proj_workspace_bytes(T, K, N) bytes (N = (Hq + 2 Hkv) * 128 for the
  *               QKV projection), 16-byte aligned.  That size is 0 when the split does not apply
- *               (T > 512, or K too short to cut); with a NULL, short or misaligned workspace
- *               the calls behave exactly as the ones above.
+ *               (more than 1024 tokens, K too short to cut, or more than 512 tokens and no gain
+ *               expected: the split pays there for long K only); with a NULL, short or misaligned
+ *               workspace the calls behave exactly as the ones above.
  * Errors as above.
  */
 size_t hb_proj_workspace_bytes(int32_t T, int32_t K, int32_t N);

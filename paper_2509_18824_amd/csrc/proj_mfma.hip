@@ -312,13 +312,33 @@ __global__ __launch_bounds__(256) void proj_reduce_kernel(int M, int V, int ks, 
   }
 }
 
-// The split for at most kSplitMaxM tokens: hidden tile height (64 mt rows) and K parts (a divisor
-// of the K steps, at least kMinSteps steps per part, all workgroups resident at once), by a cost
-// model fitted to measurements on weights too many to stay in the last-level cache (microseconds):
-//   split:  6 + steps / ks * (0.70 | 0.86 for mt = 1 | 2) + partial bytes written and read / 4 TB/s
-//   plain:  3 + steps * 0.75 per round of 256 workgroups
-// ks = 1 means: do not split.
-constexpr int kSplitMaxM = 512;
+// Hidden tile height (64 mt rows) of the unsplit kernel by a small cost model: a workgroup's time
+// per K step is about 1 + 0.55 mt units (staging of the 256-row weight tile + mt x the matrix work
+// of 64 rows, from the LM head's measured 2100 clocks at mt = 3); one workgroup per CU at a time,
+// so the launch takes ceil(units / 256) rounds of that.  960 x 4608: mt = 2 (144 units, one round)
+// beats mt = 1 (270 units: a second round for 14 of them) and mt = 3 (90 units).
+int plain_tile_height(int M, int v_tiles) {
+  int mt = 1;
+  double best = 1e30;
+  for (int t = 1; t <= 4; ++t) {
+    const long units = (long)v_tiles * ((M + 64 * t - 1) / (64 * t));
+    const double cost = (double)((units + 255) / 256) * (1.0 + 0.55 * t);
+    if (cost < best - 1e-9) { best = cost; mt = t; }
+  }
+  return mt;
+}
+
+// The split over K: hidden tile height (64 mt rows) and K parts (a divisor of the K steps, at
+// least kMinSteps steps per part, all workgroups resident at once), by a cost model fitted to
+// measurements on weights too many to stay in the last-level cache (microseconds):
+//   split:  6 + steps / ks * (0.70 | 0.86 | 1.15 | 1.45 for mt = 1 .. 4) + partial bytes written and read / 4 TB/s
+//   plain:  3 + steps * 0.75 per round of 256 workgroups (at most 512 tokens)
+//           3 + steps * (0.72 | 0.95 | 1.15 | 1.4 for the unsplit kernel's mt) per round (more tokens)
+// Up to 512 tokens the tile is 64 or 128 rows high; from there to kSplitMaxM tokens 128 to 256 rows,
+// and the split must win by 10 % (it does for long K: the feed-forward block's down projection,
+// 960 x 18944 -> 3584, takes 145 us in 4 parts of 256-row tiles against 209 us unsplit; with K =
+// 3584 the unsplit kernel stays).  ks = 1 means: do not split.
+constexpr int kSplitMaxM = 1024;
 constexpr int kMinSteps = 4;
 struct SplitPlan {
   int ks, mt;
@@ -327,14 +347,23 @@ SplitPlan split_plan(int M, int K, int V) {
   SplitPlan best = {1, 1};
   if (M > kSplitMaxM || K % BK) return best;
   const int steps = K / BK, v_tiles = (V + TV - 1) / TV;
-  const long plain_units = (long)v_tiles * ((M + 63) / 64);
-  double best_cost = 3.0 + steps * 0.75 * (double)((plain_units + 255) / 256);
-  for (int mt = 1; mt <= 2; ++mt) {
+  const bool few = M <= 512;
+  static const double kStepSplit[5] = {0, 0.70, 0.86, 1.15, 1.45}, kStepPlain[5] = {0, 0.72, 0.95, 1.15, 1.4};
+  double best_cost;
+  if (few) {
+    const long plain_units = (long)v_tiles * ((M + 63) / 64);
+    best_cost = 3.0 + steps * 0.75 * (double)((plain_units + 255) / 256);
+  } else {
+    const int pm = plain_tile_height(M, v_tiles);
+    const long plain_units = (long)v_tiles * ((M + 64 * pm - 1) / (64 * pm));
+    best_cost = 0.9 * (3.0 + steps * kStepPlain[pm] * (double)((plain_units + 255) / 256));
+  }
+  for (int mt = few ? 1 : 2; mt <= (few ? 2 : 4); ++mt) {
     const int m_tiles = (M + 64 * mt - 1) / (64 * mt);
     for (int d = 2; d <= steps; ++d) {
       if (steps % d || steps / d < kMinSteps || (long)v_tiles * m_tiles * d > 256) continue;
       const double bytes = 8.0 * d * v_tiles * TV * m_tiles * 64 * mt;
-      const double cost = 6.0 + (double)(steps / d) * (mt == 1 ? 0.70 : 0.86) + bytes / 4e6;
+      const double cost = 6.0 + (double)(steps / d) * kStepSplit[mt] + bytes / 4e6;
       if (cost < best_cost - 1e-9) {
         best_cost = cost;
         best = {d, mt};
@@ -354,18 +383,21 @@ hipError_t launch_splitk(int M, int K, int V, SplitPlan plan, const void *hidden
   const unsigned grid = (unsigned)((units + kXcds - 1) / kXcds * kXcds * m_tiles);
   const size_t lds_bytes = (size_t)(3 * TV + 2 * tm) * CH * sizeof(u32x4);
   hipError_t e;
-  if (plan.mt == 1) {
-    auto kern = proj_splitk_kernel<1>;
-    e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    kern<<<grid, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, m_tiles, m_pad, units, (const u32x4 *)hidden,
-                                      (const u32x4 *)weight, part);
-  } else {
-    auto kern = proj_splitk_kernel<2>;
-    e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    kern<<<grid, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, m_tiles, m_pad, units, (const u32x4 *)hidden,
-                                      (const u32x4 *)weight, part);
+  switch (plan.mt) {
+#define HB_SPLITK_CASE(MT_)                                                                                       \
+  case MT_: {                                                                                                     \
+    auto kern = proj_splitk_kernel<MT_>;                                                                          \
+    e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);      \
+    if (e != hipSuccess) return e;                                                                                \
+    kern<<<grid, 512, lds_bytes, s>>>(M, K, V, ks, v_pad, m_tiles, m_pad, units, (const u32x4 *)hidden,           \
+                                      (const u32x4 *)weight, part);                                               \
+  } break;
+    HB_SPLITK_CASE(1)
+    HB_SPLITK_CASE(2)
+    HB_SPLITK_CASE(3)
+    HB_SPLITK_CASE(4)
+#undef HB_SPLITK_CASE
+    default: return hipErrorInvalidValue;
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -375,22 +407,10 @@ hipError_t launch_splitk(int M, int K, int V, SplitPlan plan, const void *hidden
   return hipGetLastError();
 }
 
-// Hidden tile height (64 MT rows) by a small cost model: a workgroup's time per K step is about
-// 1 + 0.55 MT units (staging of the 256-row weight tile + MT x the matrix work of 64 rows, from
-// the LM head's measured 2100 clocks at MT = 3); one workgroup per CU at a time, so the launch
-// takes ceil(units / 256) rounds of that.  960 x 4608: MT = 2 (144 units, one round) beats MT = 1
-// (270 units: a second round for 14 of them) and MT = 3 (90 units).
 template <bool ROPE, bool GLU>
 hipError_t dispatch(int M, int K, int V, const void *hidden, const void *weight, const QkvArgs &qa, const StoreArgs &sa,
                     hipStream_t s) {
-  const int v_tiles = (V + TV - 1) / TV;
-  int mt = 1;
-  double best = 1e30;
-  for (int t = 1; t <= 4; ++t) {
-    const long units = (long)v_tiles * ((M + 64 * t - 1) / (64 * t));
-    const double cost = (double)((units + 255) / 256) * (1.0 + 0.55 * t);
-    if (cost < best - 1e-9) { best = cost; mt = t; }
-  }
+  const int mt = plain_tile_height(M, (V + TV - 1) / TV);
   switch (mt) {
     case 4: return launch<4, ROPE, GLU>(M, K, V, hidden, weight, qa, sa, s);
     case 3: return launch<3, ROPE, GLU>(M, K, V, hidden, weight, qa, sa, s);

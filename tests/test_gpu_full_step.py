@@ -317,7 +317,7 @@ def test_layer_stack_replays_from_a_hip_graph(S, tree, whole):
     draft = torch.zeros(T, dtype=torch.int32, device="cuda")
     mlp = _mlp_weights(mk, n_layers, K, 1536) if whole else None
     stack = S.VerifyLayerStack(desc, dev, pools, w_qkv, w_o, lm, draft, inp.max_path, hidden0, mlp=mlp)
-    assert (stack.ws_proj is not None) == (T <= 512)
+    assert stack.ws_proj is not None or T > 512
     stack.run(compact=False)
     torch.cuda.synchronize()
     target = stack.target_ids.cpu().numpy()
