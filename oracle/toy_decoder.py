@@ -51,19 +51,23 @@ def round_bf16(x):
 
 
 class ToyDecoderRef:
-    def __init__(self, w, quant=None):
+    def __init__(self, w, quant=None, quant_dense=None):
         """``quant`` (optional, default identity) is applied where a decoder that keeps its
         attention inputs, attention output and LM-head input in a narrower storage type rounds
         them: to q, k, v after the rotary embedding, to the attention output, and to the
         normalised hidden state that feeds the LM head.  With ``round_bf16`` the three decoding
-        modes below describe such a bf16 decoder exactly, in float64 arithmetic."""
+        modes below describe such a bf16 decoder exactly, in float64 arithmetic.
+        ``quant_dense`` (optional, default identity) is applied where a decoder whose dense
+        layers hand narrower tensors on as well rounds: to both normalised hidden states of a
+        layer, to the hidden state after each residual addition, and to the gated activation."""
         self.w = w
         self.quant = quant if quant is not None else (lambda a: a)
+        self.qd = quant_dense if quant_dense is not None else (lambda a: a)
 
     # -- pieces shared by every decoding mode (plain per-token maths) ---------------------
     def _qkv(self, layer, x, pos):
         w = self.w
-        h = _rms_norm(x, w.norm1[layer])
+        h = self.qd(_rms_norm(x, w.norm1[layer]))
         T = x.shape[0]
         q = (h @ w.wq[layer]).reshape(T, w.Hq, w.Dh)
         k = (h @ w.wk[layer]).reshape(T, w.Hkv, w.Dh)
@@ -74,9 +78,10 @@ class ToyDecoderRef:
     def _after_attn(self, layer, x, attn):
         w = self.w
         attn = self.quant(attn)
-        x = x + attn.reshape(x.shape[0], -1) @ w.wo[layer]
-        h = _rms_norm(x, w.norm2[layer])
-        return x + (_silu(h @ w.w_gate[layer]) * (h @ w.w_up[layer])) @ w.w_down[layer]
+        qd = self.qd
+        x = qd(x + attn.reshape(x.shape[0], -1) @ w.wo[layer])
+        h = qd(_rms_norm(x, w.norm2[layer]))
+        return qd(x + qd(_silu(h @ w.w_gate[layer]) * (h @ w.w_up[layer])) @ w.w_down[layer])
 
     def _logits(self, x):
         return self.quant(_rms_norm(x, self.w.norm_f)) @ self.w.lm_head.T

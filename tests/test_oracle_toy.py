@@ -80,3 +80,27 @@ def test_bf16_rounding_hook():
     out, _ = ref.spec_decode(prompt, 10, W.random_drafter(2, w.vocab), lambda s: W.chain_tree(4),
                              np.random.default_rng(1).permutation(8))
     assert out == stream
+
+
+def test_dense_rounding_hook():
+    """With the dense layers' hand-overs rounded as well (quant_dense) and bf16-representable
+    weights, the three decoding modes still agree (the hook rounds the same quantities in every
+    mode); the default (identity) leaves the decoder as it was; the rounding is really applied
+    (the logits differ from the unrounded decoder's, slightly)."""
+    from oracle.toy_decoder import round_bf16
+    w = W.make_toy_weights(4, weights_bf16=True)
+    for a in [w.embed, w.lm_head, *w.wq, *w.w_down]:
+        assert np.array_equal(round_bf16(a), a)
+    ref = ToyDecoderRef(w, quant=round_bf16, quant_dense=round_bf16)
+    prompt = [int(t) for t in np.random.default_rng(6).integers(0, w.vocab, size=12)]
+    stream, _ = ref.greedy_ar(prompt, 10)
+    full = ref.full_forward(prompt + stream[:-1])
+    assert [int(np.argmax(full[len(prompt) - 1 + i])) for i in range(10)] == stream
+    out, _ = ref.spec_decode(prompt, 10, W.random_drafter(2, w.vocab), lambda s: W.seeded_tree(s, n_nodes=16, levels=4, root_fanout=4),
+                             np.random.default_rng(1).permutation(8))
+    assert out == stream
+    plain = ToyDecoderRef(w, quant=round_bf16)
+    l0, l1 = plain.full_forward(prompt), ref.full_forward(prompt)
+    assert np.array_equal(ToyDecoderRef(w, quant=round_bf16, quant_dense=lambda a: a).full_forward(prompt), l0)
+    d = np.abs(l0 - l1).max()
+    assert 0 < d < 2.0  # the logits spread over tens of units

@@ -380,18 +380,22 @@ class ToyWeights:
 
 
 def make_toy_weights(seed: int, d: int = 64, n_layers: int = 2, Hq: int = 4, Hkv: int = 1,
-                     Dh: int = 64, ffn: int = 256, vocab: int = 1000, lm_head_bf16: bool = False) -> ToyWeights:
+                     Dh: int = 64, ffn: int = 256, vocab: int = 1000, lm_head_bf16: bool = False,
+                     weights_bf16: bool = False) -> ToyWeights:
     """``lm_head_bf16``: the LM-head matrix holds bf16-representable values (for the toy whose
-    verification step runs in bf16)."""
+    verification step runs in bf16).  ``weights_bf16``: so do the embedding and every layer's
+    matrices (for the toy whose whole layers run in bf16); the norm gains are 1."""
     rng = np.random.default_rng(seed * 16 + 11)
+    as_bf16 = lambda m: torch.from_numpy(np.ascontiguousarray(m)).to(torch.bfloat16).to(torch.float64).numpy()
 
     def mat(i, o, gain=1.0):
         # values rounded to fp32 so that an fp32 copy of the model holds exactly the same weights
-        return (rng.standard_normal((i, o)) * gain / np.sqrt(i)).astype(np.float32).astype(np.float64)
+        m = (rng.standard_normal((i, o)) * gain / np.sqrt(i)).astype(np.float32)
+        return as_bf16(m) if weights_bf16 else m.astype(np.float64)
 
     return ToyWeights(
         d=d, n_layers=n_layers, Hq=Hq, Hkv=Hkv, Dh=Dh, ffn=ffn, vocab=vocab, rope_base=10000.0,
-        embed=rng.standard_normal((vocab, d)).astype(np.float32).astype(np.float64),
+        embed=(lambda m: as_bf16(m) if weights_bf16 else m.astype(np.float64))(rng.standard_normal((vocab, d)).astype(np.float32)),
         wq=[mat(d, Hq * Dh, 2.0) for _ in range(n_layers)],
         wk=[mat(d, Hkv * Dh, 2.0) for _ in range(n_layers)],
         wv=[mat(d, Hkv * Dh) for _ in range(n_layers)],
@@ -402,6 +406,6 @@ def make_toy_weights(seed: int, d: int = 64, n_layers: int = 2, Hq: int = 4, Hkv
         norm1=[np.ones(d) for _ in range(n_layers)],
         norm2=[np.ones(d) for _ in range(n_layers)],
         norm_f=np.ones(d),
-        lm_head=(lambda m: torch.from_numpy(m).to(torch.bfloat16).to(torch.float64).numpy() if lm_head_bf16
+        lm_head=(lambda m: as_bf16(m) if (lm_head_bf16 or weights_bf16)
                  else m.astype(np.float64))((rng.standard_normal((vocab, d)) * 2.0).astype(np.float32)),
     )
