@@ -145,6 +145,52 @@ def test_greedy_losslessness_with_the_matrix_core_kernels_in_the_loop(bf16_toy, 
         assert all(l == full for l in lens[:-1])
 
 
+def _bf16_all_toy():
+    """As _bf16_toy, for the toy whose whole layers run on bf16 kernels: bf16-representable
+    weights, and the exact description rounds at every hand-over between kernels."""
+    from oracle.toy_decoder import round_bf16
+    for seed in range(200):
+        w = W.make_toy_weights(seed, d=256, n_layers=2, Hq=8, Hkv=2, Dh=128, ffn=512, vocab=4096, weights_bf16=True)
+        ref = ToyDecoderRef(w, quant=round_bf16, quant_dense=round_bf16)
+        prompt = [int(t) for t in np.random.default_rng(seed).integers(0, w.vocab, size=24)]
+        stream, margin = ref.greedy_ar(prompt, 16)
+        if margin >= 1.0:
+            return w, prompt, stream
+    raise AssertionError("no seed with a wide enough margin")
+
+
+@pytest.fixture(scope="module")
+def bf16_all_toy():
+    return _bf16_all_toy()
+
+
+@pytest.mark.parametrize("kind,topology", [("random", "tree60"), ("replay", "tree60"), ("corrupting", "chain4"),
+                                           ("replay", "chain4"), ("random", "single")])
+def test_greedy_losslessness_with_every_kernel_of_the_layer_in_the_loop(bf16_all_toy, kind, topology):
+    """The same loop with the whole decoder on the library's kernels: RMSNorm, QKV projection +
+    rotary embedding, attention, output projection with residual, RMSNorm, gated-SiLU projection,
+    down projection with residual, final RMSNorm, LM head, acceptance, compaction (only the
+    embedding lookup is torch's).  The emitted stream is the plain greedy stream of the decoder's
+    exact description (float64 arithmetic, bf16 rounding at every hand-over between kernels)."""
+    from toy_gpu import ToyDecoderGpu
+    w, prompt, stream = bf16_all_toy
+    n_new = len(stream)
+    drafter = {
+        "random": W.random_drafter(1, w.vocab),
+        "replay": W.replay_drafter(1, w.vocab, len(prompt), stream),
+        "corrupting": W.replay_drafter(1, w.vocab, len(prompt), stream, wrong_after=(0, 4)),
+    }[kind]
+    tree = {"tree60": lambda s: W.seeded_tree(s), "chain4": lambda s: W.chain_tree(4),
+            "single": lambda s: W.chain_tree(1)}[topology]
+    table = np.random.default_rng(3).permutation(16)
+    gpu = ToyDecoderGpu(w, n_blocks=16, dtype="bf16_all")
+    out, lens = gpu.spec_decode(prompt, n_new, drafter, tree, table)
+    assert out == stream
+    if kind == "replay":
+        full = 6 if topology == "tree60" else 4
+        assert all(l == full for l in lens[:-1])
+
+
 @pytest.mark.parametrize("K,T,N", [(3, 4, 12), (4, 3, 20), (1, 5, 6)])
 def test_greedy_losslessness_with_trees_built_on_the_device(bf16_toy, K, T, N):
     """Draft logits -> hb_topk_logprob -> hb_tree_grow per level -> hb_tree_finalize -> verification

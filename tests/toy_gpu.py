@@ -2,7 +2,9 @@
 
 The decoder's dense layers (embedding, RMSNorm, projections, rotary, MLP) run as ordinary
 torch fp32 ops on the device; attention, LM-head argmax, acceptance and KV compaction go
-through the C ABI.  Written independently of the oracle's decoder."""
+through the C ABI.  With dtype "bf16_all" the dense layers go through the C ABI as well
+(hb_rmsnorm, hb_rope_table + hb_qkv_rope_project, hb_out_project, hb_swiglu_project): only the
+embedding lookup is left to torch.  Written independently of the oracle's decoder."""
 import math
 
 import numpy as np
@@ -17,7 +19,8 @@ class ToyDecoderGpu:
         """dtype "bf16": q, k, v, the KV pools, the attention output and the LM head's inputs are
         bf16 (the matrix-core kernels run); everything between the library calls stays fp32."""
         self.w, self.page, self.n_blocks, self.dev = w, page, n_blocks, device
-        self.dtype = dtype
+        self.all_bf16 = dtype == "bf16_all"
+        self.dtype = dtype = "bf16" if self.all_bf16 else dtype
         self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
         f = lambda a: torch.tensor(a, dtype=torch.float32, device=device)
         self.embed = f(w.embed)
@@ -26,6 +29,13 @@ class ToyDecoderGpu:
                        for i in range(w.n_layers)]
         self.norm_f = f(w.norm_f)
         self.lm_head = f(w.lm_head).to(self.tdt).contiguous()
+        if self.all_bf16:
+            b = lambda a: f(np.ascontiguousarray(a)).to(torch.bfloat16).contiguous()
+            self.embed = b(w.embed)
+            self.norm_f = b(w.norm_f)
+            self.layers = [dict(wqkv=b(np.concatenate([w.wq[i].T, w.wk[i].T, w.wv[i].T], axis=0)), wo=b(w.wo[i].T),
+                                wgu=b(np.concatenate([w.w_gate[i].T, w.w_up[i].T], axis=0)), wd=b(w.w_down[i].T),
+                                n1=b(w.norm1[i]), n2=b(w.norm2[i])) for i in range(w.n_layers)]
         half = w.Dh // 2
         self.inv_freq = torch.tensor([w.rope_base ** (-i / half) for i in range(half)], dtype=torch.float64,
                                      device=device)
@@ -43,6 +53,16 @@ class ToyDecoderGpu:
 
     def _qkv(self, lw, x, pos):
         w = self.w
+        if self.all_bf16:
+            T = x.shape[0]
+            bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device=x.device)
+            h, q, k, v = bf(T, w.d), bf(T, w.Hq, w.Dh), bf(T, w.Hkv, w.Dh), bf(T, w.Hkv, w.Dh)
+            cos = torch.empty((T, w.Dh // 2), dtype=torch.float32, device=x.device)
+            sin = torch.empty_like(cos)
+            hb.hb_rmsnorm(x, lw["n1"], 1e-6, h)
+            hb.hb_rope_table(w.Dh, w.rope_base, pos.to(torch.int32).contiguous(), cos, sin)
+            hb.hb_qkv_rope_project(h, lw["wqkv"], None, cos, sin, q, k, v)
+            return q, k, v
         h = self._rms(x, lw["n1"])
         T = x.shape[0]
         q = self._rope((h @ lw["wq"]).view(T, w.Hq, w.Dh), pos)
@@ -51,6 +71,15 @@ class ToyDecoderGpu:
         return q.to(self.tdt).contiguous(), k.to(self.tdt).contiguous(), v.to(self.tdt).contiguous()
 
     def _mlp(self, lw, x, attn):
+        if self.all_bf16:
+            T = x.shape[0]
+            y, h, out = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+            act = torch.empty((T, self.w.ffn), dtype=torch.bfloat16, device=x.device)
+            hb.hb_out_project(attn.reshape(T, -1).contiguous(), lw["wo"], x, y)
+            hb.hb_rmsnorm(y, lw["n2"], 1e-6, h)
+            hb.hb_swiglu_project(h, lw["wgu"], act)
+            hb.hb_out_project(act, lw["wd"], y, out)
+            return out
         x = x + attn.float().reshape(x.shape[0], -1) @ lw["wo"]
         h = self._rms(x, lw["n2"])
         return x + (torch.nn.functional.silu(h @ lw["wg"]) * (h @ lw["wu"])) @ lw["wd"]
@@ -114,7 +143,11 @@ class ToyDecoderGpu:
                 attn, _ = S.tree_verify_attn(desc, d, want_lse=False)
                 tree_kv.append(d)
                 x = self._mlp(lw, x, attn)
-            hidden = self._rms(x, self.norm_f).to(self.tdt).contiguous()
+            if self.all_bf16:
+                hidden = torch.empty_like(x)
+                hb.hb_rmsnorm(x, self.norm_f, 1e-6, hidden)
+            else:
+                hidden = self._rms(x, self.norm_f).to(self.tdt).contiguous()
             target_ids, _ = S.lmhead_argmax(hidden, self.lm_head, want_max=False)
             alen, apath, otoks, _ = S.tree_accept(node_offset, parent, draft_ids, target_ids, max_path, n)
             new_len = None
