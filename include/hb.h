@@ -8,10 +8,11 @@
  * pass: attention of every tree node over the paged prefix KV cache plus its own ancestors, LM
  * head with a fused argmax, greedy longest-accepted-path selection (or sampling acceptance), and
  * the append of the accepted nodes' K/V to the cache (the paper keeps committed context in the
- * KV cache, Section 4.1).  Around it: the target's projections on both sides of the attention
- * (positions, rotary table, fused QKV projection, output projection), the construction of the
- * draft tree from the draft model's logits, and the draft model's intermediate layer
- * (aggregation of the target's layer features with meta queries, Section 3.1.1).
+ * KV cache, Section 4.1).  Around it: the rest of the target's decoder layer (positions, rotary
+ * table, fused QKV projection, output projection, normalisation, feed-forward block), the
+ * construction of the draft tree from the draft model's logits, and the draft model's
+ * intermediate layer (aggregation of the target's layer features with meta queries, Section
+ * 3.1.1).
  *
  * Conventions for every entry point
  *   - Returns an hb_status; on failure hb_last_error() gives a thread-local message.
